@@ -1,0 +1,61 @@
+"""The named workloads: table shape, quantization scheme, graph, fan-outs.
+
+Shapes follow the benchmark configurations (a tiny random graph; a
+products-scale graph with D=100; a Papers100M-shaped table, 111M x 128 with a
+3-hop fan-out; a MAG240M-shaped fp16 table, 244M x 768; a 100M x 768 table for
+the 96 x 256-entry vector-quantized form).  All data are synthetic and seeded;
+they stand in for those datasets, none of which is needed or read.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Tuple
+
+from .features import FeatureSpec
+from .graphs import PowerLawGraph, UniformGraph
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    N: int
+    D: int
+    dtype: str                  # storage dtype of the raw table
+    kind: str                   # "uniform" | "log" | "vq"
+    bits: int                   # scalar schemes: bits per value
+    graph: str                  # "uniform" | "powerlaw"
+    avg_degree: float
+    fanouts: Tuple[int, ...]    # seed side outward
+    batch: int
+    seed_mode: str = "uniform"  # "uniform" | "degree"
+    cap: int = 10_000
+    vq_width: int = 8
+    vq_length: int = 256
+    seed: int = 0
+
+    @property
+    def spec(self) -> FeatureSpec:
+        return FeatureSpec(self.N, self.D, self.seed, self.dtype)
+
+    def scaled(self, N: int, **kw) -> "Workload":
+        """Same shape of work on a smaller table (for parity tests)."""
+        return replace(self, N=N, name=f"{self.name}@{N}", **kw)
+
+
+WORKLOADS = {
+    "tiny": Workload("tiny", 10_000, 128, "f32", "uniform", 8, "uniform", 15, (10,), 1024),
+    "mid": Workload("mid", 2_400_000, 100, "f32", "uniform", 4, "powerlaw", 15, (25, 10), 1024),
+    "large": Workload("large", 111_000_000, 128, "f32", "uniform", 2, "powerlaw", 15,
+                      (15, 10, 5), 1024, seed_mode="degree"),
+    "largest1": Workload("largest1", 244_000_000, 768, "f16", "uniform", 1, "powerlaw", 12,
+                         (25, 15), 1024),
+    "largest4": Workload("largest4", 244_000_000, 768, "f16", "uniform", 4, "powerlaw", 12,
+                         (25, 15), 1024),
+    "vq": Workload("vq", 100_000_000, 768, "f32", "vq", 8, "powerlaw", 15, (25, 10), 4096),
+}
+
+
+def make_graph(w: Workload):
+    if w.graph == "uniform":
+        return UniformGraph(w.N, int(w.avg_degree), w.seed)
+    return PowerLawGraph(w.N, w.avg_degree, 2.1, w.cap, w.seed)

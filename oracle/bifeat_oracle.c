@@ -1,0 +1,424 @@
+/*
+ * BiFeat feature-loading path: the CPU oracle.
+ *
+ * TEST INFRASTRUCTURE.  A plain, slow, step-by-step implementation of what the
+ * path computes, written from the paper (BiFeat, arXiv 2207.14696) to check the
+ * GPU library against.  Only tests, the smoke check and the benchmark's CPU
+ * baseline call it; the product never does, and the two share no code.
+ *
+ * What is defined by the paper, and where:
+ *   - logarithmic scalar codes and their decoding     Sec. 3.1, Eq. (1), Eq. (2)
+ *   - 1-bit codes ("positive or not", zero with the negatives)    Sec. 3.1
+ *   - uniform scalar codes (evenly spaced levels), named in        Sec. 3.1
+ *   - vector codes: split into parts of `width` dims, one k-means codebook of
+ *     `length` entries per part, store the index      Sec. 3.2, Appendix D
+ *   - per-iteration load = rows of the sampled nodes, decoded      Sec. 3.3
+ *   - neighbourhood mean  g_i = (1/|N(i)|) sum_{j in N(i)} g_j     Appendix A.1
+ * Where the paper is silent (bit packing, the uniform scheme's exact rounding,
+ * k-means initialisation) the reading taken is stated at the function.
+ *
+ * Precision: an integer code is decided in fp32 with individually rounded
+ * operations (so a second implementation can reproduce it bit for bit);
+ * decoded values and means are computed in fp64 and rounded once to fp32.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py against
+ * closed forms, brute force, library routines or invariants.  Nothing in the
+ * paper prints a worked numeric example, so no absolute code value is pinned
+ * to a printed one.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_UNIFORM = 0, ORC_LOG = 1, ORC_VQ = 2 };
+
+/* Everything a decoder needs.  uniform: a = min[D], b = scale[D].
+ * log: a = V[2^bits] (decode table).  vq: cb = [P][len][w] codebooks. */
+typedef struct {
+    int32_t kind;
+    int32_t bits;
+    int64_t D;
+    int32_t w;
+    int32_t len;
+    const float *a;
+    const float *b;
+    const float *cb;
+} orc_scheme;
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ packing
+ * The paper does not fix a bit layout (Appendix D only advises against
+ * elaborate packing).  Layout used: row-major; column j's `bits`-bit code sits
+ * at bit offset (j*bits) mod 8 of byte floor(j*bits/8) (column 0 in the least
+ * significant bits); a row occupies ceil(D*bits/8) bytes rounded up to a
+ * multiple of 16, pad bytes zero.  Vector codes: byte p = index of part p. */
+int64_t orc_row_bytes(int64_t ncodes, int bits) {
+    int64_t nb = (ncodes * bits + 7) / 8;
+    return (nb + 15) / 16 * 16;
+}
+
+void orc_pack(const uint8_t *q, int64_t rows, int64_t ncodes, int bits, uint8_t *packed) {
+    int64_t rb = orc_row_bytes(ncodes, bits);
+    memset(packed, 0, (size_t)(rows * rb));
+    for (int64_t i = 0; i < rows; i++)
+        for (int64_t j = 0; j < ncodes; j++) {
+            int64_t bit = j * bits;
+            packed[i * rb + bit / 8] |= (uint8_t)(q[i * ncodes + j] << (bit % 8));
+        }
+}
+
+void orc_unpack(const uint8_t *packed, int64_t rows, int64_t ncodes, int bits, uint8_t *q) {
+    int64_t rb = orc_row_bytes(ncodes, bits);
+    unsigned mask = (1u << bits) - 1u;
+    for (int64_t i = 0; i < rows; i++)
+        for (int64_t j = 0; j < ncodes; j++) {
+            int64_t bit = j * bits;
+            q[i * ncodes + j] = (uint8_t)((packed[i * rb + bit / 8] >> (bit % 8)) & mask);
+        }
+}
+
+/* ------------------------------------------------------- uniform scalar codes
+ * Sec. 3.1 names uniform quantization (evenly spaced levels) without a
+ * formula.  Reading: per column j, levels min_j + q*scale_j, q = 0..L,
+ * L = 2^bits - 1, scale_j = (max_j - min_j)/L; a value maps to the nearest
+ * level (ties to the even code). */
+
+/* running per-column min/max; caller initialises mn=+inf, mx=-inf.  NaNs are
+ * skipped; a zero result is stored as +0. */
+void orc_fit_minmax(const float *x, int64_t rows, int64_t D, float *mn, float *mx) {
+    for (int64_t i = 0; i < rows; i++)
+        for (int64_t j = 0; j < D; j++) {
+            float v = x[i * D + j];
+            if (v < mn[j]) mn[j] = v;
+            if (v > mx[j]) mx[j] = v;
+        }
+    for (int64_t j = 0; j < D; j++) {
+        if (mn[j] == 0.0f) mn[j] = 0.0f;
+        if (mx[j] == 0.0f) mx[j] = 0.0f;
+    }
+}
+
+/* scale_j and its reciprocal, from fp64 arithmetic rounded once to fp32;
+ * a constant column gets scale = inv = 0 (every value encodes to code 0 and
+ * decodes to min exactly). */
+void orc_uniform_params(const float *mn, const float *mx, int64_t D, int bits,
+                        float *scale, float *inv) {
+    double L = (double)((1u << bits) - 1u);
+    for (int64_t j = 0; j < D; j++) {
+        double range = (double)mx[j] - (double)mn[j];
+        if (range > 0.0) {
+            scale[j] = (float)(range / L);
+            inv[j] = (float)(L / range);
+        } else {
+            scale[j] = 0.0f;
+            inv[j] = 0.0f;
+        }
+    }
+}
+
+/* q = clamp(round_half_even((x - min_j) * inv_j), 0, L), each operation a
+ * single fp32 rounding; NaN encodes to 0. */
+void orc_uniform_encode(const float *x, int64_t rows, int64_t D, int bits,
+                        const float *mn, const float *inv, uint8_t *q) {
+    float L = (float)((1u << bits) - 1u);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; i++)
+        for (int64_t j = 0; j < D; j++) {
+            float d = x[i * D + j] - mn[j];
+            float t = d * inv[j];
+            float r = rintf(t);
+            r = fmaxf(r, 0.0f);
+            r = fminf(r, L);
+            q[i * D + j] = (uint8_t)(int)r;
+        }
+}
+
+/* ------------------------------------------------- logarithmic scalar codes
+ * Sec. 3.1, Eq. (1): with H = 2^(k-1) and m = |x|,
+ *     level l = floor( (Clip(log2 m) - e_min) / (e_max - e_min) * H ),
+ *     Q(x) = H + l  on the positive side,  H - 1 - l  on the other side.
+ * Readings (the equation as printed leaves these open):
+ *   - l is capped at H-1 (at log2 m = e_max the printed form gives H);
+ *   - side: x > 0 is positive, x <= 0 is not (the text groups zero with the
+ *     negatives so that 0/1-valued features keep two distinct codes; the
+ *     printed case split puts x = 0 on the positive side, which would merge
+ *     0 and 1 at k = 1); NaN is treated like 0;
+ *   - e_min, e_max are global (no column subscript in the paper): log2 of the
+ *     smallest nonzero and of the largest finite |x|; a caller that clips a
+ *     tail fraction passes a narrower pair, and Clip() clamps to it.
+ * The level is decided by comparing m with the H-1 interior bin edges
+ *     T_i = exp2(e_min + i*(e_max - e_min)/H), i = 1..H-1  (fp64 -> fp32),
+ * l = #{i : m >= T_i}, which is Eq. (1) with the monotone log2 moved to the
+ * edges; orc_log_encode_direct is the printed form, for comparison.
+ * Eq. (2): Q^-1(q) = +-exp2(e_min + (l + 0.5)*(e_max - e_min)/H), minus sign on
+ * the q < H side (the printed equation omits the sign; without it the two
+ * halves of the code range would decode to the same values). */
+
+/* running min of nonzero finite |x| and max of finite |x|;
+ * caller initialises mmin=+inf, mmax=0 */
+void orc_log_fit(const float *x, int64_t n, float *mmin, float *mmax) {
+    for (int64_t i = 0; i < n; i++) {
+        float m = fabsf(x[i]);
+        if (!(m < INFINITY)) continue; /* inf, NaN */
+        if (m > 0.0f && m < *mmin) *mmin = m;
+        if (m > *mmax) *mmax = m;
+    }
+}
+
+/* e_min/e_max from the fitted magnitudes; an all-zero table gets (0, 0) */
+void orc_log_range(float mmin, float mmax, double *e_min, double *e_max) {
+    if (!(mmax > 0.0f)) {
+        *e_min = 0.0;
+        *e_max = 0.0;
+        return;
+    }
+    *e_min = log2((double)mmin);
+    *e_max = log2((double)mmax);
+}
+
+/* T[H-1] bin edges and V[2^k] decode table */
+void orc_log_tables(double e_min, double e_max, int k, float *T, float *V) {
+    int H = 1 << (k - 1);
+    double step = (e_max - e_min) / (double)H;
+    for (int i = 1; i < H; i++) T[i - 1] = (float)exp2(e_min + (double)i * step);
+    for (int l = 0; l < H; l++) {
+        float v = (float)exp2(e_min + ((double)l + 0.5) * step);
+        V[H + l] = v;
+        V[H - 1 - l] = -v;
+    }
+}
+
+void orc_log_encode(const float *x, int64_t n, int k, const float *T, uint8_t *q) {
+    int H = 1 << (k - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; i++) {
+        float v = x[i];
+        float m = fabsf(v);
+        int l = 0;
+        for (int t = 0; t < H - 1; t++)
+            if (m >= T[t]) l++;
+        q[i] = (uint8_t)((v > 0.0f) ? H + l : H - 1 - l);
+    }
+}
+
+/* Eq. (1) as printed (log2 evaluated per element, fp64), with the readings
+ * above.  Agrees with orc_log_encode except for magnitudes within rounding of
+ * a bin edge. */
+void orc_log_encode_direct(const float *x, int64_t n, int k, double e_min, double e_max,
+                           uint8_t *q) {
+    int H = 1 << (k - 1);
+    for (int64_t i = 0; i < n; i++) {
+        double v = (double)x[i];
+        double m = fabs(v);
+        int l = 0;
+        if (m > 0.0 && e_max > e_min) {
+            double e = log2(m);
+            if (e < e_min) e = e_min;
+            if (e > e_max) e = e_max;
+            l = (int)floor((e - e_min) / (e_max - e_min) * (double)H);
+            if (l > H - 1) l = H - 1;
+        } else if (m > 0.0) {
+            l = H - 1; /* e_max == e_min: every nonzero magnitude is the top edge */
+        }
+        q[i] = (uint8_t)((v > 0.0) ? H + l : H - 1 - l);
+    }
+}
+
+/* ------------------------------------------------------------- vector codes
+ * Sec. 3.2 / Appendix D: D dims are split into P = ceil(D/w) parts of w dims
+ * (a short last part is zero-padded); part p of a row is replaced by the index
+ * of its nearest entry in that part's codebook of `len` entries (Euclidean
+ * distance; len <= 256, one byte per part as the paper advises).
+ * The squared distance is accumulated in fp32, dimension ascending, multiply
+ * and add rounded separately; ties go to the lowest index. */
+static int vq_nearest(const float *sub, const float *cb, int w, int len, float *best_out) {
+    int best = 0;
+    float bestd = INFINITY;
+    for (int c = 0; c < len; c++) {
+        float dist = 0.0f;
+        for (int d = 0; d < w; d++) {
+            float diff = sub[d] - cb[c * w + d];
+            float sq = diff * diff;
+            dist = dist + sq;
+        }
+        if (dist < bestd) {
+            bestd = dist;
+            best = c;
+        }
+    }
+    if (best_out) *best_out = bestd;
+    return best;
+}
+
+static void load_part(const float *row, int64_t D, int p, int w, float *sub) {
+    for (int d = 0; d < w; d++) {
+        int64_t j = (int64_t)p * w + d;
+        sub[d] = (j < D) ? row[j] : 0.0f;
+    }
+}
+
+void orc_vq_assign(const float *x, int64_t rows, int64_t D, int w, int len, const float *cb,
+                   uint8_t *q) {
+    int P = (int)((D + w - 1) / w);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; i++) {
+        float sub[256];
+        for (int p = 0; p < P; p++) {
+            load_part(x + i * D, D, p, w, sub);
+            q[i * P + p] = (uint8_t)vq_nearest(sub, cb + (int64_t)p * len * w, w, len, NULL);
+        }
+    }
+}
+
+/* Codebook training.  The paper says k-means on a uniform row sample
+ * (Sec. 3.2, Appendix E) and nothing more.  Reading: per part, initial
+ * entries = the first `len` pairwise distinct sub-vectors of the sample in
+ * sample order (if fewer exist the rest repeat the last one and stay unused);
+ * then `iters` Lloyd rounds {assign as above; entry = fp64 mean of its members
+ * rounded to fp32; an entry without members keeps its value}.
+ * distortion[it] = mean squared distance at round it's assignment step,
+ * summed over parts (fp64). */
+void orc_vq_train(const float *sample, int64_t ns, int64_t D, int w, int len, int iters,
+                  float *cb, double *distortion) {
+    int P = (int)((D + w - 1) / w);
+    double *dpart = (double *)calloc((size_t)iters * (size_t)P, sizeof(double));
+#pragma omp parallel for schedule(dynamic)
+    for (int p = 0; p < P; p++) {
+        float *C = cb + (int64_t)p * len * w;
+        float sub[256];
+        int have = 0;
+        for (int64_t i = 0; i < ns && have < len; i++) {
+            load_part(sample + i * D, D, p, w, sub);
+            int dup = 0;
+            for (int c = 0; c < have && !dup; c++)
+                dup = (memcmp(C + c * w, sub, sizeof(float) * (size_t)w) == 0);
+            if (!dup) memcpy(C + (have++) * w, sub, sizeof(float) * (size_t)w);
+        }
+        for (int c = have; c < len; c++)
+            memcpy(C + c * w, C + (have - 1) * w, sizeof(float) * (size_t)w);
+
+        double *sum = (double *)malloc(sizeof(double) * (size_t)len * (size_t)w);
+        int64_t *cnt = (int64_t *)malloc(sizeof(int64_t) * (size_t)len);
+        for (int it = 0; it < iters; it++) {
+            memset(sum, 0, sizeof(double) * (size_t)len * (size_t)w);
+            memset(cnt, 0, sizeof(int64_t) * (size_t)len);
+            double dsum = 0.0;
+            for (int64_t i = 0; i < ns; i++) {
+                float bd;
+                load_part(sample + i * D, D, p, w, sub);
+                int c = vq_nearest(sub, C, w, len, &bd);
+                dsum += (double)bd;
+                cnt[c]++;
+                for (int d = 0; d < w; d++) sum[c * w + d] += (double)sub[d];
+            }
+            for (int c = 0; c < len; c++)
+                if (cnt[c] > 0)
+                    for (int d = 0; d < w; d++)
+                        C[c * w + d] = (float)(sum[c * w + d] / (double)cnt[c]);
+            dpart[(size_t)it * (size_t)P + (size_t)p] = dsum / (double)ns;
+        }
+        free(sum);
+        free(cnt);
+    }
+    for (int it = 0; it < iters; it++) {
+        distortion[it] = 0.0;
+        for (int p = 0; p < P; p++) distortion[it] += dpart[(size_t)it * (size_t)P + (size_t)p];
+    }
+    free(dpart);
+}
+
+/* ------------------------------------------------------------------ decoding */
+static inline unsigned code_at(const uint8_t *row, int64_t j, int bits) {
+    int64_t bit = j * bits;
+    return (row[bit / 8] >> (bit % 8)) & ((1u << bits) - 1u);
+}
+
+/* one packed row -> D decoded values (fp64) */
+static void decode_row(const orc_scheme *s, const uint8_t *row, double *out) {
+    if (s->kind == ORC_UNIFORM) {
+        for (int64_t j = 0; j < s->D; j++)
+            out[j] = (double)s->a[j] + (double)code_at(row, j, s->bits) * (double)s->b[j];
+    } else if (s->kind == ORC_LOG) {
+        for (int64_t j = 0; j < s->D; j++) out[j] = (double)s->a[code_at(row, j, s->bits)];
+    } else {
+        for (int64_t j = 0; j < s->D; j++) {
+            int64_t p = j / s->w, d = j % s->w;
+            out[j] = (double)s->cb[(p * s->len + row[p]) * s->w + d];
+        }
+    }
+}
+
+int64_t orc_scheme_row_bytes(const orc_scheme *s) {
+    if (s->kind == ORC_VQ) return orc_row_bytes((s->D + s->w - 1) / s->w, 8);
+    return orc_row_bytes(s->D, s->bits);
+}
+
+/* ---------------------------------------------------- the per-iteration load
+ * Sec. 3.3: fetch the compressed rows of the sampled nodes, decode them.    */
+void orc_gather_codes(const uint8_t *codes, int64_t rb, const int64_t *idx, int64_t M,
+                      uint8_t *out) {
+    for (int64_t i = 0; i < M; i++) memcpy(out + i * rb, codes + idx[i] * rb, (size_t)rb);
+}
+
+void orc_gather_dequant(const orc_scheme *s, const uint8_t *codes, const int64_t *idx, int64_t M,
+                        float *out) {
+    int64_t rb = orc_scheme_row_bytes(s), D = s->D;
+#pragma omp parallel
+    {
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < M; i++) {
+            decode_row(s, codes + idx[i] * rb, tmp);
+            for (int64_t j = 0; j < D; j++) out[i * D + j] = (float)tmp[j];
+        }
+        free(tmp);
+    }
+}
+
+/* Appendix A.1: out[v] = (1/|N(v)|) * sum over the listed neighbours of their
+ * decoded rows, in list order, fp64, one rounding to fp32.  The list is taken
+ * as given (repeats count with multiplicity; a self-loop is present only if
+ * the caller lists it); an empty list gives a zero row. */
+void orc_gather_mean(const orc_scheme *s, const uint8_t *codes, const int64_t *indptr,
+                     const int64_t *indices, int64_t V, float *out) {
+    int64_t rb = orc_scheme_row_bytes(s), D = s->D;
+#pragma omp parallel
+    {
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)D);
+        double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(dynamic, 64)
+        for (int64_t v = 0; v < V; v++) {
+            int64_t n = indptr[v + 1] - indptr[v];
+            for (int64_t j = 0; j < D; j++) acc[j] = 0.0;
+            for (int64_t e = indptr[v]; e < indptr[v + 1]; e++) {
+                decode_row(s, codes + indices[e] * rb, tmp);
+                for (int64_t j = 0; j < D; j++) acc[j] += tmp[j];
+            }
+            for (int64_t j = 0; j < D; j++)
+                out[v * D + j] = (n > 0) ? (float)(acc[j] / (double)n) : 0.0f;
+        }
+        free(tmp);
+        free(acc);
+    }
+}
