@@ -1,0 +1,167 @@
+/*
+ * bifeat.h - C ABI of the MI355X feature-loading library for BiFeat
+ * (graph feature quantization, arXiv 2207.14696).
+ *
+ * The library keeps a node-feature table in compressed form in GPU memory and
+ * serves minibatch iterations from it:
+ *   - one-time preprocessing (paper Sec. 3.3 "before training"): fit the
+ *     quantizer to the table, chunk by chunk, then encode + pack each chunk;
+ *   - per iteration (Sec. 3.3): gather the compressed rows of the sampled
+ *     nodes and decode them to fp32, optionally fused with the first layer's
+ *     neighbourhood mean (Appendix A.1, g_i = 1/|N(i)| sum_{j in N(i)} g_j).
+ *
+ * Conventions, all entry points
+ *   - Every data pointer documented as DEVICE points to GPU memory owned by
+ *     the caller; HOST pointers are ordinary host memory.  The library keeps no
+ *     reference to caller memory after a call returns, except that work
+ *     enqueued on `stream` reads/writes the DEVICE buffers until it completes.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return without synchronising unless stated.
+ *   - Return value: BIFEAT_OK (0) or a negative bifeat_status.  Argument
+ *     errors are detected before any GPU call is made.  bifeat_strerror()
+ *     gives a description (for BIFEAT_EHIP: the HIP error text of the last
+ *     failure on the calling thread).
+ *   - Row indices must satisfy 0 <= idx < N and indptr must be non-decreasing;
+ *     this is the caller's contract and is not checked on the GPU.
+ *   - Packed layout (the paper fixes none; Appendix D only advises against
+ *     elaborate bit packing): row-major; scalar codes: column j's `bits`-bit
+ *     code at bit (j*bits) mod 8 of byte floor(j*bits/8), column 0 in the
+ *     least significant bits; vector codes: byte p = codebook index of part p;
+ *     row stride bifeat_row_bytes() = payload rounded up to 16 bytes, pad = 0.
+ */
+#ifndef BIFEAT_H
+#define BIFEAT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BIFEAT_OK = 0,
+    BIFEAT_EINVAL = -1,  /* bad argument (null pointer, unsupported bits, size <= 0, ...) */
+    BIFEAT_ENOTFIT = -2, /* quantizer parameters not fitted / set yet */
+    BIFEAT_EHIP = -3,    /* a HIP runtime call or kernel launch failed */
+    BIFEAT_ENOTSUP = -4  /* valid request this build does not implement */
+} bifeat_status;
+
+typedef enum {
+    /* evenly spaced levels between per-column min and max - the "commonly
+     * used uniform quantization" of Sec. 3.1 */
+    BIFEAT_SQ_UNIFORM = 0,
+    /* BiFeat-SQ: sign-split uniform quantization of clipped log2|x|,
+     * Sec. 3.1 Eq. (1), decoded by Eq. (2) */
+    BIFEAT_SQ_LOG = 1,
+    /* BiFeat-VQ: per-part codebooks, Sec. 3.2 */
+    BIFEAT_VQ = 2
+} bifeat_kind;
+
+typedef enum { BIFEAT_F32 = 0, BIFEAT_F16 = 1 } bifeat_dtype;
+
+typedef struct {
+    int32_t kind;      /* bifeat_kind */
+    int32_t bits;      /* scalar kinds: 1, 2, 4 or 8 bits per value */
+    int32_t vq_width;  /* BIFEAT_VQ: dims per part (1..64); P = ceil(D/width) parts */
+    int32_t vq_length; /* BIFEAT_VQ: entries per codebook (2..256: one byte per part,
+                          the alignment Appendix D recommends) */
+} bifeat_scheme;
+
+/* Opaque quantizer state: scheme, D, fitted parameters (host + device copies).
+ * Device memory is allocated on first GPU use, on the device current then, and
+ * released by bifeat_params_destroy. */
+typedef struct bifeat_params bifeat_params;
+
+int bifeat_params_create(const bifeat_scheme *scheme, int64_t D, bifeat_params **out);
+void bifeat_params_destroy(bifeat_params *p);
+
+/* Packed bytes per row (a multiple of 16), or BIFEAT_EINVAL. */
+int64_t bifeat_row_bytes(const bifeat_params *p);
+/* Codes per row: D (scalar kinds) or the number of parts (BIFEAT_VQ). */
+int64_t bifeat_codes_per_row(const bifeat_params *p);
+
+/* ---- fitting (Sec. 3.1: e_min/e_max "of binary logarithm ... after clipping";
+ *      uniform: per-column range).  Streaming: reset, update per chunk, finalize.
+ * chunk: DEVICE, [rows x D] row-major, `dtype` elements.
+ * SQ_UNIFORM: per-column min and max over all chunks (NaNs skipped, a zero
+ *   result stored as +0); finalize derives, per column, in fp64 rounded once
+ *   to fp32: scale = (max-min)/L, inv = L/(max-min), L = 2^bits-1 (both 0 for a
+ *   constant column).  Runs entirely on `stream`.
+ * SQ_LOG: smallest nonzero and largest finite |x| over all chunks; finalize
+ *   sets e_min/e_max to their log2 and builds the tables of
+ *   bifeat_params_set_log.  finalize synchronises `stream` (the two
+ *   magnitudes come back to the host, where log2/exp2 are evaluated in fp64).
+ *   Tail clipping is not fitted here: pass a clipped pair to
+ *   bifeat_params_set_log instead.
+ * BIFEAT_VQ: BIFEAT_ENOTSUP (train codebooks elsewhere, then
+ *   bifeat_params_set_codebooks).
+ * finalize without any update returns BIFEAT_ENOTFIT. */
+int bifeat_fit_reset(bifeat_params *p, void *stream);
+int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
+                      void *stream);
+int bifeat_fit_finalize(bifeat_params *p, void *stream);
+
+/* ---- setting / reading parameters.  HOST pointers; arrays are copied.
+ * set_* uploads synchronously and marks the parameters fitted.
+ * get_* synchronises the device; any output pointer may be NULL.
+ * uniform: min[D], max[D] in; min, max, scale, inv [D] out.
+ * log:     e_min <= e_max in; out also T[2^(bits-1) - 1] (bin edges in |x|,
+ *          T_i = exp2(e_min + i*(e_max-e_min)/H), H = 2^(bits-1)) and
+ *          V[2^bits] (Eq. (2): V[H+l] = exp2(e_min + (l+.5)*(e_max-e_min)/H),
+ *          V[H-1-l] = -V[H+l]).
+ * vq:      codebooks [P][length][width] fp32. */
+int bifeat_params_set_uniform(bifeat_params *p, const float *mn, const float *mx);
+int bifeat_params_get_uniform(bifeat_params *p, float *mn, float *mx, float *scale, float *inv);
+int bifeat_params_set_log(bifeat_params *p, double e_min, double e_max);
+int bifeat_params_get_log(bifeat_params *p, double *e_min, double *e_max, float *T, float *V);
+int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks);
+int bifeat_params_get_codebooks(bifeat_params *p, float *codebooks);
+
+/* ---- encode + pack one chunk (Sec. 3.1 Eq. (1); Sec. 3.2 nearest entry).
+ * chunk: DEVICE [rows x D]; codes: DEVICE base of the packed table; rows
+ * [row0, row0+rows) of it are written (every byte of each row, padding
+ * included).
+ * SQ_UNIFORM: q = clamp(rne((x - min_j) * inv_j), 0, L), fp32, each operation
+ *   rounded separately; NaN -> 0.
+ * SQ_LOG: H = 2^(bits-1), l = #{i : |x| >= T_i}, q = H + l if x > 0 else
+ *   H - 1 - l (zero and NaN on the non-positive side, as the text of Sec. 3.1
+ *   groups them).
+ * BIFEAT_VQ: per part, index of the entry with the smallest squared Euclidean
+ *   distance (fp32, dims ascending, multiply and add rounded separately; ties
+ *   to the lowest index; a short last part is zero-padded). */
+int bifeat_quantize(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
+                    uint8_t *codes, int64_t row0, void *stream);
+
+/* ---- per-iteration load (Sec. 3.3).  codes: DEVICE packed table of N rows.
+ * gather_codes:   out[i, :] = codes[idx[i], :]              out: DEVICE [M x row_bytes]
+ * gather_dequant: out[i, j] = decode(codes[idx[i]])[j]      out: DEVICE [M x D] fp32
+ * idx: DEVICE int64 [M].  M = 0 is a no-op. */
+int bifeat_gather_codes(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *idx,
+                        int64_t M, uint8_t *out, void *stream);
+int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *idx,
+                          int64_t M, float *out, void *stream);
+
+/* ---- fused gather + decode + neighbourhood mean (Appendix A.1).
+ * For v in [0, V): out[v, :] = mean over e in [indptr[v], indptr[v+1]) of
+ * decode(codes[indices[e]]); the list is taken as given (repeats count with
+ * multiplicity; a self-loop only if listed); an empty list gives a zero row.
+ * indptr: DEVICE int64 [V+1]; indices: DEVICE int64 [indptr[V]];
+ * out: DEVICE [V x D] fp32.  fp32 result within 1e-5 * max(|exact|, A_j) of
+ * the exact mean of the decoded values, A_j the largest decodable magnitude in
+ * column j.  V = 0 is a no-op. */
+int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                       const int64_t *indices, int64_t V, float *out, void *stream);
+
+const char *bifeat_strerror(int status);
+
+/* Launch tuning for measurements (no effect on results): "mean_slots" = lanes
+ * that share one destination's neighbour list in bifeat_gather_mean (power of
+ * two, 0 = automatic), "mean_blocks" = cap on its workgroups (0 = automatic),
+ * "mean_generic" = 1 routes uniform tables through the float-accumulate
+ * kernel.  Unknown names return BIFEAT_EINVAL. */
+int bifeat_set_option(bifeat_params *p, const char *name, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BIFEAT_H */

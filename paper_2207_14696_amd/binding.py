@@ -1,0 +1,240 @@
+"""ctypes binding of the C ABI in ``include/bifeat.h``: same names, argument
+marshalling only.  Tensors are torch CUDA tensors; their ``data_ptr()`` and the
+current stream's handle are what crosses the boundary."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbifeat.so")
+
+UNIFORM, LOG, VQ = 0, 1, 2
+F32, F16 = 0, 1
+OK, EINVAL, ENOTFIT, EHIP, ENOTSUP = 0, -1, -2, -3, -4
+
+
+class BifeatError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"bifeat: {text} (status {status})")
+        self.status = status
+
+
+class _CScheme(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("bits", C.c_int32),
+                ("vq_width", C.c_int32), ("vq_length", C.c_int32)]
+
+
+@dataclass(frozen=True)
+class Scheme:
+    kind: int
+    bits: int = 8
+    vq_width: int = 0
+    vq_length: int = 0
+
+
+_lib = None
+
+_SIGNATURES = {
+    "bifeat_params_create": (C.c_int, [C.POINTER(_CScheme), C.c_int64, C.POINTER(C.c_void_p)]),
+    "bifeat_params_destroy": (None, [C.c_void_p]),
+    "bifeat_row_bytes": (C.c_int64, [C.c_void_p]),
+    "bifeat_codes_per_row": (C.c_int64, [C.c_void_p]),
+    "bifeat_fit_reset": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_fit_update": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p]),
+    "bifeat_fit_finalize": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_params_set_uniform": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "bifeat_params_get_uniform": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4),
+    "bifeat_params_set_log": (C.c_int, [C.c_void_p, C.c_double, C.c_double]),
+    "bifeat_params_get_log": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4),
+    "bifeat_params_set_codebooks": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_params_get_codebooks": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_quantize": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p,
+                                  C.c_int64, C.c_void_p]),
+    "bifeat_gather_codes": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                      C.c_void_p, C.c_void_p]),
+    "bifeat_gather_dequant": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                        C.c_void_p, C.c_void_p]),
+    "bifeat_gather_mean": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_strerror": (C.c_char_p, [C.c_int]),
+    "bifeat_set_option": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int]),
+}
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libbifeat.so (built by ``paper_2207_14696_amd.build``).  No fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with "
+                              "`python -m paper_2207_14696_amd.build`")
+        lib = C.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise BifeatError(status, load_library().bifeat_strerror(status).decode())
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev_ptr(t, dtypes=None) -> int:
+    if t is None:
+        return 0
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    if dtypes is not None and t.dtype not in dtypes:
+        raise ValueError(f"unexpected dtype {t.dtype}")
+    return t.data_ptr()
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Quantizer:
+    """Owns a ``bifeat_params`` handle.  Method names follow the C entry points
+    (``bifeat_`` prefix dropped)."""
+
+    def __init__(self, scheme: Scheme, D: int):
+        self._lib = load_library()
+        self.scheme, self.D = scheme, int(D)
+        h = C.c_void_p()
+        cs = _CScheme(scheme.kind, scheme.bits, scheme.vq_width, scheme.vq_length)
+        _check(self._lib.bifeat_params_create(C.byref(cs), self.D, C.byref(h)))
+        self._h = h
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            self._lib.bifeat_params_destroy(h)
+
+    # ---- sizes
+    @property
+    def row_bytes(self) -> int:
+        return int(self._lib.bifeat_row_bytes(self._h))
+
+    @property
+    def codes_per_row(self) -> int:
+        return int(self._lib.bifeat_codes_per_row(self._h))
+
+    def set_option(self, name: str, value: int) -> None:
+        _check(self._lib.bifeat_set_option(self._h, name.encode(), int(value)))
+
+    # ---- fit
+    @staticmethod
+    def _dtype(t) -> int:
+        import torch
+        if t.dtype == torch.float32:
+            return F32
+        if t.dtype == torch.float16:
+            return F16
+        raise ValueError("chunk must be float32 or float16")
+
+    def fit_reset(self) -> None:
+        _check(self._lib.bifeat_fit_reset(self._h, _stream()))
+
+    def fit_update(self, chunk) -> None:
+        rows = chunk.shape[0]
+        _check(self._lib.bifeat_fit_update(self._h, _dev_ptr(chunk), self._dtype(chunk), rows,
+                                           _stream()))
+
+    def fit_finalize(self) -> None:
+        _check(self._lib.bifeat_fit_finalize(self._h, _stream()))
+
+    # ---- parameters (host numpy arrays)
+    def params_set_uniform(self, mn, mx) -> None:
+        mn = np.ascontiguousarray(mn, np.float32)
+        mx = np.ascontiguousarray(mx, np.float32)
+        assert mn.shape == (self.D,) and mx.shape == (self.D,)
+        _check(self._lib.bifeat_params_set_uniform(self._h, _np_ptr(mn), _np_ptr(mx)))
+
+    def params_get_uniform(self):
+        out = [np.empty(self.D, np.float32) for _ in range(4)]
+        _check(self._lib.bifeat_params_get_uniform(self._h, *[_np_ptr(a) for a in out]))
+        return tuple(out)  # min, max, scale, inv
+
+    def params_set_log(self, e_min: float, e_max: float) -> None:
+        _check(self._lib.bifeat_params_set_log(self._h, float(e_min), float(e_max)))
+
+    def params_get_log(self):
+        k = self.scheme.bits
+        e = np.zeros(2, np.float64)
+        T = np.zeros(max((1 << (k - 1)) - 1, 1), np.float32)
+        V = np.zeros(1 << k, np.float32)
+        _check(self._lib.bifeat_params_get_log(self._h, _np_ptr(e[0:1]), _np_ptr(e[1:2]),
+                                               _np_ptr(T), _np_ptr(V)))
+        return float(e[0]), float(e[1]), T[:(1 << (k - 1)) - 1].copy(), V
+
+    def params_set_codebooks(self, cb) -> None:
+        cb = np.ascontiguousarray(cb, np.float32)
+        assert cb.shape == (self.codes_per_row, self.scheme.vq_length, self.scheme.vq_width)
+        _check(self._lib.bifeat_params_set_codebooks(self._h, _np_ptr(cb)))
+
+    def params_get_codebooks(self):
+        cb = np.empty((self.codes_per_row, self.scheme.vq_length, self.scheme.vq_width), np.float32)
+        _check(self._lib.bifeat_params_get_codebooks(self._h, _np_ptr(cb)))
+        return cb
+
+    # ---- encode
+    def quantize(self, chunk, codes, row0: int) -> None:
+        """codes: uint8 CUDA tensor [N, row_bytes]; rows [row0, row0+len(chunk)) are written."""
+        import torch
+        rows = chunk.shape[0]
+        if codes.dtype != torch.uint8 or codes.shape[1] != self.row_bytes \
+                or row0 < 0 or row0 + rows > codes.shape[0] or chunk.shape[1] != self.D:
+            raise ValueError("shape mismatch")
+        _check(self._lib.bifeat_quantize(self._h, _dev_ptr(chunk), self._dtype(chunk), rows,
+                                         _dev_ptr(codes), row0, _stream()))
+
+    # ---- per-iteration load
+    def gather_codes(self, codes, idx, out=None):
+        import torch
+        M = idx.shape[0]
+        if out is None:
+            out = torch.empty((M, self.row_bytes), dtype=torch.uint8, device=codes.device)
+        _check(self._lib.bifeat_gather_codes(self._h, _dev_ptr(codes, (torch.uint8,)),
+                                             codes.shape[0], _dev_ptr(idx, (torch.int64,)), M,
+                                             _dev_ptr(out, (torch.uint8,)), _stream()))
+        return out
+
+    def gather_dequant(self, codes, idx, out=None):
+        import torch
+        M = idx.shape[0]
+        if out is None:
+            out = torch.empty((M, self.D), dtype=torch.float32, device=codes.device)
+        elif out.shape != (M, self.D):
+            raise ValueError("out must be [M, D]")
+        _check(self._lib.bifeat_gather_dequant(self._h, _dev_ptr(codes, (torch.uint8,)),
+                                               codes.shape[0], _dev_ptr(idx, (torch.int64,)), M,
+                                               _dev_ptr(out, (torch.float32,)), _stream()))
+        return out
+
+    def gather_mean(self, codes, indptr, indices, out=None):
+        import torch
+        V = indptr.shape[0] - 1
+        if out is None:
+            out = torch.empty((V, self.D), dtype=torch.float32, device=codes.device)
+        elif out.shape != (V, self.D):
+            raise ValueError("out must be [V, D]")
+        _check(self._lib.bifeat_gather_mean(self._h, _dev_ptr(codes, (torch.uint8,)),
+                                            codes.shape[0], _dev_ptr(indptr, (torch.int64,)),
+                                            _dev_ptr(indices, (torch.int64,)), V,
+                                            _dev_ptr(out, (torch.float32,)), _stream()))
+        return out

@@ -1,0 +1,345 @@
+// C ABI of the library: argument checks, the quantizer-parameter object, and
+// dispatch to the kernels.  Everything that touches data runs in the kernels of
+// fit_quantize.hip / gather.hip / gather_mean.hip; this file only marshals.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+
+#include "common.hpp"
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char *what) {
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return BIFEAT_EHIP;
+}
+
+#define BF_HIP(call)                                  \
+    do {                                              \
+        hipError_t e_ = (call);                       \
+        if (e_ != hipSuccess) return hip_fail(e_, #call); \
+    } while (0)
+
+bool scheme_ok(const bifeat_scheme *s, int64_t D) {
+    if (!s || D <= 0 || D > (int64_t)1 << 24) return false;
+    if (s->kind == BIFEAT_SQ_UNIFORM || s->kind == BIFEAT_SQ_LOG)
+        return s->bits == 1 || s->bits == 2 || s->bits == 4 || s->bits == 8;
+    if (s->kind == BIFEAT_VQ)
+        return s->vq_width >= 1 && s->vq_width <= 64 && s->vq_length >= 2 && s->vq_length <= 256;
+    return false;
+}
+
+int64_t round16(int64_t n) { return (n + 15) / 16 * 16; }
+
+// allocate the device block on first GPU use
+int ensure_device(bifeat_params *p) {
+    if (p->d_block) return BIFEAT_OK;
+    BF_HIP(hipGetDevice(&p->device));
+    const int64_t D = p->D;
+    size_t nfloat = 0, nfit = 0;
+    if (p->scheme.kind == BIFEAT_SQ_UNIFORM) { nfloat = 4 * D; nfit = 2 * D; }
+    else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 2; }
+    else nfloat = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
+    nfloat = (nfloat + 3) / 4 * 4;
+    void *blk = nullptr;
+    BF_HIP(hipMalloc(&blk, sizeof(float) * nfloat + sizeof(int32_t) * nfit + 16));
+    p->d_block = (float *)blk;
+    if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
+        p->d_min = p->d_block;
+        p->d_scale = p->d_min + D;
+        p->d_inv = p->d_scale + D;
+        p->d_max = p->d_inv + D;
+    } else if (p->scheme.kind == BIFEAT_SQ_LOG) {
+        p->d_T = p->d_block;
+        p->d_V = p->d_block + 128;
+    } else {
+        p->d_cb = p->d_block;
+    }
+    p->d_fit = reinterpret_cast<int32_t *>(p->d_block + nfloat);
+    return BIFEAT_OK;
+}
+
+// log scheme: bin edges and decode table from (e_min, e_max), fp64 -> fp32
+void build_log_tables(bifeat_params *p) {
+    const int k = p->scheme.bits, H = 1 << (k - 1);
+    const double step = (p->e_max - p->e_min) / (double)H;
+    p->h_T.assign((size_t)(H > 1 ? H - 1 : 0), 0.f);
+    p->h_V.assign((size_t)1 << k, 0.f);
+    for (int i = 1; i < H; i++) p->h_T[i - 1] = (float)exp2(p->e_min + (double)i * step);
+    for (int l = 0; l < H; l++) {
+        float v = (float)exp2(p->e_min + ((double)l + 0.5) * step);
+        p->h_V[H + l] = v;
+        p->h_V[H - 1 - l] = -v;
+    }
+}
+
+int upload_log(bifeat_params *p) {
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    if (!p->h_T.empty())
+        BF_HIP(hipMemcpy(p->d_T, p->h_T.data(), sizeof(float) * p->h_T.size(), hipMemcpyHostToDevice));
+    BF_HIP(hipMemcpy(p->d_V, p->h_V.data(), sizeof(float) * p->h_V.size(), hipMemcpyHostToDevice));
+    return BIFEAT_OK;
+}
+
+// uniform scheme: bring the device-side fit results to the host copies
+int sync_uniform_host(bifeat_params *p) {
+    if (p->host_valid) return BIFEAT_OK;
+    const size_t D = (size_t)p->D;
+    p->h_min.resize(D); p->h_max.resize(D); p->h_scale.resize(D); p->h_inv.resize(D);
+    BF_HIP(hipDeviceSynchronize());
+    BF_HIP(hipMemcpy(p->h_min.data(), p->d_min, 4 * D, hipMemcpyDeviceToHost));
+    BF_HIP(hipMemcpy(p->h_max.data(), p->d_max, 4 * D, hipMemcpyDeviceToHost));
+    BF_HIP(hipMemcpy(p->h_scale.data(), p->d_scale, 4 * D, hipMemcpyDeviceToHost));
+    BF_HIP(hipMemcpy(p->h_inv.data(), p->d_inv, 4 * D, hipMemcpyDeviceToHost));
+    p->host_valid = true;
+    return BIFEAT_OK;
+}
+
+bool dtype_ok(int32_t d) { return d == BIFEAT_F32 || d == BIFEAT_F16; }
+
+}  // namespace
+
+extern "C" {
+
+int bifeat_params_create(const bifeat_scheme *scheme, int64_t D, bifeat_params **out) {
+    if (!out) return BIFEAT_EINVAL;
+    *out = nullptr;
+    if (!scheme_ok(scheme, D)) return BIFEAT_EINVAL;
+    bifeat_params *p = new (std::nothrow) bifeat_params();
+    if (!p) return BIFEAT_EINVAL;
+    p->scheme = *scheme;
+    p->D = D;
+    if (scheme->kind == BIFEAT_VQ) {
+        p->P = (int)((D + scheme->vq_width - 1) / scheme->vq_width);
+        p->ncodes = p->P;
+        p->rb = round16(p->P);
+        p->scheme.bits = 8;
+    } else {
+        p->ncodes = D;
+        p->rb = round16((D * scheme->bits + 7) / 8);
+    }
+    *out = p;
+    return BIFEAT_OK;
+}
+
+void bifeat_params_destroy(bifeat_params *p) {
+    if (!p) return;
+    if (p->d_block) (void)hipFree(p->d_block);
+    delete p;
+}
+
+int64_t bifeat_row_bytes(const bifeat_params *p) { return p ? p->rb : BIFEAT_EINVAL; }
+int64_t bifeat_codes_per_row(const bifeat_params *p) { return p ? p->ncodes : BIFEAT_EINVAL; }
+
+int bifeat_set_option(bifeat_params *p, const char *name, int value) {
+    if (!p || !name || value < 0) return BIFEAT_EINVAL;
+    if (!strcmp(name, "mean_slots")) p->opt_mean_slots = value;
+    else if (!strcmp(name, "mean_blocks")) p->opt_mean_blocks = value;
+    else if (!strcmp(name, "mean_generic")) p->opt_mean_generic = value;
+    else return BIFEAT_EINVAL;
+    return BIFEAT_OK;
+}
+
+int bifeat_fit_reset(bifeat_params *p, void *stream) {
+    if (!p) return BIFEAT_EINVAL;
+    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    BF_HIP(bf::launch_fit_reset(p, (hipStream_t)stream));
+    p->fit_open = true;
+    p->fit_rows = 0;
+    p->fitted = false;
+    p->host_valid = false;
+    return BIFEAT_OK;
+}
+
+int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
+                      void *stream) {
+    if (!p || !dtype_ok(dtype) || rows < 0 || (rows > 0 && !chunk)) return BIFEAT_EINVAL;
+    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
+    if (!p->fit_open) {
+        int rc = bifeat_fit_reset(p, stream);
+        if (rc) return rc;
+    }
+    if (rows == 0) return BIFEAT_OK;
+    BF_HIP(bf::launch_fit_update(p, chunk, dtype, rows, (hipStream_t)stream));
+    p->fit_rows += rows;
+    return BIFEAT_OK;
+}
+
+int bifeat_fit_finalize(bifeat_params *p, void *stream) {
+    if (!p) return BIFEAT_EINVAL;
+    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
+    if (!p->fit_open || p->fit_rows == 0) return BIFEAT_ENOTFIT;
+    if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
+        BF_HIP(bf::launch_finalize_uniform(p, (hipStream_t)stream));
+        p->host_valid = false;
+    } else {
+        uint32_t st[2];
+        BF_HIP(hipMemcpyAsync(st, p->d_fit, sizeof(st), hipMemcpyDeviceToHost, (hipStream_t)stream));
+        BF_HIP(hipStreamSynchronize((hipStream_t)stream));
+        float mmin, mmax;
+        memcpy(&mmin, &st[0], 4);
+        memcpy(&mmax, &st[1], 4);
+        if (!(mmax > 0.0f)) {  // all-zero table
+            p->e_min = p->e_max = 0.0;
+        } else {
+            p->e_min = log2((double)mmin);
+            p->e_max = log2((double)mmax);
+        }
+        build_log_tables(p);
+        int rc = upload_log(p);
+        if (rc) return rc;
+        p->host_valid = true;
+    }
+    p->fit_open = false;
+    p->fitted = true;
+    return BIFEAT_OK;
+}
+
+int bifeat_params_set_uniform(bifeat_params *p, const float *mn, const float *mx) {
+    if (!p || !mn || !mx || p->scheme.kind != BIFEAT_SQ_UNIFORM) return BIFEAT_EINVAL;
+    const size_t D = (size_t)p->D;
+    for (size_t j = 0; j < D; j++)
+        if (!(mn[j] <= mx[j])) return BIFEAT_EINVAL;
+    p->h_min.assign(mn, mn + D);
+    p->h_max.assign(mx, mx + D);
+    p->h_scale.resize(D);
+    p->h_inv.resize(D);
+    const double L = (double)((1u << p->scheme.bits) - 1u);
+    for (size_t j = 0; j < D; j++) {
+        if (p->h_min[j] == 0.0f) p->h_min[j] = 0.0f;
+        if (p->h_max[j] == 0.0f) p->h_max[j] = 0.0f;
+        const double range = (double)p->h_max[j] - (double)p->h_min[j];
+        p->h_scale[j] = range > 0.0 ? (float)(range / L) : 0.0f;
+        p->h_inv[j] = range > 0.0 ? (float)(L / range) : 0.0f;
+    }
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    BF_HIP(hipMemcpy(p->d_min, p->h_min.data(), 4 * D, hipMemcpyHostToDevice));
+    BF_HIP(hipMemcpy(p->d_max, p->h_max.data(), 4 * D, hipMemcpyHostToDevice));
+    BF_HIP(hipMemcpy(p->d_scale, p->h_scale.data(), 4 * D, hipMemcpyHostToDevice));
+    BF_HIP(hipMemcpy(p->d_inv, p->h_inv.data(), 4 * D, hipMemcpyHostToDevice));
+    p->host_valid = true;
+    p->fitted = true;
+    p->fit_open = false;
+    return BIFEAT_OK;
+}
+
+int bifeat_params_get_uniform(bifeat_params *p, float *mn, float *mx, float *scale, float *inv) {
+    if (!p || p->scheme.kind != BIFEAT_SQ_UNIFORM) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    int rc = sync_uniform_host(p);
+    if (rc) return rc;
+    const size_t n = 4 * (size_t)p->D;
+    if (mn) memcpy(mn, p->h_min.data(), n);
+    if (mx) memcpy(mx, p->h_max.data(), n);
+    if (scale) memcpy(scale, p->h_scale.data(), n);
+    if (inv) memcpy(inv, p->h_inv.data(), n);
+    return BIFEAT_OK;
+}
+
+int bifeat_params_set_log(bifeat_params *p, double e_min, double e_max) {
+    if (!p || p->scheme.kind != BIFEAT_SQ_LOG || !(e_min <= e_max) || !isfinite(e_min) ||
+        !isfinite(e_max))
+        return BIFEAT_EINVAL;
+    p->e_min = e_min;
+    p->e_max = e_max;
+    build_log_tables(p);
+    int rc = upload_log(p);
+    if (rc) return rc;
+    p->host_valid = true;
+    p->fitted = true;
+    p->fit_open = false;
+    return BIFEAT_OK;
+}
+
+int bifeat_params_get_log(bifeat_params *p, double *e_min, double *e_max, float *T, float *V) {
+    if (!p || p->scheme.kind != BIFEAT_SQ_LOG) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (e_min) *e_min = p->e_min;
+    if (e_max) *e_max = p->e_max;
+    if (T && !p->h_T.empty()) memcpy(T, p->h_T.data(), 4 * p->h_T.size());
+    if (V) memcpy(V, p->h_V.data(), 4 * p->h_V.size());
+    return BIFEAT_OK;
+}
+
+int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks) {
+    if (!p || !codebooks || p->scheme.kind != BIFEAT_VQ) return BIFEAT_EINVAL;
+    const size_t n = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
+    p->h_cb.assign(codebooks, codebooks + n);
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    BF_HIP(hipMemcpy(p->d_cb, p->h_cb.data(), 4 * n, hipMemcpyHostToDevice));
+    p->host_valid = true;
+    p->fitted = true;
+    return BIFEAT_OK;
+}
+
+int bifeat_params_get_codebooks(bifeat_params *p, float *codebooks) {
+    if (!p || p->scheme.kind != BIFEAT_VQ) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (codebooks) memcpy(codebooks, p->h_cb.data(), 4 * p->h_cb.size());
+    return BIFEAT_OK;
+}
+
+int bifeat_quantize(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
+                    uint8_t *codes, int64_t row0, void *stream) {
+    if (!p || !dtype_ok(dtype) || rows < 0 || row0 < 0) return BIFEAT_EINVAL;
+    if (rows > 0 && (!chunk || !codes)) return BIFEAT_EINVAL;
+    if ((uintptr_t)codes % 16) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (rows == 0) return BIFEAT_OK;
+    BF_HIP(bf::launch_quantize(p, chunk, dtype, rows, codes + row0 * p->rb, (hipStream_t)stream));
+    return BIFEAT_OK;
+}
+
+int bifeat_gather_codes(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *idx,
+                        int64_t M, uint8_t *out, void *stream) {
+    if (!p || M < 0 || N < 0) return BIFEAT_EINVAL;
+    if (M > 0 && (!codes || !idx || !out || N == 0)) return BIFEAT_EINVAL;
+    if ((uintptr_t)codes % 16 || (uintptr_t)out % 16) return BIFEAT_EINVAL;
+    if (M == 0) return BIFEAT_OK;
+    BF_HIP(bf::launch_gather_codes(p, codes, idx, M, out, (hipStream_t)stream));
+    return BIFEAT_OK;
+}
+
+int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *idx,
+                          int64_t M, float *out, void *stream) {
+    if (!p || M < 0 || N < 0) return BIFEAT_EINVAL;
+    if (M > 0 && (!codes || !idx || !out || N == 0)) return BIFEAT_EINVAL;
+    if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (M == 0) return BIFEAT_OK;
+    BF_HIP(bf::launch_gather_dequant(p, codes, idx, M, out, (hipStream_t)stream));
+    return BIFEAT_OK;
+}
+
+int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                       const int64_t *indices, int64_t V, float *out, void *stream) {
+    if (!p || V < 0 || N < 0) return BIFEAT_EINVAL;
+    if (V > 0 && (!codes || !indptr || !out)) return BIFEAT_EINVAL;
+    if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (V == 0) return BIFEAT_OK;
+    BF_HIP(bf::launch_gather_mean(p, codes, indptr, indices, V, out, (hipStream_t)stream));
+    return BIFEAT_OK;
+}
+
+const char *bifeat_strerror(int status) {
+    switch (status) {
+        case BIFEAT_OK: return "ok";
+        case BIFEAT_EINVAL: return "invalid argument";
+        case BIFEAT_ENOTFIT: return "quantizer parameters not fitted";
+        case BIFEAT_EHIP: return g_hip_error.empty() ? "HIP error" : g_hip_error.c_str();
+        case BIFEAT_ENOTSUP: return "not supported";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "bifeat.h"
+
+// Quantizer state behind the opaque bifeat_params handle.
+struct bifeat_params {
+    bifeat_scheme scheme{};
+    int64_t D = 0;
+    int64_t ncodes = 0;  // codes per row: D, or P for vector codes
+    int64_t rb = 0;      // packed bytes per row, multiple of 16
+    int P = 0;           // vector codes: number of parts
+
+    // host copies (valid when host_valid)
+    std::vector<float> h_min, h_max, h_scale, h_inv;  // uniform, [D] each
+    double e_min = 0.0, e_max = 0.0;                  // log
+    std::vector<float> h_T, h_V;                      // log: [H-1], [2^bits]
+    std::vector<float> h_cb;                          // vq: [P][len][w]
+    bool host_valid = false;
+
+    // device block (allocated on first GPU use)
+    int device = -1;
+    float *d_block = nullptr;
+    float *d_min = nullptr, *d_scale = nullptr, *d_inv = nullptr, *d_max = nullptr;
+    float *d_T = nullptr, *d_V = nullptr, *d_cb = nullptr;
+    int32_t *d_fit = nullptr;  // uniform: ordered-int keys [min D | max D]; log: bits of [mmin, mmax]
+
+    bool fitted = false;
+    bool fit_open = false;
+    int64_t fit_rows = 0;
+
+    // launch tuning (0 = automatic)
+    int opt_mean_slots = 0;
+    int opt_mean_blocks = 0;
+    int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
+};
+
+namespace bf {
+
+constexpr int kThreads = 256;
+// number of workgroups that fills the chip a few times over: 256 CUs x 8
+constexpr int kMaxBlocks = 2048;
+
+hipError_t launch_fit_reset(bifeat_params *p, hipStream_t s);
+hipError_t launch_fit_update(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
+                             hipStream_t s);
+hipError_t launch_finalize_uniform(bifeat_params *p, hipStream_t s);
+hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
+                           uint8_t *codes_row0, hipStream_t s);
+hipError_t launch_gather_codes(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
+                               int64_t M, uint8_t *out, hipStream_t s);
+hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
+                                 int64_t M, float *out, hipStream_t s);
+hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                              const int64_t *indices, int64_t V, float *out, hipStream_t s);
+
+// ---- order-preserving float <-> int keys for atomic min/max
+__host__ __device__ inline int32_t float_key(float f) {
+    union { float f; int32_t i; } u;
+    u.f = f;
+    return u.i >= 0 ? u.i : (u.i ^ 0x7FFFFFFF);
+}
+__host__ __device__ inline float key_float(int32_t k) {
+    union { float f; int32_t i; } u;
+    u.i = k >= 0 ? k : (k ^ 0x7FFFFFFF);
+    return u.f;
+}
+constexpr int32_t kKeyPosInf = 0x7F800000;
+constexpr int32_t kKeyNegInf = (int32_t)0x807FFFFFu;
+
+// ---- 4 consecutive elements of a row as floats
+__device__ inline float4 load4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ inline float4 load4(const __half *p) {
+    uint2 u = *reinterpret_cast<const uint2 *>(p);
+    __half2 a = *reinterpret_cast<__half2 *>(&u.x);
+    __half2 b = *reinterpret_cast<__half2 *>(&u.y);
+    float2 fa = __half22float2(a), fb = __half22float2(b);
+    return make_float4(fa.x, fa.y, fb.x, fb.y);
+}
+__device__ inline float load1(const float *p) { return *p; }
+__device__ inline float load1(const __half *p) { return __half2float(*p); }
+
+inline int blocks_for(int64_t threads_needed) {
+    int64_t b = (threads_needed + kThreads - 1) / kThreads;
+    if (b < 1) b = 1;
+    if (b > kMaxBlocks) b = kMaxBlocks;
+    return (int)b;
+}
+
+}  // namespace bf

@@ -1,0 +1,382 @@
+// Streaming fit and encode+pack kernels (one-time preprocessing, paper
+// Sec. 3.3; code definitions Sec. 3.1 Eq. (1) and Sec. 3.2).
+//
+// All three kernels stream a row-major [rows x D] chunk once.  A thread owns a
+// fixed group of consecutive columns for its whole life (the grid's row stride
+// is a multiple of the groups per row), so per-column parameters live in
+// registers while consecutive lanes still read consecutive addresses.
+#include "common.hpp"
+
+namespace bf {
+
+// ------------------------------------------------------------------ fit state
+__global__ void fit_reset_kernel(int32_t *state, int n_half, int32_t a, int32_t b) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_half) {
+        state[i] = a;
+        state[n_half + i] = b;
+    }
+}
+
+hipError_t launch_fit_reset(bifeat_params *p, hipStream_t s) {
+    if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
+        int D = (int)p->D;
+        fit_reset_kernel<<<(D + 255) / 256, 256, 0, s>>>(p->d_fit, D, kKeyPosInf, kKeyNegInf);
+    } else {
+        // log: [0] = smallest nonzero |x| (bits of +inf), [1] = largest finite |x| (0)
+        fit_reset_kernel<<<1, 64, 0, s>>>(p->d_fit, 1, 0x7F800000, 0);
+    }
+    return hipGetLastError();
+}
+
+// per-column min / max of a chunk merged into the running state.
+// VEC = 4 needs D % 4 == 0 and a 16-byte (fp16: 8-byte) aligned chunk.
+template <typename T, int VEC>
+__global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restrict__ x,
+                                                             int64_t rows, int D, int G,
+                                                             int32_t *state, int use_lds) {
+    extern __shared__ int32_t lds[];
+    if (use_lds) {
+        for (int i = threadIdx.x; i < D; i += kThreads) {
+            lds[i] = kKeyPosInf;
+            lds[D + i] = kKeyNegInf;
+        }
+        __syncthreads();
+    }
+    const int64_t total = (int64_t)gridDim.x * kThreads;
+    const int64_t rows_per_pass = total / G;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t < rows_per_pass * G) {
+        const int g = (int)(t % G);
+        float mn[VEC], mx[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; k++) {
+            mn[k] = INFINITY;
+            mx[k] = -INFINITY;
+        }
+        const T *src = x + (int64_t)g * VEC;
+#pragma unroll 4
+        for (int64_t r = t / G; r < rows; r += rows_per_pass) {
+            float v[VEC];
+            if constexpr (VEC == 4) {
+                float4 q = load4(src + r * D);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            } else {
+                v[0] = load1(src + r * D);
+            }
+#pragma unroll
+            for (int k = 0; k < VEC; k++) {
+                if (v[k] < mn[k]) mn[k] = v[k];  // NaN compares false: skipped
+                if (v[k] > mx[k]) mx[k] = v[k];
+            }
+        }
+        int32_t *lo = use_lds ? lds : state;
+#pragma unroll
+        for (int k = 0; k < VEC; k++) {
+            int col = g * VEC + k;
+            atomicMin(&lo[col], float_key(mn[k]));
+            atomicMax(&lo[D + col], float_key(mx[k]));
+        }
+    }
+    if (use_lds) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < D; i += kThreads) {
+            atomicMin(&state[i], lds[i]);
+            atomicMax(&state[D + i], lds[D + i]);
+        }
+    }
+}
+
+// smallest nonzero and largest finite magnitude of a chunk (log scheme);
+// positive floats order like their bit patterns
+template <typename T>
+__global__ __launch_bounds__(kThreads) void fit_log_kernel(const T *__restrict__ x, int64_t n,
+                                                          int32_t *state) {
+    uint32_t mmin = 0x7F800000u, mmax = 0u;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+#pragma unroll 4
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        uint32_t m = __float_as_uint(fabsf(load1(x + i)));
+        if (m < 0x7F800000u) {  // finite
+            if (m != 0u && m < mmin) mmin = m;
+            if (m > mmax) mmax = m;
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        mmin = min(mmin, (uint32_t)__shfl_xor((int)mmin, o));
+        mmax = max(mmax, (uint32_t)__shfl_xor((int)mmax, o));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicMin((uint32_t *)&state[0], mmin);
+        atomicMax((uint32_t *)&state[1], mmax);
+    }
+}
+
+hipError_t launch_fit_update(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
+                             hipStream_t s) {
+    const int D = (int)p->D;
+    if (p->scheme.kind == BIFEAT_SQ_LOG) {
+        int64_t n = rows * D;
+        int blocks = blocks_for((n + 3) / 4);
+        if (dtype == BIFEAT_F32)
+            fit_log_kernel<float><<<blocks, kThreads, 0, s>>>((const float *)chunk, n, p->d_fit);
+        else
+            fit_log_kernel<__half><<<blocks, kThreads, 0, s>>>((const __half *)chunk, n, p->d_fit);
+        return hipGetLastError();
+    }
+    const size_t esz = dtype == BIFEAT_F32 ? 4 : 2;
+    const bool vec = (D % 4 == 0) && ((uintptr_t)chunk % (4 * esz) == 0);
+    const int VEC = vec ? 4 : 1;
+    const int G = (D + VEC - 1) / VEC;
+    int64_t want = (rows * G + 7) / 8;  // about 8 rows per thread
+    if (want < G) want = G;
+    int blocks = blocks_for(want);
+    if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
+    const int use_lds = D <= 8192;
+    const size_t shm = use_lds ? sizeof(int32_t) * 2 * (size_t)D : 0;
+#define BF_FIT(T, V) \
+    fit_minmax_kernel<T, V><<<blocks, kThreads, shm, s>>>((const T *)chunk, rows, D, G, p->d_fit, use_lds)
+    if (dtype == BIFEAT_F32) {
+        if (vec) BF_FIT(float, 4); else BF_FIT(float, 1);
+    } else {
+        if (vec) BF_FIT(__half, 4); else BF_FIT(__half, 1);
+    }
+#undef BF_FIT
+    return hipGetLastError();
+}
+
+// scale_j = (max_j - min_j)/L and inv_j = L/(max_j - min_j): fp64 subtraction
+// and division, one rounding to fp32; 0 for a constant column; zeros as +0.
+__global__ void finalize_uniform_kernel(const int32_t *state, int D, int bits, float *mn,
+                                        float *mx, float *scale, float *inv) {
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= D) return;
+    float lo = key_float(state[j]), hi = key_float(state[D + j]);
+    if (lo == 0.0f) lo = 0.0f;
+    if (hi == 0.0f) hi = 0.0f;
+    double L = (double)((1u << bits) - 1u);
+    double range = (double)hi - (double)lo;
+    mn[j] = lo;
+    mx[j] = hi;
+    if (range > 0.0) {
+        scale[j] = (float)(range / L);
+        inv[j] = (float)(L / range);
+    } else {
+        scale[j] = 0.0f;
+        inv[j] = 0.0f;
+    }
+}
+
+hipError_t launch_finalize_uniform(bifeat_params *p, hipStream_t s) {
+    int D = (int)p->D;
+    finalize_uniform_kernel<<<(D + 255) / 256, 256, 0, s>>>(p->d_fit, D, p->scheme.bits, p->d_min,
+                                                            p->d_max, p->d_scale, p->d_inv);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------ scalar encoders
+struct UniformCoder {
+    static constexpr bool kEdges = false;
+    const float *mn, *inv;
+    float L;
+    struct Ctx { float mn[4], inv[4]; };
+    __device__ void prepare(Ctx &c, int col0, int D) const {
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            bool ok = col0 + k < D;
+            c.mn[k] = ok ? mn[col0 + k] : 0.0f;
+            c.inv[k] = ok ? inv[col0 + k] : 0.0f;
+        }
+    }
+    // q = clamp(rne((x - min) * inv), 0, L); sub, mul, round are separate fp32
+    // operations; max/min discard NaN, so NaN -> 0
+    __device__ uint32_t code(const Ctx &c, float x, int k) const {
+        float d = __fsub_rn(x, c.mn[k]);
+        float t = __fmul_rn(d, c.inv[k]);
+        float r = rintf(t);
+        r = fminf(fmaxf(r, 0.0f), L);
+        return (uint32_t)(int)r;
+    }
+};
+
+struct LogCoder {
+    static constexpr bool kEdges = true;
+    const float *T;  // global, H-1 edges
+    int H;
+    struct Ctx { const float *edges; };
+    __device__ void prepare(Ctx &c, int, int) const { c.edges = nullptr; }
+    // l = #{i : |x| >= T_i} by bisection over the sorted edges (in LDS)
+    __device__ uint32_t code(const Ctx &c, float x, int) const {
+        float m = fabsf(x);
+        int lo = 0, hi = H - 1;
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if (m >= c.edges[mid]) lo = mid + 1; else hi = mid;
+        }
+        return (uint32_t)((x > 0.0f) ? H + lo : H - 1 - lo);
+    }
+};
+
+// One thread encodes 4 consecutive columns (4*BITS bits); 8/BITS neighbouring
+// lanes OR their pieces into one 32-bit word and one of them stores it.  Every
+// word of the padded row is written (columns >= D encode as 0).
+template <typename T, int BITS, typename Coder, bool VEC>
+__global__ __launch_bounds__(kThreads) void quantize_sq_kernel(const T *__restrict__ x,
+                                                              int64_t rows, int D, int64_t rb,
+                                                              Coder coder,
+                                                              uint8_t *__restrict__ codes) {
+    __shared__ float s_edges[128];
+    typename Coder::Ctx ctx;
+    constexpr int LG = 8 / BITS;  // lanes per 32-bit word
+    const int GW = (int)(2 * rb / BITS);  // 4-column groups per padded row; multiple of 4*LG
+    if constexpr (Coder::kEdges) {
+        for (int i = threadIdx.x; i < coder.H - 1; i += kThreads) s_edges[i] = coder.T[i];
+        __syncthreads();
+    }
+    const int64_t total = (int64_t)gridDim.x * kThreads;
+    const int64_t rows_per_pass = total / GW;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * GW) return;
+    const int g = (int)(t % GW);
+    const int col0 = 4 * g;
+    coder.prepare(ctx, col0, D);
+    if constexpr (Coder::kEdges) ctx.edges = s_edges;
+    const int sub = g % LG;
+    uint32_t *dst_word = reinterpret_cast<uint32_t *>(codes) + (g / LG);
+    const int64_t rw = rb / 4;
+    for (int64_t r = t / GW; r < rows; r += rows_per_pass) {
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        const T *src = x + r * D + col0;
+        if (VEC) {
+            if (col0 < D) {
+                float4 q = load4(src);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+                if (col0 + k < D) v[k] = load1(src + k);
+        }
+        uint32_t piece = 0;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            uint32_t q = (col0 + k < D) ? coder.code(ctx, v[k], k) : 0u;
+            piece |= q << (BITS * k);
+        }
+        piece <<= (4 * BITS) * sub;
+#pragma unroll
+        for (int o = 1; o < LG; o <<= 1) piece |= (uint32_t)__shfl_xor((int)piece, o);
+        if (sub == 0) dst_word[r * rw] = piece;
+    }
+}
+
+template <typename T, typename Coder>
+static void launch_sq(const T *x, int64_t rows, int D, int64_t rb, int bits, Coder coder,
+                      uint8_t *codes, bool vec, hipStream_t s) {
+    const int GW = (int)(2 * rb / bits);
+    int64_t want = (rows * GW + 3) / 4;
+    if (want < GW) want = GW;
+    int blocks = blocks_for(want);
+    if ((int64_t)blocks * kThreads < GW) blocks = (GW + kThreads - 1) / kThreads;
+#define BF_Q(B)                                                                                 \
+    if (vec) quantize_sq_kernel<T, B, Coder, true><<<blocks, kThreads, 0, s>>>(x, rows, D, rb, coder, codes); \
+    else quantize_sq_kernel<T, B, Coder, false><<<blocks, kThreads, 0, s>>>(x, rows, D, rb, coder, codes)
+    switch (bits) {
+        case 1: BF_Q(1); break;
+        case 2: BF_Q(2); break;
+        case 4: BF_Q(4); break;
+        default: BF_Q(8); break;
+    }
+#undef BF_Q
+}
+
+// ------------------------------------------------------------- vector encoder
+// Block = one part p (its codebook in LDS) x 256 rows; a thread scans all
+// entries for its row.  Distance: fp32, dims ascending, subtract / multiply /
+// add rounded separately; strict < keeps the lowest index on ties.
+template <typename T, int W>
+__global__ __launch_bounds__(kThreads) void vq_assign_kernel(const T *__restrict__ x, int64_t rows,
+                                                            int D, int w_rt, int len, int P,
+                                                            const float *__restrict__ cb,
+                                                            uint8_t *__restrict__ codes,
+                                                            int64_t rb) {
+    extern __shared__ float s_cb[];
+    const int w = W > 0 ? W : w_rt;
+    const int p = blockIdx.x;
+    for (int i = threadIdx.x; i < len * w; i += kThreads) s_cb[i] = cb[(int64_t)p * len * w + i];
+    __syncthreads();
+    for (int64_t r = (int64_t)blockIdx.y * kThreads + threadIdx.x; r < rows;
+         r += (int64_t)gridDim.y * kThreads) {
+        const T *src = x + r * D + (int64_t)p * w;
+        int best = 0;
+        float bestd = INFINITY;
+        if constexpr (W > 0) {
+            float sub[W];
+#pragma unroll
+            for (int d = 0; d < W; d++) sub[d] = (p * W + d < D) ? load1(src + d) : 0.0f;
+            for (int c = 0; c < len; c++) {
+                float dist = 0.0f;
+#pragma unroll
+                for (int d = 0; d < W; d++) {
+                    float diff = __fsub_rn(sub[d], s_cb[c * W + d]);
+                    dist = __fadd_rn(dist, __fmul_rn(diff, diff));
+                }
+                if (dist < bestd) { bestd = dist; best = c; }
+            }
+        } else {
+            for (int c = 0; c < len; c++) {
+                float dist = 0.0f;
+                for (int d = 0; d < w; d++) {
+                    float xv = (p * w + d < D) ? load1(src + d) : 0.0f;
+                    float diff = __fsub_rn(xv, s_cb[c * w + d]);
+                    dist = __fadd_rn(dist, __fmul_rn(diff, diff));
+                }
+                if (dist < bestd) { bestd = dist; best = c; }
+            }
+        }
+        codes[r * rb + p] = (uint8_t)best;
+        if (p == 0)
+            for (int64_t b = P; b < rb; b++) codes[r * rb + b] = 0;  // row padding
+    }
+}
+
+template <typename T>
+static void launch_vq(const T *x, int64_t rows, bifeat_params *p, uint8_t *codes, hipStream_t s) {
+    const int w = p->scheme.vq_width, len = p->scheme.vq_length;
+    int64_t tiles = (rows + kThreads - 1) / kThreads;
+    dim3 grid((unsigned)p->P, (unsigned)(tiles > 4096 ? 4096 : tiles));
+    size_t shm = sizeof(float) * (size_t)len * (size_t)w;
+#define BF_VQ(W) \
+    vq_assign_kernel<T, W><<<grid, kThreads, shm, s>>>(x, rows, (int)p->D, w, len, p->P, p->d_cb, codes, p->rb)
+    switch (w) {
+        case 1: BF_VQ(1); break;
+        case 2: BF_VQ(2); break;
+        case 4: BF_VQ(4); break;
+        case 8: BF_VQ(8); break;
+        case 16: BF_VQ(16); break;
+        default: BF_VQ(0); break;
+    }
+#undef BF_VQ
+}
+
+hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
+                           uint8_t *codes, hipStream_t s) {
+    const int D = (int)p->D;
+    const size_t esz = dtype == BIFEAT_F32 ? 4 : 2;
+    const bool vec = (D % 4 == 0) && ((uintptr_t)chunk % (4 * esz) == 0);
+    if (p->scheme.kind == BIFEAT_VQ) {
+        if (dtype == BIFEAT_F32) launch_vq((const float *)chunk, rows, p, codes, s);
+        else launch_vq((const __half *)chunk, rows, p, codes, s);
+    } else if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
+        UniformCoder c{p->d_min, p->d_inv, (float)((1u << p->scheme.bits) - 1u)};
+        if (dtype == BIFEAT_F32) launch_sq((const float *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
+        else launch_sq((const __half *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
+    } else {
+        LogCoder c{p->d_T, 1 << (p->scheme.bits - 1)};
+        if (dtype == BIFEAT_F32) launch_sq((const float *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
+        else launch_sq((const __half *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace bf

@@ -1,0 +1,174 @@
+// Per-iteration load (paper Sec. 3.3): gather the packed rows of the sampled
+// nodes, and the fused gather + unpack + decode (Sec. 3.1 Eq. (2); Sec. 3.2
+// codebook lookup).
+//
+// gather_dequant writes 4*D bytes per row and reads at most D bytes, so the
+// mapping is output-centric: a lane owns 4 consecutive output columns (one
+// 16-byte store, consecutive lanes consecutive addresses) and fetches only the
+// 4*bits code bits it needs.  The lane keeps its column group for its whole
+// life, so scale/offset sit in registers.
+#include "common.hpp"
+
+namespace bf {
+
+// out[i, :] = codes[idx[i], :], 16 bytes per lane
+__global__ __launch_bounds__(kThreads) void gather_codes_kernel(const uint4 *__restrict__ codes,
+                                                               int rc /* 16B chunks per row */,
+                                                               const int64_t *__restrict__ idx,
+                                                               int64_t M, uint4 *__restrict__ out) {
+    const int64_t total = (int64_t)gridDim.x * kThreads;
+    const int64_t rows_per_pass = total / rc;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * rc) return;
+    const int c = (int)(t % rc);
+    for (int64_t i = t / rc; i < M; i += rows_per_pass) out[i * rc + c] = codes[idx[i] * rc + c];
+}
+
+hipError_t launch_gather_codes(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
+                               int64_t M, uint8_t *out, hipStream_t s) {
+    const int rc = (int)(p->rb / 16);
+    int64_t want = M * rc;
+    int blocks = blocks_for(want);
+    if ((int64_t)blocks * kThreads < rc) blocks = (rc + kThreads - 1) / kThreads;
+    gather_codes_kernel<<<blocks, kThreads, 0, s>>>((const uint4 *)codes, rc, idx, M, (uint4 *)out);
+    return hipGetLastError();
+}
+
+// the 4*BITS code bits of columns 4g..4g+3 of a packed row (always inside the
+// 16-byte padded row)
+template <int BITS>
+__device__ inline uint32_t code_bits4(const uint8_t *row, int g) {
+    if constexpr (BITS == 8) return *reinterpret_cast<const uint32_t *>(row + 4 * g);
+    else if constexpr (BITS == 4) return *reinterpret_cast<const uint16_t *>(row + 2 * g);
+    else if constexpr (BITS == 2) return row[g];
+    else return (uint32_t)(row[g >> 1] >> (4 * (g & 1))) & 0xFu;
+}
+
+__device__ inline void store4(float *out, int64_t row, int D, int col0, const float v[4], bool vec) {
+    float *dst = out + row * D + col0;
+    if (vec) {
+        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            if (col0 + k < D) dst[k] = v[k];
+    }
+}
+
+enum { DEC_UNIFORM = 0, DEC_LOG = 1 };
+
+// scalar codes.  uniform: x' = fma(q, scale_j, min_j); log: x' = V[q] (table in LDS)
+template <int BITS, int DEC>
+__global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
+    const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ idx, int64_t M,
+    int D, const float *__restrict__ pa, const float *__restrict__ pb, float *__restrict__ out,
+    int vec) {
+    __shared__ float s_lut[DEC == DEC_LOG ? (1 << BITS) : 1];
+    if constexpr (DEC == DEC_LOG) {
+        for (int i = threadIdx.x; i < (1 << BITS); i += kThreads) s_lut[i] = pa[i];
+        __syncthreads();
+    }
+    const int G = (D + 3) / 4;
+    const int64_t total = (int64_t)gridDim.x * kThreads;
+    const int64_t rows_per_pass = total / G;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * G) return;
+    const int g = (int)(t % G), col0 = 4 * g;
+    float mn[4], sc[4];
+    if constexpr (DEC == DEC_UNIFORM) {
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            bool ok = col0 + k < D;
+            mn[k] = ok ? pa[col0 + k] : 0.f;
+            sc[k] = ok ? pb[col0 + k] : 0.f;
+        }
+    }
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+#pragma unroll 2
+    for (int64_t i = t / G; i < M; i += rows_per_pass) {
+        const uint32_t bits = code_bits4<BITS>(codes + idx[i] * rb, g);
+        float v[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            uint32_t q = (bits >> (BITS * k)) & mask;
+            if constexpr (DEC == DEC_UNIFORM) v[k] = fmaf((float)q, sc[k], mn[k]);
+            else v[k] = s_lut[q];
+        }
+        store4(out, i, D, col0, v, vec);
+    }
+}
+
+// vector codes: columns 4g..4g+3 of part p = col / w come from entry q = row[p]
+template <bool W4>
+__global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
+    const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ idx, int64_t M,
+    int D, int w, int len, const float *__restrict__ cb, float *__restrict__ out, int vec) {
+    const int G = (D + 3) / 4;
+    const int64_t total = (int64_t)gridDim.x * kThreads;
+    const int64_t rows_per_pass = total / G;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * G) return;
+    const int g = (int)(t % G), col0 = 4 * g;
+    int part[4], dim[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        part[k] = (col0 + k) / w;
+        dim[k] = (col0 + k) % w;
+    }
+#pragma unroll 2
+    for (int64_t i = t / G; i < M; i += rows_per_pass) {
+        const uint8_t *row = codes + idx[i] * rb;
+        float v[4];
+        if constexpr (W4) {  // w % 4 == 0: the four columns share a part, entry rows 16B aligned
+            const int q = row[part[0]];
+            float4 c = *reinterpret_cast<const float4 *>(cb + ((int64_t)part[0] * len + q) * w + dim[0]);
+            v[0] = c.x; v[1] = c.y; v[2] = c.z; v[3] = c.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                v[k] = 0.f;
+                if (col0 + k < D) v[k] = cb[((int64_t)part[k] * len + row[part[k]]) * w + dim[k]];
+            }
+        }
+        store4(out, i, D, col0, v, vec);
+    }
+}
+
+hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
+                                 int64_t M, float *out, hipStream_t s) {
+    const int D = (int)p->D;
+    const int G = (D + 3) / 4;
+    const int vec = (D % 4 == 0) && ((uintptr_t)out % 16 == 0);
+    int blocks = blocks_for(M * G);
+    if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
+    const int kind = p->scheme.kind, bits = p->scheme.bits;
+    if (kind == BIFEAT_VQ) {
+        const int w = p->scheme.vq_width;
+        if (w % 4 == 0 && vec)
+            gather_dequant_vq_kernel<true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out, vec);
+        else
+            gather_dequant_vq_kernel<false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out, vec);
+        return hipGetLastError();
+    }
+#define BF_GD(B, DEC, A, Bp) \
+    gather_dequant_sq_kernel<B, DEC><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, A, Bp, out, vec)
+    if (kind == BIFEAT_SQ_UNIFORM) {
+        switch (bits) {
+            case 1: BF_GD(1, DEC_UNIFORM, p->d_min, p->d_scale); break;
+            case 2: BF_GD(2, DEC_UNIFORM, p->d_min, p->d_scale); break;
+            case 4: BF_GD(4, DEC_UNIFORM, p->d_min, p->d_scale); break;
+            default: BF_GD(8, DEC_UNIFORM, p->d_min, p->d_scale); break;
+        }
+    } else {
+        switch (bits) {
+            case 1: BF_GD(1, DEC_LOG, p->d_V, nullptr); break;
+            case 2: BF_GD(2, DEC_LOG, p->d_V, nullptr); break;
+            case 4: BF_GD(4, DEC_LOG, p->d_V, nullptr); break;
+            default: BF_GD(8, DEC_LOG, p->d_V, nullptr); break;
+        }
+    }
+#undef BF_GD
+    return hipGetLastError();
+}
+
+}  // namespace bf

@@ -1,0 +1,248 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on
+the same seeded inputs.  Codes, packed rows and fitted parameters are compared
+bit for bit; decoded values and means to 1e-5 relative (see helpers.assert_close).
+Sizes span several workgroup tiles and a ragged tail."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from bifeat_inputs import FeatureSpec, feature_chunk
+from helpers import (assert_close, gpu_build_table, oracle_uniform_table, random_csr, scheme_of)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bf():
+    import paper_2207_14696_amd as m
+    m.load_library()
+    return m
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    return t
+
+
+def _dev_table(spec):
+    from bifeat_inputs.device import DeviceTable
+    return DeviceTable(spec)
+
+
+@pytest.mark.parametrize("D,dtype", [(100, "f32"), (128, "f16"), (37, "f32"), (37, "f16"), (768, "f16")])
+def test_device_generator_is_bit_identical(torch, D, dtype):
+    spec = FeatureSpec(5003, D, 0, dtype)
+    got = _dev_table(spec).chunk(1000, 4003).cpu().numpy()
+    want = feature_chunk(spec, 1000, 4003)
+    assert got.dtype == want.dtype and np.array_equal(got.view(np.uint8), want.view(np.uint8))
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+@pytest.mark.parametrize("D,dtype", [(100, "f32"), (128, "f32"), (37, "f32"), (200, "f16")])
+def test_uniform_fit_and_codes_bit_exact(bf, torch, bits, D, dtype):
+    spec = FeatureSpec(9001, D, 1, dtype)
+    x, (mn, mx, scale, inv), s, codes = oracle_uniform_table(spec, bits)
+    q = bf.Quantizer(scheme_of("uniform", bits), D)
+    assert q.row_bytes == s.row_bytes
+    got = gpu_build_table(q, _dev_table(spec), spec.N, 2500)     # 4 chunks, ragged last
+    gmn, gmx, gscale, ginv = q.params_get_uniform()
+    for a, b in [(gmn, mn), (gmx, mx), (gscale, scale), (ginv, inv)]:
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.array_equal(got.cpu().numpy(), codes)
+
+
+def test_uniform_params_set_matches_fit(bf, torch):
+    spec = FeatureSpec(3000, 64, 2)
+    x, (mn, mx, scale, inv), s, codes = oracle_uniform_table(spec, 4)
+    q = bf.Quantizer(scheme_of("uniform", 4), 64)
+    q.params_set_uniform(mn, mx)
+    _, _, gscale, ginv = q.params_get_uniform()
+    assert np.array_equal(gscale, scale) and np.array_equal(ginv, inv)
+    got = gpu_build_table(q, _dev_table(spec), spec.N, 3000, fit=False)
+    assert np.array_equal(got.cpu().numpy(), codes)
+
+
+def test_uniform_special_values(bf, torch):
+    # constant column, NaN, out-of-range values, exact ties
+    D = 8
+    x = feature_chunk(FeatureSpec(600, D, 3), 0, 600).copy()
+    x[:, 2] = 0.25
+    x[5, 0] = np.nan
+    mn, mx = orc.fit_minmax(x)
+    scale, inv = orc.uniform_params(mn, mx, 4)
+    q = bf.Quantizer(scheme_of("uniform", 4), D)
+    xt = torch.from_numpy(x).cuda()
+    q.fit_update(xt)
+    q.fit_finalize()
+    gmn, gmx, gscale, ginv = q.params_get_uniform()
+    assert np.array_equal(gmn, mn) and np.array_equal(gmx, mx) and gscale[2] == 0 and ginv[2] == 0
+    y = x.copy()
+    y[0, :] = 1e9
+    y[1, :] = -1e9
+    y[2, :] = (mn + 2.5 * scale).astype(np.float32)           # near ties
+    codes = torch.zeros((600, q.row_bytes), dtype=torch.uint8, device="cuda")
+    q.quantize(torch.from_numpy(y).cuda(), codes, 0)
+    want = orc.pack(orc.uniform_encode(y, 4, mn, inv), 4)
+    assert np.array_equal(codes.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_log_fit_and_codes_bit_exact(bf, torch, k):
+    D = 52
+    spec = FeatureSpec(7001, D, 4)
+    x = feature_chunk(spec, 0, spec.N)
+    st = orc.log_fit(x)
+    e_min, e_max = orc.log_range(st)
+    T, V = orc.log_tables(e_min, e_max, k)
+    want = orc.pack(orc.log_encode(x, k, T), k)
+    q = bf.Quantizer(scheme_of("log", k), D)
+    got = gpu_build_table(q, _dev_table(spec), spec.N, 3000)
+    ge_min, ge_max, gT, gV = q.params_get_log()
+    assert (ge_min, ge_max) == (e_min, e_max)
+    assert np.array_equal(gT, T) and np.array_equal(gV, V)
+    assert np.array_equal(got.cpu().numpy(), want)
+    # a clipped range supplied by the caller (oracle: exact order statistics)
+    c_min, c_max = orc.log_range_clipped(x, 0.02)
+    T, V = orc.log_tables(c_min, c_max, k)
+    q.params_set_log(c_min, c_max)
+    got = gpu_build_table(q, _dev_table(spec), spec.N, 7001, fit=False)
+    assert np.array_equal(got.cpu().numpy(), orc.pack(orc.log_encode(x, k, T), k))
+
+
+def test_log_zero_and_sign_handling(bf, torch):
+    x = np.array([[0.0, -0.0, 1.0, -1.0, np.nan, 3.0, -2.0, 0.5]], np.float32)
+    q = bf.Quantizer(scheme_of("log", 2), 8)
+    q.params_set_log(-1.0, 2.0)
+    T, _ = orc.log_tables(-1.0, 2.0, 2)
+    codes = torch.zeros((1, q.row_bytes), dtype=torch.uint8, device="cuda")
+    q.quantize(torch.from_numpy(x).cuda(), codes, 0)
+    assert np.array_equal(codes.cpu().numpy(), orc.pack(orc.log_encode(x, 2, T), 2))
+
+
+@pytest.mark.parametrize("D,w,length,dtype", [(64, 8, 256, "f32"), (96, 4, 16, "f16"),
+                                              (23, 5, 7, "f32"), (40, 16, 64, "f32"),
+                                              (12, 1, 4, "f32")])
+def test_vq_codes_bit_exact(bf, torch, D, w, length, dtype):
+    spec = FeatureSpec(4099, D, 5, dtype)
+    x = feature_chunk(spec, 0, spec.N).astype(np.float32)
+    cb, _ = orc.vq_train(x[:1500], w, length, iters=4)
+    want = orc.pack(orc.vq_assign(x, w, cb), 8)
+    q = bf.Quantizer(scheme_of("vq", 8, w, length), D)
+    q.params_set_codebooks(cb)
+    assert np.array_equal(q.params_get_codebooks(), cb)
+    got = gpu_build_table(q, _dev_table(spec), spec.N, 1700, fit=False)
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
+def _tables(bf, torch, kind, bits, D, N=6007, w=8, length=32, seed=6):
+    """(quantizer, oracle scheme, packed codes as numpy + as CUDA tensor)."""
+    spec = FeatureSpec(N, D, seed)
+    x = feature_chunk(spec, 0, N)
+    if kind == "uniform":
+        _, (mn, mx, scale, inv), s, codes = oracle_uniform_table(spec, bits)
+        q = bf.Quantizer(scheme_of("uniform", bits), D)
+        q.params_set_uniform(mn, mx)
+    elif kind == "log":
+        e_min, e_max = orc.log_range_clipped(x, 0.01)
+        T, V = orc.log_tables(e_min, e_max, bits)
+        s = orc.Scheme.log(D, V, bits)
+        codes = orc.pack(orc.log_encode(x, bits, T), bits)
+        q = bf.Quantizer(scheme_of("log", bits), D)
+        q.params_set_log(e_min, e_max)
+    else:
+        cb, _ = orc.vq_train(x[:1000], w, length, iters=3)
+        s = orc.Scheme.vq(D, cb)
+        codes = orc.pack(orc.vq_assign(x, w, cb), 8)
+        q = bf.Quantizer(scheme_of("vq", 8, w, length), D)
+        q.params_set_codebooks(cb)
+    return q, s, codes, torch.from_numpy(codes).cuda()
+
+
+CASES = [("uniform", 1, 768), ("uniform", 2, 128), ("uniform", 4, 100), ("uniform", 8, 128),
+         ("uniform", 4, 37), ("uniform", 8, 5), ("uniform", 1, 70), ("uniform", 2, 1),
+         ("log", 1, 64), ("log", 2, 100), ("log", 4, 37), ("log", 8, 16),
+         ("vq", 8, 64), ("vq", 8, 100), ("vq", 8, 23)]
+
+
+@pytest.mark.parametrize("kind,bits,D", CASES)
+def test_gather_codes_and_dequant(bf, torch, kind, bits, D):
+    w = 5 if D == 23 else (4 if D == 100 else 8)
+    q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, w=w)
+    rng = np.random.default_rng(0)
+    idx = rng.integers(0, codes.shape[0], 3001).astype(np.int64)
+    idx[:3] = [0, codes.shape[0] - 1, 0]
+    didx = torch.from_numpy(idx).cuda()
+    assert np.array_equal(q.gather_codes(dcodes, didx).cpu().numpy(), orc.gather_codes(codes, idx))
+    got = q.gather_dequant(dcodes, didx).cpu().numpy()
+    assert_close(got, orc.gather_dequant(s, codes, idx), s, "gather_dequant")
+    # empty request
+    empty = torch.empty(0, dtype=torch.int64, device="cuda")
+    assert q.gather_dequant(dcodes, empty).shape == (0, D)
+    assert q.gather_codes(dcodes, empty).shape == (0, q.row_bytes)
+
+
+@pytest.mark.parametrize("kind,bits,D", CASES)
+def test_gather_mean(bf, torch, kind, bits, D):
+    w = 5 if D == 23 else (4 if D == 100 else 8)
+    q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, w=w)
+    rng = np.random.default_rng(1)
+    # long lists cross the integer-accumulator capacity of every bit width
+    hubs = (90, 300, 700, 4500) if kind == "uniform" else (300,)
+    indptr, indices = random_csr(1501, codes.shape[0], 30, rng, hubs=hubs)
+    want = orc.gather_mean(s, codes, indptr, indices)
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    got = q.gather_mean(dcodes, dptr, dind).cpu().numpy()
+    assert not got[0].any()
+    assert_close(got, want, s, "gather_mean")
+    if kind == "uniform":
+        for slots in (1, 2, 8, 64):
+            q.set_option("mean_slots", slots)
+            assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), want, s, f"slots={slots}")
+        q.set_option("mean_slots", 0)
+        q.set_option("mean_generic", 1)
+        assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), want, s, "generic")
+        q.set_option("mean_generic", 0)
+
+
+def test_gather_mean_degenerate_blocks(bf, torch):
+    q, s, codes, dcodes = _tables(bf, torch, "uniform", 4, 100)
+    z = torch.zeros(1, dtype=torch.int64, device="cuda")
+    assert q.gather_mean(dcodes, z, torch.empty(0, dtype=torch.int64, device="cuda")).shape == (0, 100)
+    # every list empty
+    ptr = torch.zeros(18, dtype=torch.int64, device="cuda")
+    out = q.gather_mean(dcodes, ptr, torch.empty(0, dtype=torch.int64, device="cuda"))
+    assert out.shape == (17, 100) and not out.any()
+    # one destination, one neighbour: equals that row's dequantization
+    ptr = torch.tensor([0, 1], dtype=torch.int64, device="cuda")
+    ind = torch.tensor([77], dtype=torch.int64, device="cuda")
+    one = q.gather_mean(dcodes, ptr, ind).cpu().numpy()
+    assert_close(one, orc.gather_dequant(s, codes, np.array([77])), s)
+
+
+def test_wide_rows_take_several_passes(bf, torch):
+    # 8-bit codes, D = 1500: a packed row is longer than one wavefront's 64 x 16 bytes
+    q, s, codes, dcodes = _tables(bf, torch, "uniform", 8, 1500, N=301)
+    rng = np.random.default_rng(2)
+    indptr, indices = random_csr(97, 301, 12, rng, hubs=(300,))
+    got = q.gather_mean(dcodes, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda())
+    assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, indptr, indices), s)
+    idx = rng.integers(0, 301, 200).astype(np.int64)
+    got = q.gather_dequant(dcodes, torch.from_numpy(idx).cuda()).cpu().numpy()
+    assert_close(got, orc.gather_dequant(s, codes, idx), s)
+
+
+def test_argument_errors(bf, torch):
+    q = bf.Quantizer(scheme_of("uniform", 4), 16)
+    codes = torch.zeros((4, q.row_bytes), dtype=torch.uint8, device="cuda")
+    idx = torch.zeros(2, dtype=torch.int64, device="cuda")
+    with pytest.raises(bf.BifeatError) as e:
+        q.gather_dequant(codes, idx)
+    assert e.value.status == -2                       # not fitted
+    with pytest.raises(bf.BifeatError) as e:
+        q.fit_finalize()
+    assert e.value.status == -2
+    v = bf.Quantizer(scheme_of("vq", 8, 4, 16), 16)
+    with pytest.raises(bf.BifeatError) as e:
+        v.fit_update(torch.zeros((3, 16), device="cuda"))
+    assert e.value.status == -4                       # codebook training is not a fit pass here
