@@ -1,0 +1,326 @@
+#!/usr/bin/env python3
+"""Benchmark of the feature-loading path on one MI355X.
+
+A *step* is one minibatch launch-set of the per-iteration path: decode the
+input-node rows (gather_dequant) and, for every hop's sampled block, the fused
+gather + decode + neighbourhood mean (gather_mean), all against the packed
+table resident in HBM.  ``--batches-per-step L`` concatenates L independently
+sampled minibatches into each launch (what a prefetching loader hands over);
+L = 1 is one 1,024-seed minibatch per launch.  The one-time fit + quantize pass
+that builds the table runs before the timed region and is reported separately
+under "preprocess".
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="mid",
+                    choices=["tiny", "mid", "large", "largest1", "largest4", "vq"])
+    ap.add_argument("--rows", type=int, default=0, help="override N (debugging)")
+    ap.add_argument("--batches", type=int, default=0, help="distinct pre-sampled launch-sets")
+    ap.add_argument("--batches-per-step", type=int, default=0)
+    ap.add_argument("--chunk-rows", type=int, default=1 << 20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (counter calibration under rocprofv3)")
+    ap.add_argument("--mean-slots", type=int, default=0)
+    ap.add_argument("--mean-blocks", type=int, default=0)
+    ap.add_argument("--max-blocks", type=int, default=0)
+    return ap.parse_args()
+
+
+def concat_blocks(blocks):
+    """Concatenate the CSR blocks of several minibatches into one launch."""
+    indptr = [np.zeros(1, np.int64)]
+    off = 0
+    for b in blocks:
+        indptr.append(b.indptr[1:] + off)
+        off += b.E
+    return np.concatenate(indptr), np.concatenate([b.indices for b in blocks])
+
+
+def traffic_from_profile(workload: str, kernel: str):
+    """HBM bytes per launch of a kernel, from the committed rocprofv3 --pmc
+    summary for this workload (None if there is none)."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.md")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU path only: this build has no multi-GPU leg "
+              "(run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2207_14696_amd as bf
+    from bifeat_inputs import WORKLOADS, make_graph, draw_seeds, sample_blocks, feature_rows
+    from bifeat_inputs.device import DeviceTable
+
+    w = WORKLOADS[args.workload]
+    if args.rows:
+        w = w.scaled(args.rows)
+    L = args.batches_per_step or {"tiny": 64, "mid": 64, "large": 8, "largest1": 32,
+                                  "largest4": 32, "vq": 8}[w.name.split("@")[0]]
+    B = args.batches or 8
+    torch.cuda.set_device(0)
+    dev = "cuda"
+
+    # ------------------------------------------------------------ the table
+    kind = {"uniform": bf.UNIFORM, "log": bf.LOG, "vq": bf.VQ}[w.kind]
+    q = bf.Quantizer(bf.Scheme(kind, w.bits, w.vq_width if w.kind == "vq" else 0,
+                               w.vq_length if w.kind == "vq" else 0), w.D)
+    for opt in ("mean_slots", "mean_blocks", "max_blocks"):
+        if getattr(args, opt):
+            q.set_option(opt, getattr(args, opt))
+    table = DeviceTable(w.spec)
+    rb = q.row_bytes
+    codes = torch.empty((w.N, rb), dtype=torch.uint8, device=dev)
+    chunk_rows = min(args.chunk_rows, w.N)
+    buf = torch.empty((chunk_rows, w.D), dtype=table.torch_dtype, device=dev)
+    esz = 4 if w.dtype == "f32" else 2
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    pre = {}
+    if w.kind == "vq":
+        # codebooks: sub-vectors of the first `length` sampled rows (no trainer on
+        # the GPU path yet); enough for throughput, which does not depend on values
+        from bifeat_inputs.features import mix64, stream_key, STREAM_MISC
+        ids = (mix64(stream_key(w.seed, STREAM_MISC) + np.arange(w.vq_length, dtype=np.uint64))
+               % np.uint64(w.N)).astype(np.int64)
+        rows = feature_rows(w.spec, ids).astype(np.float32)
+        P = q.codes_per_row
+        cb = np.ascontiguousarray(rows.reshape(w.vq_length, P, w.vq_width).transpose(1, 0, 2))
+        q.params_set_codebooks(cb)
+    else:
+        fit_ms = 0.0
+        q.fit_reset()
+        for r0 in range(0, w.N, chunk_rows):
+            n = min(chunk_rows, w.N - r0)
+            table.chunk(r0, n, buf[:n])
+            a, b = ev(), ev()
+            a.record()
+            q.fit_update(buf[:n])
+            b.record()
+            b.synchronize()
+            fit_ms += a.elapsed_time(b)
+        q.fit_finalize()
+        pre["fit_GBps"] = w.N * w.D * esz / fit_ms / 1e6
+    quant_ms = 0.0
+    for r0 in range(0, w.N, chunk_rows):
+        n = min(chunk_rows, w.N - r0)
+        table.chunk(r0, n, buf[:n])
+        a, b = ev(), ev()
+        a.record()
+        q.quantize(buf[:n], codes, r0)
+        b.record()
+        b.synchronize()
+        quant_ms += a.elapsed_time(b)
+    pre["quantize_GBps"] = (w.N * w.D * esz + w.N * rb) / quant_ms / 1e6
+    pre["quantize_rows_per_s"] = w.N / quant_ms * 1e3
+    pre["table_GB"] = w.N * rb / 1e9
+    del buf
+
+    # ------------------------------------------------- pre-sampled launch-sets
+    g = make_graph(w)
+    sets = []
+    for s in range(B):
+        mbs = []
+        for l in range(L):
+            bi = s * L + l
+            seeds = draw_seeds(g, w.batch, w.seed, bi, w.seed_mode)
+            mbs.append(sample_blocks(g, seeds, w.fanouts, w.seed, bi))
+        hops = []
+        for h in range(len(w.fanouts)):
+            indptr, indices = concat_blocks([mb[0][h] for mb in mbs])
+            hops.append((indptr, indices))
+        inputs = np.concatenate([mb[1] for mb in mbs])
+        sets.append({"hops": hops, "inputs": inputs})
+    for s in sets:
+        s["d_inputs"] = torch.from_numpy(s["inputs"]).to(dev)
+        s["d_hops"] = [(torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)) for a, b in s["hops"]]
+        s["rows"] = int(s["inputs"].shape[0] + sum(b.shape[0] for _, b in s["hops"]))
+    max_in = max(s["inputs"].shape[0] for s in sets)
+    max_v = [max(s["hops"][h][0].shape[0] - 1 for s in sets) for h in range(len(w.fanouts))]
+    out_in = torch.empty((max_in, w.D), dtype=torch.float32, device=dev)
+    out_h = [torch.empty((v, w.D), dtype=torch.float32, device=dev) for v in max_v]
+    outer = len(w.fanouts) - 1
+
+    def step(i, timed=None):
+        s = sets[i % B]
+        if timed is not None:
+            timed[0].record()
+        q.gather_dequant(codes, s["d_inputs"], out_in[:s["d_inputs"].shape[0]])
+        if timed is not None:
+            timed[1].record()
+        for h, (dp, di) in enumerate(s["d_hops"]):
+            if timed is not None and h == outer:
+                timed[2].record()
+            q.gather_mean(codes, dp, di, out_h[h][:dp.shape[0] - 1])
+        if timed is not None:
+            timed[3].record()
+
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [tuple(ev() for _ in range(4)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall = t1 - t0
+    rows_total = sum(sets[i % B]["rows"] for i in range(args.steps))
+    ms_per_step = wall / args.steps * 1e3
+
+    # ------------------------------------------ roofline per kernel, dominant one first
+    # algorithmic bytes (what the method must move): gather_dequant, per row
+    # 8 (index) + row_bytes + 4*D; gather_mean, per block 8*(V+1) + 8*E + row_bytes*U
+    # + 4*D*V with U = distinct source rows of the launch (compulsory reads).
+    for s in sets:
+        M = s["inputs"].shape[0]
+        s["bytes_dequant"] = M * (8 + rb + 4 * w.D)
+        bm = []
+        for indptr, indices in s["hops"]:
+            V, E = indptr.shape[0] - 1, indices.shape[0]
+            U = np.unique(indices).shape[0]
+            bm.append((8 * (V + 1) + 8 * E + rb * U + 4 * w.D * V, V, E, U))
+        s["bytes_mean"] = bm
+    t_deq = sum(e[0].elapsed_time(e[1]) for e in events)
+    t_inner = sum(e[1].elapsed_time(e[2]) for e in events)
+    t_outer = sum(e[2].elapsed_time(e[3]) for e in events)
+    b_deq = sum(sets[i % B]["bytes_dequant"] for i in range(args.steps))
+    b_outer = sum(sets[i % B]["bytes_mean"][outer][0] for i in range(args.steps))
+    b_inner = sum(sum(x[0] for x in sets[i % B]["bytes_mean"][:outer]) for i in range(args.steps))
+
+    def roof(name, nbytes, ms, extra=None):
+        ach = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        r = {"bound": "hbm", "kernel": name, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+             "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+             "traffic": traffic_from_profile(args.workload, name),
+             "avg_kernel_us": round(ms / args.steps * 1e3, 2),
+             "algorithmic_bytes_per_launch": int(nbytes / args.steps)}
+        if extra:
+            r.update(extra)
+        return r
+
+    o = [sets[i % B]["bytes_mean"][outer] for i in range(args.steps)]
+    kernels = {
+        "gather_dequant": roof("gather_dequant", b_deq, t_deq,
+                               {"rows_per_launch": int(np.mean([s["inputs"].shape[0] for s in sets]))}),
+        "gather_mean": roof("gather_mean", b_outer, t_outer,
+                            {"block": "outermost hop", "dst_per_launch": int(np.mean([x[1] for x in o])),
+                             "edges_per_launch": int(np.mean([x[2] for x in o])),
+                             "distinct_rows_per_launch": int(np.mean([x[3] for x in o]))}),
+    }
+    if outer > 0:
+        kernels["gather_mean_inner_hops"] = roof("gather_mean", b_inner, t_inner,
+                                                 {"block": f"{outer} inner hop(s), one launch each"})
+    dominant = "gather_dequant" if t_deq > t_outer else "gather_mean"
+    roofline = kernels[dominant]
+
+    # ------------------------------------------------------------ CPU baseline
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, g, args.cpu_seconds)
+
+    value = rows_total / wall
+    res = {
+        "metric": "sampled rows gathered+dequantized/s", "value": round(value, 1), "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "N": w.N, "D": w.D, "scheme": w.kind,
+                   "bits": w.bits if w.kind != "vq" else None,
+                   "vq": [w.vq_width, w.vq_length] if w.kind == "vq" else None,
+                   "row_bytes": rb, "graph": w.graph, "avg_degree": w.avg_degree,
+                   "fanouts": list(w.fanouts), "batch": w.batch, "batches_per_step": L,
+                   "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B},
+        "rows_per_step": int(rows_total / args.steps),
+        "uncompressed_equiv_GBps": round(value * w.D * esz / 1e9, 1),
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+        "preprocess": {k: round(v, 3) for k, v in pre.items()},
+    }
+    print(json.dumps(res))
+
+
+def cpu_baseline(w, g, seconds: float):
+    """The oracle timed on this machine's host cores on single minibatches of the
+    same workload.  It runs on a compact sub-table holding only the rows a
+    minibatch touches (the full table is not built on the host), which flatters
+    the CPU's caches."""
+    import oracle as orc
+    from bifeat_inputs import draw_seeds, sample_blocks, feature_rows
+    rows_done, spent, nb = 0, 0.0, 0
+    bi = 10_000
+    while spent < seconds and nb < 64:
+        seeds = draw_seeds(g, w.batch, w.seed, bi, w.seed_mode)
+        blocks, inputs = sample_blocks(g, seeds, w.fanouts, w.seed, bi)
+        x = feature_rows(w.spec, inputs).astype(np.float32)     # inputs is sorted & unique
+        remap = lambda ids: np.searchsorted(inputs, ids)        # noqa: E731
+        if w.kind == "uniform":
+            mn, mx = orc.fit_minmax(x)
+            scale, inv = orc.uniform_params(mn, mx, w.bits)
+            s = orc.Scheme.uniform(mn, scale, w.bits)
+            codes = orc.pack(orc.uniform_encode(x, w.bits, mn, inv), w.bits)
+        elif w.kind == "log":
+            T, V = orc.log_tables(*orc.log_range(orc.log_fit(x)), w.bits)
+            s = orc.Scheme.log(w.D, V, w.bits)
+            codes = orc.pack(orc.log_encode(x, w.bits, T), w.bits)
+        else:
+            P = (w.D + w.vq_width - 1) // w.vq_width
+            cb = np.ascontiguousarray(
+                x[:w.vq_length].reshape(w.vq_length, P, w.vq_width).transpose(1, 0, 2))
+            s = orc.Scheme.vq(w.D, cb)
+            codes = orc.pack(orc.vq_assign(x, w.vq_width, cb), 8)
+        idx = np.arange(inputs.shape[0], dtype=np.int64)
+        csr = [(b.indptr, remap(b.indices)) for b in blocks]
+        t0 = time.perf_counter()
+        orc.gather_dequant(s, codes, idx)
+        for indptr, indices in csr:
+            orc.gather_mean(s, codes, indptr, indices)
+        spent += time.perf_counter() - t0
+        rows_done += inputs.shape[0] + sum(b.E for b in blocks)
+        nb += 1
+        bi += 1
+    return {"value": round(rows_done / spent, 1), "unit": "rows/s", "cores": orc.max_threads(),
+            "kind": "oracle",
+            "sample": f"{nb} single minibatches (gather_dequant of the input rows + gather_mean per "
+                      f"hop), each on a compact sub-table of the rows it touches; "
+                      f"{spent:.1f} s of oracle time"}
+
+
+if __name__ == "__main__":
+    main()

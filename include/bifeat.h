@@ -145,12 +145,12 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
  * For v in [0, V): out[v, :] = mean over e in [indptr[v], indptr[v+1]) of
  * decode(codes[indices[e]]); the list is taken as given (repeats count with
  * multiplicity; a self-loop only if listed); an empty list gives a zero row.
- * indptr: DEVICE int64 [V+1]; indices: DEVICE int64 [indptr[V]];
- * out: DEVICE [V x D] fp32.  fp32 result within 1e-5 * max(|exact|, A_j) of
+ * indptr: DEVICE int64 [V+1]; indices: DEVICE int64 [E], E = indptr[V] (the host
+ * passes E, which also sizes the launch); out: DEVICE [V x D] fp32.  fp32 result within 1e-5 * max(|exact|, A_j) of
  * the exact mean of the decoded values, A_j the largest decodable magnitude in
  * column j.  V = 0 is a no-op. */
 int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
-                       const int64_t *indices, int64_t V, float *out, void *stream);
+                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream);
 
 const char *bifeat_strerror(int status);
 

@@ -59,7 +59,7 @@ _SIGNATURES = {
     "bifeat_gather_dequant": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                         C.c_void_p, C.c_void_p]),
     "bifeat_gather_mean": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
-                                     C.c_int64, C.c_void_p, C.c_void_p]),
+                                     C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_strerror": (C.c_char_p, [C.c_int]),
     "bifeat_set_option": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int]),
 }
@@ -236,5 +236,6 @@ class Quantizer:
         _check(self._lib.bifeat_gather_mean(self._h, _dev_ptr(codes, (torch.uint8,)),
                                             codes.shape[0], _dev_ptr(indptr, (torch.int64,)),
                                             _dev_ptr(indices, (torch.int64,)), V,
+                                            indices.shape[0],
                                             _dev_ptr(out, (torch.float32,)), _stream()))
         return out

@@ -141,6 +141,7 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     if (!strcmp(name, "mean_slots")) p->opt_mean_slots = value;
     else if (!strcmp(name, "mean_blocks")) p->opt_mean_blocks = value;
     else if (!strcmp(name, "mean_generic")) p->opt_mean_generic = value;
+    else if (!strcmp(name, "max_blocks")) p->opt_max_blocks = value;
     else return BIFEAT_EINVAL;
     return BIFEAT_OK;
 }
@@ -321,13 +322,13 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
 }
 
 int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
-                       const int64_t *indices, int64_t V, float *out, void *stream) {
-    if (!p || V < 0 || N < 0) return BIFEAT_EINVAL;
-    if (V > 0 && (!codes || !indptr || !out)) return BIFEAT_EINVAL;
+                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+    if (!p || V < 0 || N < 0 || E < 0) return BIFEAT_EINVAL;
+    if (V > 0 && (!codes || !indptr || !out || (E > 0 && !indices))) return BIFEAT_EINVAL;
     if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
     if (!p->fitted) return BIFEAT_ENOTFIT;
     if (V == 0) return BIFEAT_OK;
-    BF_HIP(bf::launch_gather_mean(p, codes, indptr, indices, V, out, (hipStream_t)stream));
+    BF_HIP(bf::launch_gather_mean(p, codes, indptr, indices, V, E, out, (hipStream_t)stream));
     return BIFEAT_OK;
 }
 

@@ -38,6 +38,7 @@ struct bifeat_params {
     // launch tuning (0 = automatic)
     int opt_mean_slots = 0;
     int opt_mean_blocks = 0;
+    int opt_max_blocks = 0;    // cap on workgroups of the gather kernels
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
 };
 
@@ -58,7 +59,11 @@ hipError_t launch_gather_codes(bifeat_params *p, const uint8_t *codes, const int
 hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                  int64_t M, float *out, hipStream_t s);
 hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                              const int64_t *indices, int64_t V, float *out, hipStream_t s);
+                              const int64_t *indices, int64_t V, int64_t E, float *out,
+                              hipStream_t s);
+void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                             const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
+                             hipStream_t s);
 
 // ---- order-preserving float <-> int keys for atomic min/max
 __host__ __device__ inline int32_t float_key(float f) {
@@ -86,10 +91,10 @@ __device__ inline float4 load4(const __half *p) {
 __device__ inline float load1(const float *p) { return *p; }
 __device__ inline float load1(const __half *p) { return __half2float(*p); }
 
-inline int blocks_for(int64_t threads_needed) {
+inline int blocks_for(int64_t threads_needed, int64_t cap = kMaxBlocks) {
     int64_t b = (threads_needed + kThreads - 1) / kThreads;
     if (b < 1) b = 1;
-    if (b > kMaxBlocks) b = kMaxBlocks;
+    if (b > cap) b = cap;
     return (int)b;
 }
 

@@ -43,11 +43,11 @@ __global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restric
         }
         __syncthreads();
     }
-    const int64_t total = (int64_t)gridDim.x * kThreads;
-    const int64_t rows_per_pass = total / G;
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t < rows_per_pass * G) {
-        const int g = (int)(t % G);
+    const uint32_t total = gridDim.x * kThreads;
+    const uint32_t rows_per_pass = total / (uint32_t)G;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    if (t < rows_per_pass * (uint32_t)G) {
+        const int g = (int)(t % (uint32_t)G);
         float mn[VEC], mx[VEC];
 #pragma unroll
         for (int k = 0; k < VEC; k++) {
@@ -233,11 +233,11 @@ __global__ __launch_bounds__(kThreads) void quantize_sq_kernel(const T *__restri
         for (int i = threadIdx.x; i < coder.H - 1; i += kThreads) s_edges[i] = coder.T[i];
         __syncthreads();
     }
-    const int64_t total = (int64_t)gridDim.x * kThreads;
-    const int64_t rows_per_pass = total / GW;
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t >= rows_per_pass * GW) return;
-    const int g = (int)(t % GW);
+    const uint32_t total = gridDim.x * kThreads;
+    const uint32_t rows_per_pass = total / (uint32_t)GW;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * (uint32_t)GW) return;
+    const int g = (int)(t % (uint32_t)GW);
     const int col0 = 4 * g;
     coder.prepare(ctx, col0, D);
     if constexpr (Coder::kEdges) ctx.edges = s_edges;

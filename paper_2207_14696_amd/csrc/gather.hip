@@ -16,11 +16,11 @@ __global__ __launch_bounds__(kThreads) void gather_codes_kernel(const uint4 *__r
                                                                int rc /* 16B chunks per row */,
                                                                const int64_t *__restrict__ idx,
                                                                int64_t M, uint4 *__restrict__ out) {
-    const int64_t total = (int64_t)gridDim.x * kThreads;
-    const int64_t rows_per_pass = total / rc;
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t >= rows_per_pass * rc) return;
-    const int c = (int)(t % rc);
+    const uint32_t total = gridDim.x * kThreads;
+    const uint32_t rows_per_pass = total / (uint32_t)rc;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * (uint32_t)rc) return;
+    const int c = (int)(t % (uint32_t)rc);
     for (int64_t i = t / rc; i < M; i += rows_per_pass) out[i * rc + c] = codes[idx[i] * rc + c];
 }
 
@@ -44,9 +44,10 @@ __device__ inline uint32_t code_bits4(const uint8_t *row, int g) {
     else return (uint32_t)(row[g >> 1] >> (4 * (g & 1))) & 0xFu;
 }
 
-__device__ inline void store4(float *out, int64_t row, int D, int col0, const float v[4], bool vec) {
+template <bool VEC>
+__device__ inline void store4(float *out, int64_t row, int D, int col0, const float v[4]) {
     float *dst = out + row * D + col0;
-    if (vec) {
+    if constexpr (VEC) {
         *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
     } else {
 #pragma unroll
@@ -58,22 +59,22 @@ __device__ inline void store4(float *out, int64_t row, int D, int col0, const fl
 enum { DEC_UNIFORM = 0, DEC_LOG = 1 };
 
 // scalar codes.  uniform: x' = fma(q, scale_j, min_j); log: x' = V[q] (table in LDS)
-template <int BITS, int DEC>
+template <int BITS, int DEC, bool VEC>
 __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ idx, int64_t M,
-    int D, const float *__restrict__ pa, const float *__restrict__ pb, float *__restrict__ out,
-    int vec) {
+    int D, const float *__restrict__ pa, const float *__restrict__ pb, float *__restrict__ out) {
     __shared__ float s_lut[DEC == DEC_LOG ? (1 << BITS) : 1];
     if constexpr (DEC == DEC_LOG) {
         for (int i = threadIdx.x; i < (1 << BITS); i += kThreads) s_lut[i] = pa[i];
         __syncthreads();
     }
     const int G = (D + 3) / 4;
-    const int64_t total = (int64_t)gridDim.x * kThreads;
-    const int64_t rows_per_pass = total / G;
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t >= rows_per_pass * G) return;
-    const int g = (int)(t % G), col0 = 4 * g;
+    // grids stay below 2^20 workgroups: 32-bit thread ids and divisions
+    const uint32_t total = gridDim.x * kThreads;
+    const uint32_t rows_per_pass = total / (uint32_t)G;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * (uint32_t)G) return;
+    const int g = (int)(t % (uint32_t)G), col0 = 4 * g;
     float mn[4], sc[4];
     if constexpr (DEC == DEC_UNIFORM) {
 #pragma unroll
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
         }
     }
     constexpr uint32_t mask = (1u << BITS) - 1u;
-#pragma unroll 2
+#pragma unroll 4
     for (int64_t i = t / G; i < M; i += rows_per_pass) {
         const uint32_t bits = code_bits4<BITS>(codes + idx[i] * rb, g);
         float v[4];
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
             if constexpr (DEC == DEC_UNIFORM) v[k] = fmaf((float)q, sc[k], mn[k]);
             else v[k] = s_lut[q];
         }
-        store4(out, i, D, col0, v, vec);
+        store4<VEC>(out, i, D, col0, v);
     }
 }
 
@@ -102,13 +103,14 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
 template <bool W4>
 __global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ idx, int64_t M,
-    int D, int w, int len, const float *__restrict__ cb, float *__restrict__ out, int vec) {
+    int D, int w, int len, const float *__restrict__ cb, float *__restrict__ out) {
     const int G = (D + 3) / 4;
-    const int64_t total = (int64_t)gridDim.x * kThreads;
-    const int64_t rows_per_pass = total / G;
-    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t >= rows_per_pass * G) return;
-    const int g = (int)(t % G), col0 = 4 * g;
+    // grids stay below 2^20 workgroups: 32-bit thread ids and divisions
+    const uint32_t total = gridDim.x * kThreads;
+    const uint32_t rows_per_pass = total / (uint32_t)G;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    if (t >= rows_per_pass * (uint32_t)G) return;
+    const int g = (int)(t % (uint32_t)G), col0 = 4 * g;
     int part[4], dim[4];
 #pragma unroll
     for (int k = 0; k < 4; k++) {
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
                 if (col0 + k < D) v[k] = cb[((int64_t)part[k] * len + row[part[k]]) * w + dim[k]];
             }
         }
-        store4(out, i, D, col0, v, vec);
+        store4<W4>(out, i, D, col0, v);
     }
 }
 
@@ -139,19 +141,22 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
     const int D = (int)p->D;
     const int G = (D + 3) / 4;
     const int vec = (D % 4 == 0) && ((uintptr_t)out % 16 == 0);
-    int blocks = blocks_for(M * G);
+    int blocks = blocks_for((M * G + 3) / 4, p->opt_max_blocks > 0 ? p->opt_max_blocks : (1 << 20));
     if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
     const int kind = p->scheme.kind, bits = p->scheme.bits;
     if (kind == BIFEAT_VQ) {
         const int w = p->scheme.vq_width;
         if (w % 4 == 0 && vec)
-            gather_dequant_vq_kernel<true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out, vec);
+            gather_dequant_vq_kernel<true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
         else
-            gather_dequant_vq_kernel<false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out, vec);
+            gather_dequant_vq_kernel<false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
         return hipGetLastError();
     }
-#define BF_GD(B, DEC, A, Bp) \
-    gather_dequant_sq_kernel<B, DEC><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, A, Bp, out, vec)
+#define BF_GD(B, DEC, A, Bp)                                                                             \
+    do {                                                                                                 \
+        if (vec) gather_dequant_sq_kernel<B, DEC, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, A, Bp, out); \
+        else gather_dequant_sq_kernel<B, DEC, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, A, Bp, out);    \
+    } while (0)
     if (kind == BIFEAT_SQ_UNIFORM) {
         switch (bits) {
             case 1: BF_GD(1, DEC_UNIFORM, p->d_min, p->d_scale); break;
