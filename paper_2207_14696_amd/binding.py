@@ -10,7 +10,7 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libbifeat.so")
+_LIB_PATH = os.environ.get("BIFEAT_LIB") or os.path.join(_HERE, "libbifeat.so")
 
 UNIFORM, LOG, VQ = 0, 1, 2
 F32, F16 = 0, 1

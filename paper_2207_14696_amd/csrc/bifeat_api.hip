@@ -142,6 +142,7 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     else if (!strcmp(name, "mean_blocks")) p->opt_mean_blocks = value;
     else if (!strcmp(name, "mean_generic")) p->opt_mean_generic = value;
     else if (!strcmp(name, "max_blocks")) p->opt_max_blocks = value;
+    else if (!strcmp(name, "dequant_flat")) p->opt_dequant_flat = value;
     else return BIFEAT_EINVAL;
     return BIFEAT_OK;
 }

@@ -39,6 +39,7 @@ struct bifeat_params {
     int opt_mean_slots = 0;
     int opt_mean_blocks = 0;
     int opt_max_blocks = 0;    // cap on workgroups of the gather kernels
+    int opt_dequant_flat = 0;  // 1: gather_dequant without the LDS-staged tile kernel
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
 };
 

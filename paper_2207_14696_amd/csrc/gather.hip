@@ -99,6 +99,83 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
     }
 }
 
+// orders this wave's LDS writes before its later LDS reads (all lanes of a wave
+// execute each DS instruction together, in program order)
+__device__ inline void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Tile form of the scalar-code kernel (output rows 16-byte aligned, packed row
+// of at most 64 16-byte chunks).  A wavefront takes RT = 64/c16 consecutive
+// output rows: one 16-byte load per lane fetches their packed rows in whole
+// sectors (sub-dword gathers cost an L2 request per few lanes), the raw codes
+// are parked in LDS, and the tile's output span - contiguous in memory - is
+// written with consecutive 16-byte stores, granule m of the span by lane m%64.
+template <int BITS, int DEC>
+__global__ __launch_bounds__(kThreads) void gather_dequant_tile_kernel(
+    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int D,
+    const float *__restrict__ pa, const float *__restrict__ pb, float *__restrict__ out) {
+    extern __shared__ uint32_t smem[];
+    constexpr int kLut = 1 << BITS;
+    const int npar = DEC == DEC_UNIFORM ? 2 * D : kLut;  // D % 4 == 0 here
+    float *s_par = reinterpret_cast<float *>(smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4 *raw = reinterpret_cast<uint4 *>(smem + ((npar + 3) & ~3)) + wave * 64;
+    for (int i = threadIdx.x; i < npar; i += kThreads) {
+        if constexpr (DEC == DEC_UNIFORM) s_par[i] = i < D ? pb[i] : pa[i - D];  // [scale | min]
+        else s_par[i] = pa[i];
+    }
+    __syncthreads();
+
+    const int RT = 64 / c16;
+    const int r = lane / c16, c = lane - r * c16;
+    const int nf4 = D >> 2;
+    const int step_d = 64 / nf4, step_f = 64 % nf4;
+    const int lane_d = lane / nf4, lane_f = lane % nf4;
+    const int rb = c16 * 16;
+    const int64_t tiles = (M + RT - 1) / RT;
+    const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < tiles; tile += n_waves) {
+        const int64_t row0 = tile * RT;
+        const int nrow = (int)min((int64_t)RT, M - row0);
+        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * c16 + c];  // lane = r*c16 + c
+        wave_sync();
+        float4 *span = reinterpret_cast<float4 *>(out + row0 * D);
+        const int ngran = nrow * nf4;
+        int d = lane_d, f = lane_f;
+#pragma unroll 2
+        for (int m = lane; m < ngran; m += 64) {
+            const uint8_t *rowp = reinterpret_cast<const uint8_t *>(raw) + d * rb;
+            const uint32_t bits = code_bits4<BITS>(rowp, f);
+            float4 v;
+            if constexpr (DEC == DEC_UNIFORM) {
+                const float4 a = *reinterpret_cast<const float4 *>(s_par + 4 * f);
+                const float4 b = *reinterpret_cast<const float4 *>(s_par + D + 4 * f);
+                v.x = fmaf((float)(bits & mask), a.x, b.x);
+                v.y = fmaf((float)((bits >> BITS) & mask), a.y, b.y);
+                v.z = fmaf((float)((bits >> (2 * BITS)) & mask), a.z, b.z);
+                v.w = fmaf((float)((bits >> (3 * BITS)) & mask), a.w, b.w);
+            } else {
+                v.x = s_par[bits & mask];
+                v.y = s_par[(bits >> BITS) & mask];
+                v.z = s_par[(bits >> (2 * BITS)) & mask];
+                v.w = s_par[(bits >> (3 * BITS)) & mask];
+            }
+            span[m] = v;
+            d += step_d;
+            f += step_f;
+            if (f >= nf4) {
+                f -= nf4;
+                d++;
+            }
+        }
+        wave_sync();  // raw is rewritten by the next tile
+    }
+}
+
 // vector codes: columns 4g..4g+3 of part p = col / w come from entry q = row[p]
 template <bool W4>
 __global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
@@ -152,7 +229,36 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
             gather_dequant_vq_kernel<false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
         return hipGetLastError();
     }
-#define BF_GD(B, DEC, A, Bp)                                                                             \
+    const int c16 = (int)(p->rb / 16);
+    if (vec && c16 <= 64 && !p->opt_dequant_flat) {
+        const int RT = 64 / c16;
+        const int64_t tiles = (M + RT - 1) / RT;
+        const int64_t cap = p->opt_max_blocks > 0 ? p->opt_max_blocks : (1 << 16);
+        int64_t want = (tiles + 3) / 4;
+        const int tb = (int)(want < cap ? want : cap);
+        const int npar = kind == BIFEAT_SQ_UNIFORM ? 2 * D : (1 << bits);
+        const size_t shm = sizeof(uint32_t) * (size_t)((npar + 3) & ~3) + (size_t)(kThreads / 64) * 64 * 16;
+#define BF_GT(B, DEC, A, Bp) \
+    gather_dequant_tile_kernel<B, DEC><<<tb, kThreads, shm, s>>>((const uint4 *)codes, c16, idx, M, D, A, Bp, out)
+        if (kind == BIFEAT_SQ_UNIFORM) {
+            switch (bits) {
+                case 1: BF_GT(1, DEC_UNIFORM, p->d_min, p->d_scale); break;
+                case 2: BF_GT(2, DEC_UNIFORM, p->d_min, p->d_scale); break;
+                case 4: BF_GT(4, DEC_UNIFORM, p->d_min, p->d_scale); break;
+                default: BF_GT(8, DEC_UNIFORM, p->d_min, p->d_scale); break;
+            }
+        } else {
+            switch (bits) {
+                case 1: BF_GT(1, DEC_LOG, p->d_V, nullptr); break;
+                case 2: BF_GT(2, DEC_LOG, p->d_V, nullptr); break;
+                case 4: BF_GT(4, DEC_LOG, p->d_V, nullptr); break;
+                default: BF_GT(8, DEC_LOG, p->d_V, nullptr); break;
+            }
+        }
+#undef BF_GT
+        return hipGetLastError();
+    }
+#define BF_GD(B, DEC, A, Bp)                                                                        \
     do {                                                                                                 \
         if (vec) gather_dequant_sq_kernel<B, DEC, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, A, Bp, out); \
         else gather_dequant_sq_kernel<B, DEC, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, A, Bp, out);    \

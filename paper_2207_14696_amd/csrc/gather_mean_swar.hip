@@ -79,6 +79,9 @@ __device__ inline void wave_sync() {
 enum : uint32_t { F_SKIP = 1u, F_MORE = 2u, F_PREV = 4u, F_EMPTY = 8u };
 
 constexpr int kWaves = kThreads / 64;
+#ifndef BF_SWAR_U
+#define BF_SWAR_U 4
+#endif
 
 template <int BITS, int CW, bool VEC>
 __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
     constexpr int R0 = CW * W::kN0, R1 = CW * W::kN1;
     constexpr int CPW = 32 / BITS;  // codes per word
     constexpr int CPL = CW * CPW;   // columns per lane
-    constexpr int U = 4;            // neighbour rows in flight per lane
+    constexpr int U = BF_SWAR_U < W::kCap0 ? BF_SWAR_U : W::kCap0;  // neighbour rows in flight per lane
     constexpr uint32_t FMAX1 = (1u << W::kF1) - 1u;
     static_assert(W::kCap0 >= U, "a lane must be able to add U rows between folds");
 
@@ -181,7 +184,12 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                         for (int u = 0; u < U; u++)
                             row[u] = indices[min(e + (int64_t)u * S, rend - 1)];
 #pragma unroll
+#ifdef BF_ABL_NO_ROWS
+                        for (int u = 0; u < U; u++)
+                            for (int k = 0; k < CW; k++) w[u][k] = (uint32_t)row[u] + k;
+#else
                         for (int u = 0; u < U; u++) load_words<CW>(cptr + row[u] * rb, w[u]);
+#endif
 #pragma unroll
                         for (int u = 0; u < U; u++) {
                             const uint32_t keep = (chunk_ok && e + (int64_t)u * S < rend) ? ~0u : 0u;
@@ -301,7 +309,11 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                                     val = make_float4(__uint_as_float(sum[0]), __uint_as_float(sum[1]),
                                                       __uint_as_float(sum[2]), __uint_as_float(sum[3]));
                             }
+#ifdef BF_ABL_NO_OUTPUT
+                            if (write && val.x == 1.2345e-30f) *dst = val;
+#else
                             if (write) *dst = val;
+#endif
                         };
                         const int n_it = (ndst * nf4 + 63) >> 6;
                         int d = lane_d, f = lane_f;

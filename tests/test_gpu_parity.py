@@ -174,8 +174,12 @@ def test_gather_codes_and_dequant(bf, torch, kind, bits, D):
     idx[:3] = [0, codes.shape[0] - 1, 0]
     didx = torch.from_numpy(idx).cuda()
     assert np.array_equal(q.gather_codes(dcodes, didx).cpu().numpy(), orc.gather_codes(codes, idx))
-    got = q.gather_dequant(dcodes, didx).cpu().numpy()
-    assert_close(got, orc.gather_dequant(s, codes, idx), s, "gather_dequant")
+    want = orc.gather_dequant(s, codes, idx)
+    assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant")
+    if kind != "vq":            # both forms of the scalar kernel (LDS-staged tiles / flat)
+        q.set_option("dequant_flat", 1)
+        assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant flat")
+        q.set_option("dequant_flat", 0)
     # empty request
     empty = torch.empty(0, dtype=torch.int64, device="cuda")
     assert q.gather_dequant(dcodes, empty).shape == (0, D)
