@@ -50,16 +50,6 @@ def parse_args():
     return ap.parse_args()
 
 
-def concat_blocks(blocks):
-    """Concatenate the CSR blocks of several minibatches into one launch."""
-    indptr = [np.zeros(1, np.int64)]
-    off = 0
-    for b in blocks:
-        indptr.append(b.indptr[1:] + off)
-        off += b.E
-    return np.concatenate(indptr), np.concatenate([b.indices for b in blocks])
-
-
 def traffic_from_profile(workload: str, kernel: str):
     """HBM bytes per launch of a kernel, from the committed rocprofv3 --pmc
     summary for this workload (None if there is none)."""
@@ -79,14 +69,13 @@ def main():
 
     import torch
     import paper_2207_14696_amd as bf
-    from bifeat_inputs import WORKLOADS, make_graph, draw_seeds, sample_blocks, feature_rows
+    from bifeat_inputs import WORKLOADS, BATCHES_PER_STEP, make_graph, launch_set, feature_rows
     from bifeat_inputs.device import DeviceTable
 
     w = WORKLOADS[args.workload]
     if args.rows:
         w = w.scaled(args.rows)
-    L = args.batches_per_step or {"tiny": 64, "mid": 64, "large": 8, "largest1": 32,
-                                  "largest4": 32, "vq": 8}[w.name.split("@")[0]]
+    L = args.batches_per_step or BATCHES_PER_STEP[w.name.split("@")[0]]
     B = args.batches or 8
     torch.cuda.set_device(0)
     dev = "cuda"
@@ -148,17 +137,8 @@ def main():
     # ------------------------------------------------- pre-sampled launch-sets
     g = make_graph(w)
     sets = []
-    for s in range(B):
-        mbs = []
-        for l in range(L):
-            bi = s * L + l
-            seeds = draw_seeds(g, w.batch, w.seed, bi, w.seed_mode)
-            mbs.append(sample_blocks(g, seeds, w.fanouts, w.seed, bi))
-        hops = []
-        for h in range(len(w.fanouts)):
-            indptr, indices = concat_blocks([mb[0][h] for mb in mbs])
-            hops.append((indptr, indices))
-        inputs = np.concatenate([mb[1] for mb in mbs])
+    for si in range(B):
+        hops, inputs = launch_set(w, g, si, L)
         sets.append({"hops": hops, "inputs": inputs})
     for s in sets:
         s["d_inputs"] = torch.from_numpy(s["inputs"]).to(dev)

@@ -59,3 +59,30 @@ def make_graph(w: Workload):
     if w.graph == "uniform":
         return UniformGraph(w.N, int(w.avg_degree), w.seed)
     return PowerLawGraph(w.N, w.avg_degree, 2.1, w.cap, w.seed)
+
+
+# minibatches concatenated into one launch by default (what a prefetching
+# loader hands over); 1 = a single minibatch per launch
+BATCHES_PER_STEP = {"tiny": 64, "mid": 64, "large": 8, "largest1": 32, "largest4": 32, "vq": 8}
+
+
+def launch_set(w: Workload, graph, set_index: int, L: int):
+    """Launch-set ``set_index``: L independently sampled minibatches with their
+    per-hop CSR blocks concatenated (destinations of all minibatches one after
+    the other) and their input-node lists concatenated.
+    Returns (hops, inputs): hops[h] = (indptr int64 [V+1], indices int64 [E])."""
+    import numpy as np
+    from .graphs import draw_seeds, sample_blocks
+    mbs = []
+    for l in range(L):
+        bi = set_index * L + l
+        seeds = draw_seeds(graph, w.batch, w.seed, bi, w.seed_mode)
+        mbs.append(sample_blocks(graph, seeds, w.fanouts, w.seed, bi))
+    hops = []
+    for h in range(len(w.fanouts)):
+        ptr, off = [np.zeros(1, np.int64)], 0
+        for blocks, _ in mbs:
+            ptr.append(blocks[h].indptr[1:] + off)
+            off += blocks[h].E
+        hops.append((np.concatenate(ptr), np.concatenate([b[h].indices for b, _ in mbs])))
+    return hops, np.concatenate([inp for _, inp in mbs])

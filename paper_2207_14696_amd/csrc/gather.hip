@@ -164,7 +164,14 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_tile_kernel(
                 v.z = s_par[(bits >> (2 * BITS)) & mask];
                 v.w = s_par[(bits >> (3 * BITS)) & mask];
             }
+#ifdef BF_NT_STORE
+            __builtin_nontemporal_store(v.x, &span[m].x);
+            __builtin_nontemporal_store(v.y, &span[m].y);
+            __builtin_nontemporal_store(v.z, &span[m].z);
+            __builtin_nontemporal_store(v.w, &span[m].w);
+#else
             span[m] = v;
+#endif
             d += step_d;
             f += step_f;
             if (f >= nf4) {

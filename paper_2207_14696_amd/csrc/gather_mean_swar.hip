@@ -79,12 +79,15 @@ __device__ inline void wave_sync() {
 enum : uint32_t { F_SKIP = 1u, F_MORE = 2u, F_PREV = 4u, F_EMPTY = 8u };
 
 constexpr int kWaves = kThreads / 64;
+#ifndef BF_SWAR_WPE
+#define BF_SWAR_WPE 4
+#endif
 #ifndef BF_SWAR_U
 #define BF_SWAR_U 4
 #endif
 
 template <int BITS, int CW, bool VEC>
-__global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
+__global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
     const float *__restrict__ sc, float *__restrict__ out, int lpr_log2, int s_log2, int chunks,
@@ -123,6 +126,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
     const int lane_d = lane / nf4, lane_f = lane % nf4;
     const int lane_chunk = lane & (LPR - 1);
     const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+    const bool multi_seg = chunks > LPR;  // packed row longer than one pass of LPR lanes
 
     for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += n_waves) {
         const int64_t v_tile = tile << dpw_log2;
@@ -168,70 +172,83 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                 do {
                     const int64_t rbeg = beg + (int64_t)round * W::kCap1;
                     const int64_t rend = min(end, rbeg + (int64_t)W::kCap1);
-                    uint32_t l0[R0], l1[R1];
+                    uint32_t l1[R1];
+                    // kFold = false: no lane adds more than kCap0 rows, level 1 is only
+                    // formed after the loop (and its registers are free during it)
+                    auto accumulate = [&](auto fold_tag) {
+                        constexpr bool kFold = decltype(fold_tag)::value;
+                        uint32_t l0[R0];
 #pragma unroll
-                    for (int r = 0; r < R0; r++) l0[r] = 0u;
+                        for (int r = 0; r < R0; r++) l0[r] = 0u;
+                        if constexpr (kFold) {
 #pragma unroll
-                    for (int r = 0; r < R1; r++) l1[r] = 0u;
-                    int cnt = 0;
-                    for (int64_t e = rbeg + slot; e < rend; e += (int64_t)U * S) {
-                        // branch-free: out-of-range slots re-read the list's last row
-                        // and are masked, so all U index loads, then all U row loads,
-                        // are in flight together
-                        uint32_t w[U][CW];
-                        int64_t row[U];
-#pragma unroll
-                        for (int u = 0; u < U; u++)
-                            row[u] = indices[min(e + (int64_t)u * S, rend - 1)];
-#pragma unroll
-#ifdef BF_ABL_NO_ROWS
-                        for (int u = 0; u < U; u++)
-                            for (int k = 0; k < CW; k++) w[u][k] = (uint32_t)row[u] + k;
-#else
-                        for (int u = 0; u < U; u++) load_words<CW>(cptr + row[u] * rb, w[u]);
-#endif
-#pragma unroll
-                        for (int u = 0; u < U; u++) {
-                            const uint32_t keep = (chunk_ok && e + (int64_t)u * S < rend) ? ~0u : 0u;
-#pragma unroll
-                            for (int k = 0; k < CW; k++) w[u][k] &= keep;
+                            for (int r = 0; r < R1; r++) l1[r] = 0u;
                         }
-                        if constexpr (kTwoLevel) {
-                            if (cnt + U > W::kCap0) {  // fold level 0 into level 1
+                        int cnt = 0;
+                        for (int64_t e = rbeg + slot; e < rend; e += (int64_t)U * S) {
+                            // branch-free: out-of-range slots re-read the list's last row
+                            // and are masked, so all U index loads, then all U row loads,
+                            // are in flight together
+                            uint32_t w[U][CW];
+                            int64_t row[U];
+#pragma unroll
+                            for (int u = 0; u < U; u++)
+                                row[u] = indices[min(e + (int64_t)u * S, rend - 1)];
+#pragma unroll
+                            for (int u = 0; u < U; u++) load_words<CW>(cptr + row[u] * rb, w[u]);
+#pragma unroll
+                            for (int u = 0; u < U; u++) {
+                                const uint32_t keep = (chunk_ok && e + (int64_t)u * S < rend) ? ~0u : 0u;
+#pragma unroll
+                                for (int k = 0; k < CW; k++) w[u][k] &= keep;
+                            }
+                            if constexpr (kFold) {
+                                if (cnt + U > W::kCap0) {  // fold level 0 into level 1
+#pragma unroll
+                                    for (int k = 0; k < CW; k++)
+#pragma unroll
+                                        for (int i = 0; i < W::kN0; i++) {
+                                            const uint32_t a = l0[k * W::kN0 + i];
+                                            l1[k * W::kN1 + i] += a & W::kMask1;
+                                            l1[k * W::kN1 + W::kN0 + i] += (a >> W::kF0) & W::kMask1;
+                                            l0[k * W::kN0 + i] = 0u;
+                                        }
+                                    cnt = 0;
+                                }
+                                cnt += U;
+                            }
+#pragma unroll
+                            for (int u = 0; u < U; u++)
 #pragma unroll
                                 for (int k = 0; k < CW; k++)
 #pragma unroll
-                                    for (int i = 0; i < W::kN0; i++) {
-                                        const uint32_t a = l0[k * W::kN0 + i];
-                                        l1[k * W::kN1 + i] += a & W::kMask1;
-                                        l1[k * W::kN1 + W::kN0 + i] += (a >> W::kF0) & W::kMask1;
-                                        l0[k * W::kN0 + i] = 0u;
-                                    }
-                                cnt = 0;
-                            }
+                                    for (int i = 0; i < W::kN0; i++)
+                                        l0[k * W::kN0 + i] += (w[u][k] >> (BITS * i)) & W::kMask0;
                         }
-                        cnt += U;
-#pragma unroll
-                        for (int u = 0; u < U; u++)
+                        if constexpr (kTwoLevel) {
 #pragma unroll
                             for (int k = 0; k < CW; k++)
 #pragma unroll
-                                for (int i = 0; i < W::kN0; i++)
-                                    l0[k * W::kN0 + i] += (w[u][k] >> (BITS * i)) & W::kMask0;
-                    }
-                    if constexpr (kTwoLevel) {
+                                for (int i = 0; i < W::kN0; i++) {
+                                    const uint32_t a = l0[k * W::kN0 + i];
+                                    const uint32_t lo = a & W::kMask1, hi = (a >> W::kF0) & W::kMask1;
+                                    if constexpr (kFold) {
+                                        l1[k * W::kN1 + i] += lo;
+                                        l1[k * W::kN1 + W::kN0 + i] += hi;
+                                    } else {
+                                        l1[k * W::kN1 + i] = lo;
+                                        l1[k * W::kN1 + W::kN0 + i] = hi;
+                                    }
+                                }
+                        } else {
 #pragma unroll
-                        for (int k = 0; k < CW; k++)
-#pragma unroll
-                            for (int i = 0; i < W::kN0; i++) {
-                                const uint32_t a = l0[k * W::kN0 + i];
-                                l1[k * W::kN1 + i] += a & W::kMask1;
-                                l1[k * W::kN1 + W::kN0 + i] += (a >> W::kF0) & W::kMask1;
-                            }
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < R1; r++) l1[r] = l0[r];
-                    }
+                            for (int r = 0; r < R1; r++) l1[r] = l0[r];
+                        }
+                    };
+                    if (!kTwoLevel || __all(rend - rbeg <= (int64_t)W::kCap0 * S))
+                        accumulate(std::false_type{});
+                    else
+                        accumulate(std::true_type{});
                     for (int st = LPR; st < G; st <<= 1)
 #pragma unroll
                         for (int r = 0; r < R1; r++) l1[r] += (uint32_t)__shfl_xor((int)l1[r], st);
@@ -258,12 +275,13 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                         // one float4 granule (row d, granule f) of the tile's output span.
                         // Loads are unconditional (clamped in range) so that consecutive
                         // granules overlap their LDS latency; only the store is predicated.
-                        auto granule = [&](int d, int f, auto rounds_tag) {
+                        float4 *span = reinterpret_cast<float4 *>(out + vbase * D);
+                        auto granule = [&](int m, int d, int f, auto rounds_tag) {
                             constexpr bool kRounds = decltype(rounds_tag)::value;
                             const bool in = d < ndst;
                             const int dd = in ? d : 0;
                             const int j0 = 4 * f;
-                            const bool seg = j0 >= col_lo && j0 < col_lo + LPR * CPL;
+                            const bool seg = !multi_seg || (j0 >= col_lo && j0 < col_lo + LPR * CPL);
                             const int jl = seg ? j0 - col_lo : 0;
                             const float2 md = meta[dd];
                             const uint32_t fl = __float_as_uint(md.y);
@@ -288,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                             const float4 a = *reinterpret_cast<const float4 *>(s_sc + j0);
                             const float4 b = *reinterpret_cast<const float4 *>(s_mn + j0);
                             const bool write = in && seg && !(fl & F_SKIP);
-                            float4 *dst = reinterpret_cast<float4 *>(out + (vbase + dd) * D + j0);
+                            float4 *dst = span + (in ? m : 0);  // granule m of the tile's contiguous span
                             if constexpr (kRounds) {
                                 if (write && (fl & F_PREV)) {
                                     const float4 pv = *dst;
@@ -320,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                         if (mode == 0) {  // short lists: never in rounds
 #pragma unroll 2
                             for (int it = 0; it < n_it; it++) {
-                                granule(d, f, std::false_type{});
+                                granule(lane + 64 * it, d, f, std::false_type{});
                                 d += step_d;
                                 f += step_f;
                                 if (f >= nf4) {
@@ -330,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_swar_kernel(
                             }
                         } else {
                             for (int it = 0; it < n_it; it++) {
-                                granule(d, f, std::true_type{});
+                                granule(lane + 64 * it, d, f, std::true_type{});
                                 d += step_d;
                                 f += step_f;
                                 if (f >= nf4) {

@@ -1,0 +1,203 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py
+times (L minibatches per launch, whole blocks).
+
+The tables are far too large for the oracle to sweep (up to 187 G values), so:
+  * fitted per-column min/max are checked against torch.amin/amax over the same
+    chunks (an independent routine), their witness rows are regenerated on the
+    host (attainment) and every sampled row is checked to lie inside (bound);
+    the workloads small enough (tiny, mid) also get the oracle's full fit;
+  * scale / inv derived from them must equal the oracle's bit for bit;
+  * for a sample of destinations of the outermost block, and a sample of input
+    rows, the oracle regenerates exactly the table rows involved, encodes them
+    itself, and its packed rows / decoded rows / means are compared with what
+    the GPU produced from its resident table (codes bit-exact, floats 1e-5).
+"""
+import numpy as np
+import pytest
+
+import oracle as orc
+from bifeat_inputs import (WORKLOADS, BATCHES_PER_STEP, make_graph, launch_set, feature_rows,
+                           feature_chunk)
+from helpers import assert_close, scheme_of
+
+pytestmark = pytest.mark.gpu
+
+CHUNK = 1 << 20
+N_DST_SAMPLE = 192
+N_ROW_SAMPLE = 1024
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    return t
+
+
+def _stream_table(torch, w, quantizers, fit):
+    """Generate the table chunk by chunk on the GPU; fit (optionally) and
+    quantize with every quantizer in ``quantizers``.  Returns
+    (codes per quantizer, torch min, torch max, witness rows of min / max)."""
+    from bifeat_inputs.device import DeviceTable
+    table = DeviceTable(w.spec)
+    buf = torch.empty((min(CHUNK, w.N), w.D), dtype=table.torch_dtype, device="cuda")
+    tmin = tmax = amin = amax = None
+    if fit:
+        for q in quantizers:
+            q.fit_reset()
+        for r0 in range(0, w.N, CHUNK):
+            n = min(CHUNK, w.N - r0)
+            x = table.chunk(r0, n, buf[:n])
+            for q in quantizers:
+                q.fit_update(x)
+            lo, ilo = x.min(dim=0)
+            hi, ihi = x.max(dim=0)
+            if tmin is None:
+                tmin, tmax, amin, amax = lo.clone(), hi.clone(), ilo + r0, ihi + r0
+            else:
+                sel = lo < tmin
+                tmin, amin = torch.where(sel, lo, tmin), torch.where(sel, ilo + r0, amin)
+                sel = hi > tmax
+                tmax, amax = torch.where(sel, hi, tmax), torch.where(sel, ihi + r0, amax)
+        for q in quantizers:
+            q.fit_finalize()
+    codes = [torch.empty((w.N, q.row_bytes), dtype=torch.uint8, device="cuda") for q in quantizers]
+    for r0 in range(0, w.N, CHUNK):
+        n = min(CHUNK, w.N - r0)
+        x = table.chunk(r0, n, buf[:n])
+        for q, c in zip(quantizers, codes):
+            q.quantize(x, c, r0)
+    torch.cuda.synchronize()
+    del buf
+    if fit:
+        return codes, tmin.float().cpu().numpy(), tmax.float().cpu().numpy(), \
+            amin.cpu().numpy(), amax.cpu().numpy()
+    return codes, None, None, None, None
+
+
+def _check_uniform_params(w, q, tmin, tmax, amin, amax):
+    mn, mx, scale, inv = q.params_get_uniform()
+    tmin = np.where(tmin == 0, np.float32(0), tmin)
+    tmax = np.where(tmax == 0, np.float32(0), tmax)
+    assert np.array_equal(mn, tmin) and np.array_equal(mx, tmax)
+    # attainment: the witness rows, regenerated on the host, hold min / max
+    cols = np.arange(w.D)
+    assert np.array_equal(feature_rows(w.spec, amin).astype(np.float32)[cols, cols], mn)
+    assert np.array_equal(feature_rows(w.spec, amax).astype(np.float32)[cols, cols], mx)
+    oscale, oinv = orc.uniform_params(mn, mx, w.bits)
+    assert np.array_equal(scale.view(np.uint32), oscale.view(np.uint32))
+    assert np.array_equal(inv.view(np.uint32), oinv.view(np.uint32))
+    if w.N * w.D <= 300_000_000:      # the oracle can sweep this one whole
+        omn = omx = None
+        for r0 in range(0, w.N, 400_000):
+            omn, omx = orc.fit_minmax(feature_chunk(w.spec, r0, min(400_000, w.N - r0)), omn, omx)
+        assert np.array_equal(omn, mn) and np.array_equal(omx, mx)
+    return mn, mx, scale, inv
+
+
+def _oracle_rows(w, rows, encode):
+    """Packed oracle sub-table for the sorted unique row ids ``rows``."""
+    x = feature_rows(w.spec, rows).astype(np.float32)
+    return x, encode(x)
+
+
+def _run_iteration_checks(torch, w, q, codes, s_of, encode, bound=None):
+    """The per-iteration calls as bench.py launches them, checked on samples."""
+    g = make_graph(w)
+    L = BATCHES_PER_STEP[w.name]
+    hops, inputs = launch_set(w, g, 0, L)
+    rng = np.random.default_rng(0)
+    d_inputs = torch.from_numpy(inputs).cuda()
+    feats = q.gather_dequant(codes, d_inputs)
+    rows_codes = q.gather_codes(codes, d_inputs)
+    outs = []
+    for indptr, indices in hops:
+        outs.append(q.gather_mean(codes, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()))
+    torch.cuda.synchronize()
+
+    # ---- sampled input rows: packed bytes bit-exact, decoded rows within tolerance
+    pick = np.sort(rng.choice(inputs.shape[0], size=min(N_ROW_SAMPLE, inputs.shape[0]), replace=False))
+    uniq, inv_map = np.unique(inputs[pick], return_inverse=True)
+    x, ocodes = _oracle_rows(w, uniq, encode)
+    if bound is not None:
+        assert np.all(x >= bound[0][None, :]) and np.all(x <= bound[1][None, :])
+    s = s_of()
+    dpick = torch.from_numpy(pick).cuda()
+    assert np.array_equal(rows_codes[dpick].cpu().numpy(), ocodes[inv_map])
+    assert_close(feats[dpick].cpu().numpy(), orc.gather_dequant(s, ocodes, inv_map), s,
+                 f"{w.name} gather_dequant")
+
+    # ---- sampled destinations of every hop's block
+    for h, (indptr, indices) in enumerate(hops):
+        V = indptr.shape[0] - 1
+        deg = np.diff(indptr)
+        dst = rng.choice(V, size=min(N_DST_SAMPLE, V), replace=False)
+        dst = np.unique(np.concatenate([dst, [0, V - 1, int(deg.argmax()), int(deg.argmin())]]))
+        lists = [indices[indptr[v]:indptr[v + 1]] for v in dst]
+        uniq = np.unique(np.concatenate(lists))
+        x, ocodes = _oracle_rows(w, uniq, encode)
+        sub_ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int64)
+        sub_idx = np.searchsorted(uniq, np.concatenate(lists)).astype(np.int64)
+        want = orc.gather_mean(s, ocodes, sub_ptr, sub_idx)
+        got = outs[h][torch.from_numpy(dst).cuda()].cpu().numpy()
+        assert_close(got, want, s, f"{w.name} gather_mean hop {h}")
+
+
+def _uniform_case(torch, bf, names):
+    ws = [WORKLOADS[n] for n in names]
+    qs = [bf.Quantizer(scheme_of("uniform", w.bits), w.D) for w in ws]
+    codes, tmin, tmax, amin, amax = _stream_table(torch, ws[0], qs, fit=True)
+    for w, q, c in zip(ws, qs, codes):
+        mn, mx, scale, inv = _check_uniform_params(w, q, tmin, tmax, amin, amax)
+        _run_iteration_checks(
+            torch, w, q, c,
+            s_of=lambda: orc.Scheme.uniform(mn, scale, w.bits),
+            encode=lambda x: orc.pack(orc.uniform_encode(x, w.bits, mn, inv), w.bits),
+            bound=(mn, mx))
+    del codes
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def bf():
+    import paper_2207_14696_amd as m
+    m.load_library()
+    return m
+
+
+def test_tiny_8bit(torch, bf):
+    _uniform_case(torch, bf, ["tiny"])
+
+
+def test_mid_4bit(torch, bf):
+    _uniform_case(torch, bf, ["mid"])
+
+
+@pytest.mark.timeout(600)
+def test_large_2bit(torch, bf):
+    _uniform_case(torch, bf, ["large"])
+
+
+@pytest.mark.timeout(900)
+def test_largest_1bit_and_4bit(torch, bf):
+    # one table, two packed forms built from the same two generation passes
+    _uniform_case(torch, bf, ["largest1", "largest4"])
+
+
+@pytest.mark.timeout(900)
+def test_vq_96x256(torch, bf):
+    w = WORKLOADS["vq"]
+    # codebooks: the oracle's 10-round Lloyd k-means on a seeded uniform row sample
+    from bifeat_inputs.features import mix64, stream_key, STREAM_MISC
+    ids = (mix64(stream_key(w.seed, STREAM_MISC) + np.arange(4096, dtype=np.uint64))
+           % np.uint64(w.N)).astype(np.int64)
+    cb, dist = orc.vq_train(feature_rows(w.spec, ids).astype(np.float32), w.vq_width, w.vq_length, 10)
+    assert np.all(np.diff(dist) <= 1e-9 * dist[0])
+    q = bf.Quantizer(scheme_of("vq", 8, w.vq_width, w.vq_length), w.D)
+    q.params_set_codebooks(cb)
+    (codes,), *_ = _stream_table(torch, w, [q], fit=False)
+    _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.vq(w.D, cb),
+        encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb), 8))
+    del codes
+    torch.cuda.empty_cache()
