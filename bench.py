@@ -53,7 +53,7 @@ def parse_args():
 def traffic_from_profile(workload: str, kernel: str):
     """HBM bytes per launch of a kernel, from the committed rocprofv3 --pmc
     summary for this workload (None if there is none)."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.md")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}.md")
     if not os.path.exists(path):
         return None
     m = re.search(r"^traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), re.M)

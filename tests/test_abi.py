@@ -1,0 +1,76 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "bifeat.h")
+
+
+@pytest.fixture(scope="module")
+def bf():
+    import paper_2207_14696_amd as m
+    if not os.path.exists(m.library_path()):
+        from paper_2207_14696_amd.build import build
+        build()
+    m.load_library()
+    return m
+
+
+def test_every_declared_symbol_is_exported(bf):
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    names = set(re.findall(r"\b(bifeat_[a-z_]+)\s*\(", text))
+    assert {"bifeat_quantize", "bifeat_gather_dequant", "bifeat_gather_mean", "bifeat_gather_codes",
+            "bifeat_fit_update", "bifeat_params_create"} <= names
+    lib = C.CDLL(bf.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_sizes_and_scheme_validation(bf):
+    q = bf.Quantizer(bf.Scheme(bf.UNIFORM, 4), 100)
+    assert (q.row_bytes, q.codes_per_row) == (64, 100)
+    assert bf.Quantizer(bf.Scheme(bf.UNIFORM, 2), 128).row_bytes == 32
+    assert bf.Quantizer(bf.Scheme(bf.LOG, 1), 768).row_bytes == 96
+    v = bf.Quantizer(bf.Scheme(bf.VQ, 8, 8, 256), 768)
+    assert (v.row_bytes, v.codes_per_row) == (96, 96)
+    for bad in [bf.Scheme(bf.UNIFORM, 3), bf.Scheme(bf.LOG, 16), bf.Scheme(bf.VQ, 8, 0, 256),
+                bf.Scheme(bf.VQ, 8, 8, 1000), bf.Scheme(7, 4)]:
+        with pytest.raises(bf.BifeatError) as e:
+            bf.Quantizer(bad, 100)
+        assert e.value.status == -1
+    with pytest.raises(bf.BifeatError):
+        bf.Quantizer(bf.Scheme(bf.UNIFORM, 4), 0)
+
+
+def test_argument_errors_come_before_any_gpu_call(bf):
+    lib = bf.load_library()
+    q = bf.Quantizer(bf.Scheme(bf.UNIFORM, 4), 16)
+    h = q._h
+    # null / negative arguments: EINVAL; unfitted parameters: ENOTFIT (no device needed)
+    assert lib.bifeat_gather_dequant(h, None, 10, None, 5, None, None) == -1
+    assert lib.bifeat_gather_dequant(h, None, 10, None, -1, None, None) == -1
+    assert lib.bifeat_gather_mean(h, None, 10, None, None, 3, 7, None, None) == -1
+    assert lib.bifeat_quantize(h, None, 0, 4, None, 0, None) == -1
+    assert lib.bifeat_quantize(h, None, 9, 0, None, 0, None) == -1           # bad dtype
+    assert lib.bifeat_fit_update(h, None, 0, 5, None) == -1
+    assert lib.bifeat_gather_dequant(h, 16, 10, 16, 5, 16, None) == -2       # aligned dummies, not fitted
+    assert lib.bifeat_gather_dequant(h, 8, 10, 16, 5, 16, None) == -1        # misaligned table
+    assert lib.bifeat_set_option(h, b"no_such_option", 1) == -1
+    assert lib.bifeat_set_option(h, b"mean_slots", 4) == 0
+    assert lib.bifeat_row_bytes(None) == -1
+    assert lib.bifeat_strerror(-2) == b"quantizer parameters not fitted"
+    with pytest.raises(bf.BifeatError):
+        q.params_get_uniform()
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2207_14696_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "__init__.py" and "no CPU fallback" in text, f
