@@ -160,6 +160,8 @@ def main():
         for h, (dp, di) in enumerate(s["d_hops"]):
             if timed is not None and h == outer:
                 timed[2].record()
+            # the sampler's contract: no list of hop h is longer than its fan-out
+            q.set_option("mean_max_degree", w.fanouts[h])
             q.gather_mean(codes, dp, di, out_h[h][:dp.shape[0] - 1])
         if timed is not None:
             timed[3].record()

@@ -45,8 +45,11 @@ int ensure_device(bifeat_params *p) {
     else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 2; }
     else nfloat = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
     nfloat = (nfloat + 3) / 4 * 4;
+    nfit = (nfit + 3) / 4 * 4;
     void *blk = nullptr;
-    BF_HIP(hipMalloc(&blk, sizeof(float) * nfloat + sizeof(int32_t) * nfit + 16));
+    const size_t bytes = sizeof(float) * nfloat + sizeof(int32_t) * nfit + 64;
+    BF_HIP(hipMalloc(&blk, bytes));
+    BF_HIP(hipMemset(blk, 0, bytes));
     p->d_block = (float *)blk;
     if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
         p->d_min = p->d_block;
@@ -60,6 +63,7 @@ int ensure_device(bifeat_params *p) {
         p->d_cb = p->d_block;
     }
     p->d_fit = reinterpret_cast<int32_t *>(p->d_block + nfloat);
+    p->d_zero = reinterpret_cast<uint8_t *>(p->d_fit + nfit);
     return BIFEAT_OK;
 }
 
@@ -143,6 +147,8 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     else if (!strcmp(name, "mean_generic")) p->opt_mean_generic = value;
     else if (!strcmp(name, "max_blocks")) p->opt_max_blocks = value;
     else if (!strcmp(name, "dequant_flat")) p->opt_dequant_flat = value;
+    else if (!strcmp(name, "mean_lean")) p->opt_mean_lean = value;
+    else if (!strcmp(name, "mean_max_degree")) p->opt_mean_max_degree = value;
     else return BIFEAT_EINVAL;
     return BIFEAT_OK;
 }

@@ -29,6 +29,7 @@ struct bifeat_params {
     float *d_block = nullptr;
     float *d_min = nullptr, *d_scale = nullptr, *d_inv = nullptr, *d_max = nullptr;
     float *d_T = nullptr, *d_V = nullptr, *d_cb = nullptr;
+    uint8_t *d_zero = nullptr;  // 64 zero bytes (stand-in row for masked loads)
     int32_t *d_fit = nullptr;  // uniform: ordered-int keys [min D | max D]; log: bits of [mmin, mmax]
 
     bool fitted = false;
@@ -39,6 +40,8 @@ struct bifeat_params {
     int opt_mean_slots = 0;
     int opt_mean_blocks = 0;
     int opt_max_blocks = 0;    // cap on workgroups of the gather kernels
+    int opt_mean_lean = 1;        // 0: never use the short-list kernel
+    int opt_mean_max_degree = 0;  // caller's promise: no neighbour list is longer (0 = unknown)
     int opt_dequant_flat = 0;  // 1: gather_dequant without the LDS-staged tile kernel
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
 };
@@ -62,8 +65,14 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
 hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                               const int64_t *indices, int64_t V, int64_t E, float *out,
                               hipStream_t s);
+// min_len: lists with at most this many neighbours are skipped (left to the
+// short-list kernel); -1 = none
 void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
+                             int min_len, hipStream_t s);
+int lean_capacity(int bits, bool wide);
+bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                             const int64_t *indices, int64_t V, float *out, int thr, bool wide,
                              hipStream_t s);
 
 // ---- order-preserving float <-> int keys for atomic min/max

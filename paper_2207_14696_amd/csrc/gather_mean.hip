@@ -129,7 +129,18 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
     const int vec = (D % 4 == 0) && ((uintptr_t)out % 16 == 0);
     const int kind = p->scheme.kind;
     if (kind == BIFEAT_SQ_UNIFORM && !p->opt_mean_generic && D <= 2048) {
-        launch_gather_mean_swar(p, codes, indptr, indices, V, E, out, vec, s);
+        // Short lists (sampled blocks) go to the lean kernel, anything longer to the
+        // general one; each skips the other's destinations.  The caller's bound on
+        // the list length (or, without one, twice the average) picks the lean
+        // kernel's field width.
+        const int64_t avg = V > 0 ? E / V : 0;
+        const int64_t need = p->opt_mean_max_degree > 0 ? p->opt_mean_max_degree : 2 * avg;
+        const bool wide = need > lean_capacity(p->scheme.bits, false);
+        const int thr = lean_capacity(p->scheme.bits, wide);
+        const bool lean = p->opt_mean_lean && p->opt_mean_slots == 0 && vec && V > 0 && need <= thr &&
+                          launch_gather_mean_lean(p, codes, indptr, indices, V, out, thr, wide, s);
+        const bool all_short = lean && p->opt_mean_max_degree > 0;
+        if (!all_short) launch_gather_mean_swar(p, codes, indptr, indices, V, E, out, vec, lean ? thr : -1, s);
     } else if (kind == BIFEAT_SQ_UNIFORM) {
         launch_float<MK_UNIFORM>(p, codes, indptr, indices, V, p->d_min, p->d_scale, out, vec, s);
     } else if (kind == BIFEAT_SQ_LOG) {

@@ -1,0 +1,281 @@
+// Fused gather + neighbourhood mean for uniform scalar codes, short lists
+// (paper Sec. 3.3 load fused with the aggregation of Appendix A.1) - the form
+// sampled minibatch blocks take: every destination has at most `fanout`
+// neighbours.
+//
+// Same arithmetic as gather_mean_swar.hip (mean_j = min_j + scale_j*sum(q)/n,
+// packed code words added as integers in wide-enough fields), cut down to what
+// short lists need so that it fits in few registers and many waves stay
+// resident:
+//   - LPR lanes own a destination (one 4..16-byte chunk of the packed row each)
+//     and walk its whole list: no cross-lane traffic, one level of fields
+//     (lists longer than the field capacity `thr` are left to the general
+//     kernel, which is launched right after with the complementary filter);
+//   - slots past the end of a list load a 16-byte zero row instead of being
+//     masked, so the U index loads and then the U row loads of an iteration are
+//     all in flight together;
+//   - field sums go through LDS once and the tile's output rows (contiguous in
+//     memory) are written by the whole wave with consecutive 16-byte stores.
+#include "common.hpp"
+
+namespace bf {
+
+template <int BITS, bool WIDE> struct LeanSwar;
+// kF: field width, kN: registers per 32-bit word; register i, field f holds the
+// sum of code number i + f*kN; kCap = rows a field can sum.  The WIDE forms
+// spend more shift+mask work per word on fields that hold longer lists.
+template <bool WIDE> struct LeanSwar<8, WIDE> { static constexpr int kF = 16, kN = 2, kCap = 257; static constexpr uint32_t kMask = 0x00FF00FFu; };
+template <> struct LeanSwar<4, false> { static constexpr int kF = 8, kN = 2, kCap = 17; static constexpr uint32_t kMask = 0x0F0F0F0Fu; };
+template <> struct LeanSwar<4, true> { static constexpr int kF = 16, kN = 4, kCap = 4369; static constexpr uint32_t kMask = 0x000F000Fu; };
+template <bool WIDE> struct LeanSwar<2, WIDE> { static constexpr int kF = 8, kN = 4, kCap = 85; static constexpr uint32_t kMask = 0x03030303u; };
+template <> struct LeanSwar<1, false> { static constexpr int kF = 4, kN = 4, kCap = 15; static constexpr uint32_t kMask = 0x11111111u; };
+template <> struct LeanSwar<1, true> { static constexpr int kF = 8, kN = 8, kCap = 255; static constexpr uint32_t kMask = 0x01010101u; };
+
+static int cap64(int cap) { return cap < 64 ? cap : 64; }
+
+// longest list the short-list kernel takes, in its narrow and wide forms
+int lean_capacity(int bits, bool wide) {
+    switch (bits) {
+        case 8: return cap64(LeanSwar<8, false>::kCap);
+        case 4: return cap64(wide ? LeanSwar<4, true>::kCap : LeanSwar<4, false>::kCap);
+        case 2: return cap64(LeanSwar<2, false>::kCap);
+        default: return cap64(wide ? LeanSwar<1, true>::kCap : LeanSwar<1, false>::kCap);
+    }
+}
+
+namespace {
+
+struct __attribute__((aligned(4))) U3 { uint32_t x, y, z; };
+
+template <int CW>
+__device__ inline void load_words(const uint8_t *p, uint32_t *w) {
+    if constexpr (CW == 4) {
+        uint4 q = *reinterpret_cast<const uint4 *>(p);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else if constexpr (CW == 3) {
+        U3 q = *reinterpret_cast<const U3 *>(p);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z;
+    } else if constexpr (CW == 2) {
+        uint2 q = *reinterpret_cast<const uint2 *>(p);
+        w[0] = q.x; w[1] = q.y;
+    } else {
+        w[0] = *reinterpret_cast<const uint32_t *>(p);
+    }
+}
+
+__device__ inline void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr int kWaves = kThreads / 64;
+#ifndef BF_LEAN_U
+#define BF_LEAN_U 4
+#endif
+#ifndef BF_LEAN_WPE
+#define BF_LEAN_WPE 6
+#endif
+
+template <int BITS, int CW, bool WIDE>
+__global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel(
+    const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
+    const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
+    const float *__restrict__ sc, const uint8_t *__restrict__ zero_row, float *__restrict__ out,
+    int lpr_log2, int chunks, int thr) {
+    using W = LeanSwar<BITS, WIDE>;
+    constexpr int R = CW * W::kN;   // accumulator registers per lane
+    constexpr int CPW = 32 / BITS;  // codes per word
+    constexpr int CPL = CW * CPW;   // columns per lane
+    constexpr int U = BF_LEAN_U;    // neighbour rows in flight per lane
+    constexpr uint32_t FMAX = (1u << W::kF) - 1u;
+
+    extern __shared__ uint32_t smem[];
+    float *s_sc = reinterpret_cast<float *>(smem);  // [scale D | min D], D % 4 == 0
+    float *s_mn = s_sc + D;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *meta = reinterpret_cast<float *>(smem + 2 * D) + wave * 64;
+    uint32_t *stage = smem + 2 * D + 64 * kWaves + wave * (64 * R);
+    for (int i = threadIdx.x; i < D; i += kThreads) {
+        s_sc[i] = sc[i];
+        s_mn[i] = mn[i];
+    }
+    __syncthreads();
+
+    const int LPR = 1 << lpr_log2;
+    const int dpw_log2 = 6 - lpr_log2;
+    const int dpw = 1 << dpw_log2;
+    const int lane_chunk = lane & (LPR - 1);
+    const int d_local = lane >> lpr_log2;
+    const bool chunk_ok = lane_chunk < chunks;
+    const uint32_t coff = (uint32_t)lane_chunk * (CW * 4);
+    const int nf4 = D >> 2;
+    const int step_d = 64 / nf4, step_f = 64 % nf4;
+    const int lane_d = lane / nf4, lane_f = lane % nf4;
+    const int64_t tiles = (V + dpw - 1) >> dpw_log2;
+    const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+
+    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += n_waves) {
+        const int64_t v_tile = tile << dpw_log2;
+        const int ndst = (int)min((int64_t)dpw, V - v_tile);
+        int64_t beg = 0, end = 0;
+        if (d_local < ndst) {
+            beg = indptr[v_tile + d_local];
+            end = indptr[v_tile + d_local + 1];
+        }
+        const int64_t n64 = end - beg;
+        const bool mine = d_local < ndst && n64 <= thr;  // longer lists: the general kernel
+        const int n = mine ? (int)n64 : 0;
+        if (lane_chunk == 0) meta[d_local] = mine ? (n > 0 ? 1.0f / (float)n : 0.0f) : -1.0f;
+
+        uint32_t acc[R];
+#pragma unroll
+        for (int r = 0; r < R; r++) acc[r] = 0u;
+        const int64_t *ip = indices + beg;
+        const int cnt = chunk_ok ? n : 0;
+        for (int k = 0; k < cnt; k += U) {
+            int64_t row[U];
+            uint32_t w[U][CW];
+#pragma unroll
+            for (int u = 0; u < U; u++) row[u] = ip[min(k + u, cnt - 1)];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const uint8_t *src = (k + u < cnt) ? codes + (uint64_t)row[u] * rb + coff : zero_row;
+                load_words<CW>(src, w[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++)
+#pragma unroll
+                for (int c = 0; c < CW; c++)
+#pragma unroll
+                    for (int i = 0; i < W::kN; i++)
+                        acc[c * W::kN + i] += (w[u][c] >> (BITS * i)) & W::kMask;
+        }
+        {
+            uint32_t *sp = stage + lane * R;
+#pragma unroll
+            for (int r = 0; r < R; r++) sp[r] = acc[r];
+        }
+        wave_sync();
+
+        // ---- the tile's output rows, one contiguous span of ndst*nf4 float4 granules
+        float4 *span = reinterpret_cast<float4 *>(out + v_tile * D);
+        const int ngran = ndst * nf4;
+        int d = lane_d, f = lane_f;
+#pragma unroll 2
+        for (int m = lane; m < ngran; m += 64) {
+            const float md = meta[d];
+            const int j0 = 4 * f;
+            const int lc = j0 / CPL, jj = j0 % CPL;
+            const int k = jj / CPW, c = jj % CPW;
+            const uint32_t *sp = stage + (((d << lpr_log2) + lc) * CW + k) * W::kN;
+            uint32_t sum[4];
+            if constexpr (W::kN >= 4) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(sp + c % W::kN);
+                const int sh = W::kF * (c / W::kN);
+                sum[0] = (q.x >> sh) & FMAX;
+                sum[1] = (q.y >> sh) & FMAX;
+                sum[2] = (q.z >> sh) & FMAX;
+                sum[3] = (q.w >> sh) & FMAX;
+            } else {
+                const uint2 q = *reinterpret_cast<const uint2 *>(sp);
+                const int sh = W::kF * (c / 2);
+                sum[0] = (q.x >> sh) & FMAX;
+                sum[1] = (q.y >> sh) & FMAX;
+                sum[2] = (q.x >> (sh + W::kF)) & FMAX;
+                sum[3] = (q.y >> (sh + W::kF)) & FMAX;
+            }
+            const float4 a = *reinterpret_cast<const float4 *>(s_sc + j0);
+            const float4 b = *reinterpret_cast<const float4 *>(s_mn + j0);
+            const bool some = md > 0.0f;  // md == 0: empty list, zero row
+            float4 val;
+            val.x = some ? fmaf(a.x, (float)sum[0] * md, b.x) : 0.0f;
+            val.y = some ? fmaf(a.y, (float)sum[1] * md, b.y) : 0.0f;
+            val.z = some ? fmaf(a.z, (float)sum[2] * md, b.z) : 0.0f;
+            val.w = some ? fmaf(a.w, (float)sum[3] * md, b.w) : 0.0f;
+            if (md >= 0.0f) span[m] = val;  // md < 0: not this kernel's destination
+            d += step_d;
+            f += step_f;
+            if (f >= nf4) {
+                f -= nf4;
+                d++;
+            }
+        }
+        wave_sync();  // stage / meta are rewritten by the next tile
+    }
+}
+
+inline int pow2ceil(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+inline int ilog2(int x) {
+    int l = 0;
+    while ((1 << l) < x) l++;
+    return l;
+}
+
+template <int BITS, bool WIDE>
+bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                      const int64_t *indices, int64_t V, float *out, int thr, hipStream_t s) {
+    using W = LeanSwar<BITS, WIDE>;
+    const int64_t rb = p->rb;
+    int cw = 0;
+    double best_eff = -1.0;
+    for (int c = 4; c >= 1; c--) {
+        if (rb % (4 * c)) continue;
+        const int chunks = (int)(rb / (4 * c));
+        if (chunks > 64) continue;
+        const double eff = (double)chunks / pow2ceil(chunks);
+        if (eff > best_eff + 1e-9) {
+            best_eff = eff;
+            cw = c;
+        }
+    }
+    if (!cw) return false;  // packed row longer than 64 lane loads
+    const int chunks = (int)(rb / (4 * cw));
+    const int lpr = pow2ceil(chunks);
+    const int dpw = 64 / lpr;
+    const int64_t tiles = (V + dpw - 1) / dpw;
+    const int64_t cap = p->opt_mean_blocks > 0 ? p->opt_mean_blocks : (1 << 16);
+    int64_t want = (tiles + kWaves - 1) / kWaves;
+    const int blocks = (int)(want < cap ? (want < 1 ? 1 : want) : cap);
+    const int D = (int)p->D;
+    const int R = cw * W::kN;
+    const size_t shm = sizeof(uint32_t) * ((size_t)2 * D + 64 * kWaves + (size_t)kWaves * 64 * R);
+#define BF_LN(CWV)                                                                               \
+    gather_mean_lean_kernel<BITS, CWV, WIDE><<<blocks, kThreads, shm, s>>>(                            \
+        codes, (uint32_t)rb, indptr, indices, V, D, p->d_min, p->d_scale, p->d_zero, out,        \
+        ilog2(lpr), chunks, thr)
+    switch (cw) {
+        case 4: BF_LN(4); break;
+        case 3: BF_LN(3); break;
+        case 2: BF_LN(2); break;
+        default: BF_LN(1); break;
+    }
+#undef BF_LN
+    return true;
+}
+
+}  // namespace
+
+// Launches the short-list kernel (lists of at most `thr` rows; wide = the form
+// with the larger field capacity); returns false (nothing launched) when the
+// table's shape is outside what it handles.
+bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                             const int64_t *indices, int64_t V, float *out, int thr, bool wide,
+                             hipStream_t s) {
+    switch (p->scheme.bits) {
+        case 1:
+            return wide ? launch_lean_bits<1, true>(p, codes, indptr, indices, V, out, thr, s)
+                        : launch_lean_bits<1, false>(p, codes, indptr, indices, V, out, thr, s);
+        case 2: return launch_lean_bits<2, false>(p, codes, indptr, indices, V, out, thr, s);
+        case 4:
+            return wide ? launch_lean_bits<4, true>(p, codes, indptr, indices, V, out, thr, s)
+                        : launch_lean_bits<4, false>(p, codes, indptr, indices, V, out, thr, s);
+        default: return launch_lean_bits<8, false>(p, codes, indptr, indices, V, out, thr, s);
+    }
+}
+
+}  // namespace bf

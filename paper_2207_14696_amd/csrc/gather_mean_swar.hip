@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
     const float *__restrict__ sc, float *__restrict__ out, int lpr_log2, int s_log2, int chunks,
-    int long_thr) {
+    int long_thr, int min_len) {
     using W = Swar<BITS>;
     constexpr bool kTwoLevel = W::kF1 != W::kF0;
     constexpr int R0 = CW * W::kN0, R1 = CW * W::kN1;
@@ -116,7 +116,11 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
     __syncthreads();
 
     const int LPR = 1 << lpr_log2;
-    const int g0_log2 = lpr_log2 + s_log2;  // lanes per destination in the main pass
+    // filter mode (min_len >= 0: the short-list kernel has taken every list of at
+    // most min_len rows): the main pass only scans 64 list lengths per wave and
+    // hands each longer list to the whole wave
+    const bool scan = min_len >= 0;
+    const int g0_log2 = scan ? 0 : lpr_log2 + s_log2;  // lanes per destination in the main pass
     const int dpw_log2 = 6 - g0_log2;       // destinations per wave tile
     const int dpw = 1 << dpw_log2;
     const int64_t tiles = (V + dpw - 1) >> dpw_log2;
@@ -146,7 +150,8 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                 vbase = v_tile + (hl >> g0_log2);
                 ndst = 1;
             }
-            const int g_log2 = lpr_log2 + sl2, S = 1 << sl2, G = 1 << g_log2;
+            const int g_log2 = (mode == 0 && scan) ? 0 : lpr_log2 + sl2;
+            const int S = 1 << sl2, G = 1 << g_log2;
             const int lig = lane & (G - 1);
             const int slot = lig >> lpr_log2;
             const int d_local = lane >> g_log2;
@@ -157,10 +162,12 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                 end = indptr[vbase + d_local + 1];
             }
             const int64_t n = end - beg;
-            const bool is_long = mode == 0 && n > long_thr;
-            if (mode == 0) hubs = __ballot(is_long && lig == 0);
+            const bool is_short = n <= min_len;  // the short-list kernel's destination
+            const bool is_long = mode == 0 && (scan ? !is_short : n > long_thr);
+            if (mode == 0) hubs = __ballot(valid && is_long && lig == 0);
+            if (mode == 0 && scan) continue;  // nothing is accumulated in the scan pass
             const float inv_n = n > 0 ? 1.0f / (float)n : 0.0f;
-            if (is_long) end = beg;  // handled by the whole wave afterwards
+            if (is_long || is_short) end = beg;  // whole wave afterwards / other kernel
 
             for (int cbase = 0; cbase < chunks; cbase += LPR) {
                 const int chunk = cbase + lane_chunk;
@@ -261,7 +268,7 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                     }
                     if (lig == 0) {
                         uint32_t fl = 0;
-                        if (!valid || is_long || (round > 0 && rbeg >= end)) fl |= F_SKIP;
+                        if (!valid || is_long || is_short || (round > 0 && rbeg >= end)) fl |= F_SKIP;
                         if (more) fl |= F_MORE;
                         if (round > 0) fl |= F_PREV;
                         if (n == 0) fl |= F_EMPTY;
@@ -360,7 +367,7 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                     } else {
                         // rows not 16-byte aligned: each group writes its own row, scalar stores
                         const float2 md = meta[valid ? d_local : 0];
-                        const uint32_t fl = valid ? __float_as_uint(md.y) : F_SKIP;
+                        const uint32_t fl = valid ? __float_as_uint(md.y) : (uint32_t)F_SKIP;
                         if (!(fl & F_SKIP)) {
                             const int f4_lo = cbase * (CPL / 4);
                             const int f4_hi = min(nf4, (cbase + LPR) * (CPL / 4));
@@ -417,7 +424,7 @@ static inline int ilog2(int x) {
 template <int BITS>
 static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                         const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
-                        hipStream_t s) {
+                        int min_len, hipStream_t s) {
     using W = Swar<BITS>;
     const int64_t rb = p->rb;
     // words per lane: every row chunk must be whole; prefer the choice that
@@ -439,6 +446,7 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
     const int lpr = pow2ceil(chunks > 64 ? 64 : chunks);
     // slots per destination: about one per 16 neighbours of the average list
     int S = p->opt_mean_slots;
+    if (min_len >= 0) S = 1;  // scan mode: 64 list lengths per wave, long lists by the whole wave
     if (S <= 0) {
         const int64_t avg = V > 0 ? E / V : 0;
         S = pow2ceil((int)((avg + 15) / 16 > 64 ? 64 : (avg + 15) / 16));
@@ -447,7 +455,7 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
     while (lpr * S > 64) S >>= 1;
     int long_thr = 32 * S;
     if (long_thr > W::kCap1) long_thr = W::kCap1;
-    const int dpw = 64 / (lpr * S);
+    const int dpw = min_len >= 0 ? 64 : 64 / (lpr * S);
     const int64_t tiles = (V + dpw - 1) / dpw;
     int64_t want = (tiles + kWaves - 1) / kWaves;
     const int64_t cap = p->opt_mean_blocks > 0 ? p->opt_mean_blocks : (1 << 20);
@@ -461,11 +469,11 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
         if (vec)                                                                                   \
             gather_mean_swar_kernel<BITS, CWV, true><<<blocks, kThreads, shm, s>>>(                \
                 codes, rb, indptr, indices, V, (int)p->D, p->d_min, p->d_scale, out, ilog2(lpr),   \
-                ilog2(S), chunks, long_thr);                                                       \
+                ilog2(S), chunks, long_thr, min_len);                                                       \
         else                                                                                       \
             gather_mean_swar_kernel<BITS, CWV, false><<<blocks, kThreads, shm, s>>>(               \
                 codes, rb, indptr, indices, V, (int)p->D, p->d_min, p->d_scale, out, ilog2(lpr),   \
-                ilog2(S), chunks, long_thr);                                                       \
+                ilog2(S), chunks, long_thr, min_len);                                                       \
     } while (0)
     switch (cw) {
         case 4: BF_SW(4); break;
@@ -478,12 +486,12 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
 
 void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
-                             hipStream_t s) {
+                             int min_len, hipStream_t s) {
     switch (p->scheme.bits) {
-        case 1: launch_swar<1>(p, codes, indptr, indices, V, E, out, vec, s); break;
-        case 2: launch_swar<2>(p, codes, indptr, indices, V, E, out, vec, s); break;
-        case 4: launch_swar<4>(p, codes, indptr, indices, V, E, out, vec, s); break;
-        default: launch_swar<8>(p, codes, indptr, indices, V, E, out, vec, s); break;
+        case 1: launch_swar<1>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
+        case 2: launch_swar<2>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
+        case 4: launch_swar<4>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
+        default: launch_swar<8>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
     }
 }
 

@@ -250,3 +250,28 @@ def test_argument_errors(bf, torch):
     with pytest.raises(bf.BifeatError) as e:
         v.fit_update(torch.zeros((3, 16), device="cuda"))
     assert e.value.status == -4                       # codebook training is not a fit pass here
+
+
+@pytest.mark.parametrize("bits,D", [(1, 768), (2, 128), (4, 100), (8, 128), (4, 768), (1, 64), (8, 4)])
+def test_gather_mean_short_lists_take_two_kernels(bf, torch, bits, D):
+    # sampled-block shape: short lists (the lean kernel) with a few long ones mixed
+    # in (left to the general kernel, which skips the short ones)
+    q, s, codes, dcodes = _tables(bf, torch, "uniform", bits, D, N=4001)
+    rng = np.random.default_rng(3)
+    indptr, indices = random_csr(2307, codes.shape[0], 10, rng, hubs=(16, 18, 40, 300))
+    want = orc.gather_mean(s, codes, indptr, indices)
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    out = torch.full((2307, D), float("nan"), device="cuda")
+    q.gather_mean(dcodes, dptr, dind, out)
+    assert_close(out.cpu().numpy(), want, s, "lean + general")
+    q.set_option("mean_lean", 0)
+    assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), want, s, "general only")
+    q.set_option("mean_lean", 1)
+    # all lists short and the caller says so: the lean kernel alone
+    indptr, indices = random_csr(1000, codes.shape[0], 5, rng)
+    want = orc.gather_mean(s, codes, indptr, indices)
+    q.set_option("mean_max_degree", 5)
+    out = torch.full((1000, D), float("nan"), device="cuda")
+    q.gather_mean(dcodes, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), out)
+    assert_close(out.cpu().numpy(), want, s, "lean only")
+    q.set_option("mean_max_degree", 0)
