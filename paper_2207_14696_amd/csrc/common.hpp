@@ -98,6 +98,25 @@ __device__ inline float4 load4(const __half *p) {
     float2 fa = __half22float2(a), fb = __half22float2(b);
     return make_float4(fa.x, fa.y, fb.x, fb.y);
 }
+// Output rows are written once and not read again by these kernels: streaming
+// (non-temporal) stores keep them from evicting the packed table from the
+// caches the gathers depend on.
+__device__ inline void store_stream(float4 *p, const float4 v) {
+    __builtin_nontemporal_store(v.x, &p->x);
+    __builtin_nontemporal_store(v.y, &p->y);
+    __builtin_nontemporal_store(v.z, &p->z);
+    __builtin_nontemporal_store(v.w, &p->w);
+}
+__device__ inline void store_stream(uint4 *p, const uint4 v) {
+    __builtin_nontemporal_store(v.x, &p->x);
+    __builtin_nontemporal_store(v.y, &p->y);
+    __builtin_nontemporal_store(v.z, &p->z);
+    __builtin_nontemporal_store(v.w, &p->w);
+}
+// index arrays are streamed once as well
+template <typename T>
+__device__ inline T load_stream(const T *p) { return __builtin_nontemporal_load(p); }
+
 __device__ inline float load1(const float *p) { return *p; }
 __device__ inline float load1(const __half *p) { return __half2float(*p); }
 

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(kThreads) void gather_codes_kernel(const uint4 *__r
     const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
     if (t >= rows_per_pass * (uint32_t)rc) return;
     const int c = (int)(t % (uint32_t)rc);
-    for (int64_t i = t / rc; i < M; i += rows_per_pass) out[i * rc + c] = codes[idx[i] * rc + c];
+    for (int64_t i = t / rc; i < M; i += rows_per_pass) store_stream(&out[i * rc + c], codes[idx[i] * rc + c]);
 }
 
 hipError_t launch_gather_codes(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
@@ -48,7 +48,7 @@ template <bool VEC>
 __device__ inline void store4(float *out, int64_t row, int D, int col0, const float v[4]) {
     float *dst = out + row * D + col0;
     if constexpr (VEC) {
-        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        store_stream(reinterpret_cast<float4 *>(dst), make_float4(v[0], v[1], v[2], v[3]));
     } else {
 #pragma unroll
         for (int k = 0; k < 4; k++)
@@ -164,14 +164,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_tile_kernel(
                 v.z = s_par[(bits >> (2 * BITS)) & mask];
                 v.w = s_par[(bits >> (3 * BITS)) & mask];
             }
-#ifdef BF_NT_STORE
-            __builtin_nontemporal_store(v.x, &span[m].x);
-            __builtin_nontemporal_store(v.y, &span[m].y);
-            __builtin_nontemporal_store(v.z, &span[m].z);
-            __builtin_nontemporal_store(v.w, &span[m].w);
-#else
-            span[m] = v;
-#endif
+            store_stream(&span[m], v);
             d += step_d;
             f += step_f;
             if (f >= nf4) {
@@ -240,6 +233,9 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
     if (vec && c16 <= 64 && !p->opt_dequant_flat) {
         const int RT = 64 / c16;
         const int64_t tiles = (M + RT - 1) / RT;
+        // about one tile per wave: the hardware's wave scheduling hides the index -> row ->
+        // store latency better than a persistent, software-pipelined loop (measured); grids
+        // beyond 2^16 workgroups lose again
         const int64_t cap = p->opt_max_blocks > 0 ? p->opt_max_blocks : (1 << 16);
         int64_t want = (tiles + 3) / 4;
         const int tb = (int)(want < cap ? want : cap);

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
         const float inv_n = 1.0f;
         float *dst = out + v * D + col0;
         if constexpr (VEC) {
-            *reinterpret_cast<float4 *>(dst) = make_float4(acc[0] * inv_n, acc[1] * inv_n, acc[2] * inv_n, acc[3] * inv_n);
+            store_stream(reinterpret_cast<float4 *>(dst), make_float4(acc[0] * inv_n, acc[1] * inv_n, acc[2] * inv_n, acc[3] * inv_n));
         } else {
 #pragma unroll
             for (int k = 0; k < 4; k++)

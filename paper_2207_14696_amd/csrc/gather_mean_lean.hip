@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
             val.y = some ? fmaf(a.y, (float)sum[1] * md, b.y) : 0.0f;
             val.z = some ? fmaf(a.z, (float)sum[2] * md, b.z) : 0.0f;
             val.w = some ? fmaf(a.w, (float)sum[3] * md, b.w) : 0.0f;
-            if (md >= 0.0f) span[m] = val;  // md < 0: not this kernel's destination
+            if (md >= 0.0f) store_stream(&span[m], val);  // md < 0: not this kernel's destination
             d += step_d;
             f += step_f;
             if (f >= nf4) {

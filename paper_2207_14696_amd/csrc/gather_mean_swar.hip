@@ -334,11 +334,11 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                                     val = make_float4(__uint_as_float(sum[0]), __uint_as_float(sum[1]),
                                                       __uint_as_float(sum[2]), __uint_as_float(sum[3]));
                             }
-#ifdef BF_ABL_NO_OUTPUT
-                            if (write && val.x == 1.2345e-30f) *dst = val;
-#else
-                            if (write) *dst = val;
-#endif
+                            // final values stream out; parked partial sums are read back
+                            if (write) {
+                                if (kRounds && (fl & F_MORE)) *dst = val;
+                                else store_stream(dst, val);
+                            }
                         };
                         const int n_it = (ndst * nf4 + 63) >> 6;
                         int d = lane_d, f = lane_f;
