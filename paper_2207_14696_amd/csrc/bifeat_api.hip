@@ -148,6 +148,7 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     else if (!strcmp(name, "max_blocks")) p->opt_max_blocks = value;
     else if (!strcmp(name, "dequant_flat")) p->opt_dequant_flat = value;
     else if (!strcmp(name, "mean_lean")) p->opt_mean_lean = value;
+    else if (!strcmp(name, "vq_sliced")) p->opt_vq_sliced = value;
     else if (!strcmp(name, "mean_max_degree")) p->opt_mean_max_degree = value;
     else return BIFEAT_EINVAL;
     return BIFEAT_OK;

@@ -42,6 +42,7 @@ struct bifeat_params {
     int opt_max_blocks = 0;    // cap on workgroups of the gather kernels
     int opt_mean_lean = 1;        // 0: never use the short-list kernel
     int opt_mean_max_degree = 0;  // caller's promise: no neighbour list is longer (0 = unknown)
+    int opt_vq_sliced = 1;        // 0: vector codes decode from L2 instead of LDS-resident slices
     int opt_dequant_flat = 0;  // 1: gather_dequant without the LDS-staged tile kernel
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
 };
@@ -70,6 +71,10 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
 void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
                              int min_len, hipStream_t s);
+bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
+                                     int64_t M, float *out, hipStream_t s);
+bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                                  const int64_t *indices, int64_t V, float *out, hipStream_t s);
 int lean_capacity(int bits, bool wide);
 bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, float *out, int thr, bool wide,

@@ -222,6 +222,8 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
     if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
     const int kind = p->scheme.kind, bits = p->scheme.bits;
     if (kind == BIFEAT_VQ) {
+        if (p->opt_vq_sliced && launch_gather_dequant_vq_sliced(p, codes, idx, M, out, s))
+            return hipGetLastError();
         const int w = p->scheme.vq_width;
         if (w % 4 == 0 && vec)
             gather_dequant_vq_kernel<true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);

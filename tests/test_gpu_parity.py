@@ -180,6 +180,10 @@ def test_gather_codes_and_dequant(bf, torch, kind, bits, D):
         q.set_option("dequant_flat", 1)
         assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant flat")
         q.set_option("dequant_flat", 0)
+    else:                       # codebooks from L2 instead of LDS-resident slices
+        q.set_option("vq_sliced", 0)
+        assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant L2")
+        q.set_option("vq_sliced", 1)
     # empty request
     empty = torch.empty(0, dtype=torch.int64, device="cuda")
     assert q.gather_dequant(dcodes, empty).shape == (0, D)
@@ -207,6 +211,10 @@ def test_gather_mean(bf, torch, kind, bits, D):
         q.set_option("mean_generic", 1)
         assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), want, s, "generic")
         q.set_option("mean_generic", 0)
+    if kind == "vq":
+        q.set_option("vq_sliced", 0)
+        assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), want, s, "L2 codebooks")
+        q.set_option("vq_sliced", 1)
 
 
 def test_gather_mean_degenerate_blocks(bf, torch):
