@@ -96,15 +96,19 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
     pre = {}
     if w.kind == "vq":
-        # codebooks: sub-vectors of the first `length` sampled rows (no trainer on
-        # the GPU path yet); enough for throughput, which does not depend on values
-        from bifeat_inputs.features import mix64, stream_key, STREAM_MISC
-        ids = (mix64(stream_key(w.seed, STREAM_MISC) + np.arange(w.vq_length, dtype=np.uint64))
-               % np.uint64(w.N)).astype(np.int64)
-        rows = feature_rows(w.spec, ids).astype(np.float32)
-        P = q.codes_per_row
-        cb = np.ascontiguousarray(rows.reshape(w.vq_length, P, w.vq_width).transpose(1, 0, 2))
-        q.params_set_codebooks(cb)
+        # codebooks: 10 Lloyd rounds on the GPU over a 65 536-row sample (rows of the
+        # synthetic table are i.i.d., so its first rows are a uniform sample)
+        ns = min(w.N, 1 << 16)
+        sample = table.chunk(0, ns)
+        a, b = ev(), ev()
+        a.record()
+        q.fit_update(sample)
+        q.fit_finalize()
+        b.record()
+        b.synchronize()
+        pre["vq_train_ms"] = a.elapsed_time(b)
+        pre["vq_train_rows"] = ns
+        del sample
     else:
         fit_ms = 0.0
         q.fit_reset()

@@ -93,8 +93,14 @@ int64_t bifeat_codes_per_row(const bifeat_params *p);
  *   magnitudes come back to the host, where log2/exp2 are evaluated in fp64).
  *   Tail clipping is not fitted here: pass a clipped pair to
  *   bifeat_params_set_log instead.
- * BIFEAT_VQ: BIFEAT_ENOTSUP (train codebooks elsewhere, then
- *   bifeat_params_set_codebooks).
+ * BIFEAT_VQ (Sec. 3.2 k-means per part; Appendix E: on a uniform row sample,
+ *   which is what the caller passes as the chunk): the first chunk after a
+ *   reset seeds every part's codebook with the sub-vectors of its first
+ *   `vq_length` rows (it must have at least that many); every update then runs
+ *   Lloyd rounds over its chunk (10, option "vq_iters"): nearest entry by the
+ *   encoder's distance rule, entry = mean of its members, an entry without
+ *   members keeps its value.  Sums are accumulated with fp32 atomics, so the
+ *   codebooks are reproducible in distortion, not bit for bit.
  * finalize without any update returns BIFEAT_ENOTFIT. */
 int bifeat_fit_reset(bifeat_params *p, void *stream);
 int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
@@ -116,6 +122,10 @@ int bifeat_params_set_log(bifeat_params *p, double e_min, double e_max);
 int bifeat_params_get_log(bifeat_params *p, double *e_min, double *e_max, float *T, float *V);
 int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks);
 int bifeat_params_get_codebooks(bifeat_params *p, float *codebooks);
+/* BIFEAT_VQ: mean squared distance (summed over parts) of each Lloyd round's
+ * assignment step in the last bifeat_fit_update; out: HOST [n], n <= 64.
+ * Synchronises the device. */
+int bifeat_vq_distortion(bifeat_params *p, float *out, int32_t n);
 
 /* ---- encode + pack one chunk (Sec. 3.1 Eq. (1); Sec. 3.2 nearest entry).
  * chunk: DEVICE [rows x D]; codes: DEVICE base of the packed table; rows
@@ -158,7 +168,14 @@ const char *bifeat_strerror(int status);
  * that share one destination's neighbour list in bifeat_gather_mean (power of
  * two, 0 = automatic), "mean_blocks" = cap on its workgroups (0 = automatic),
  * "mean_generic" = 1 routes uniform tables through the float-accumulate
- * kernel.  Unknown names return BIFEAT_EINVAL. */
+ * kernel; "mean_lean" = 0 disables the short-list kernel; "max_blocks" caps the
+ * gather_dequant grid; "dequant_flat" = 1 / "vq_sliced" = 0 select the
+ * unstaged decode kernels.  Two options carry information rather than tuning:
+ * "mean_max_degree" = d is the caller's promise that no neighbour list of the
+ * following bifeat_gather_mean calls is longer than d (0 = unknown; a sampler
+ * knows its fan-out), which lets the library skip the pass that looks for
+ * longer lists; "vq_iters" = Lloyd rounds per training chunk.
+ * Unknown names return BIFEAT_EINVAL. */
 int bifeat_set_option(bifeat_params *p, const char *name, int value);
 
 #ifdef __cplusplus

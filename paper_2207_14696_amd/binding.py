@@ -52,6 +52,7 @@ _SIGNATURES = {
     "bifeat_params_get_log": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4),
     "bifeat_params_set_codebooks": (C.c_int, [C.c_void_p, C.c_void_p]),
     "bifeat_params_get_codebooks": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_vq_distortion": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32]),
     "bifeat_quantize": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p,
                                   C.c_int64, C.c_void_p]),
     "bifeat_gather_codes": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
@@ -191,6 +192,11 @@ class Quantizer:
         cb = np.empty((self.codes_per_row, self.scheme.vq_length, self.scheme.vq_width), np.float32)
         _check(self._lib.bifeat_params_get_codebooks(self._h, _np_ptr(cb)))
         return cb
+
+    def vq_distortion(self, n: int = 10):
+        out = np.zeros(n, np.float32)
+        _check(self._lib.bifeat_vq_distortion(self._h, _np_ptr(out), n))
+        return out
 
     # ---- encode
     def quantize(self, chunk, codes, row0: int) -> None:

@@ -43,7 +43,7 @@ int ensure_device(bifeat_params *p) {
     size_t nfloat = 0, nfit = 0;
     if (p->scheme.kind == BIFEAT_SQ_UNIFORM) { nfloat = 4 * D; nfit = 2 * D; }
     else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 2; }
-    else nfloat = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
+    else nfloat = (size_t)p->P * p->scheme.vq_length * (2 * p->scheme.vq_width + 1) + 64;
     nfloat = (nfloat + 3) / 4 * 4;
     nfit = (nfit + 3) / 4 * 4;
     void *blk = nullptr;
@@ -60,7 +60,10 @@ int ensure_device(bifeat_params *p) {
         p->d_T = p->d_block;
         p->d_V = p->d_block + 128;
     } else {
+        const size_t ncb = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
         p->d_cb = p->d_block;
+        p->d_train = p->d_block + ncb;
+        p->d_dist = p->d_train + ncb + (size_t)p->P * p->scheme.vq_length;
     }
     p->d_fit = reinterpret_cast<int32_t *>(p->d_block + nfloat);
     p->d_zero = reinterpret_cast<uint8_t *>(p->d_fit + nfit);
@@ -149,6 +152,7 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     else if (!strcmp(name, "dequant_flat")) p->opt_dequant_flat = value;
     else if (!strcmp(name, "mean_lean")) p->opt_mean_lean = value;
     else if (!strcmp(name, "vq_sliced")) p->opt_vq_sliced = value;
+    else if (!strcmp(name, "vq_iters") && value >= 1 && value <= 64) p->opt_vq_iters = value;
     else if (!strcmp(name, "mean_max_degree")) p->opt_mean_max_degree = value;
     else return BIFEAT_EINVAL;
     return BIFEAT_OK;
@@ -156,10 +160,10 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
 
 int bifeat_fit_reset(bifeat_params *p, void *stream) {
     if (!p) return BIFEAT_EINVAL;
-    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
     int rc = ensure_device(p);
     if (rc) return rc;
-    BF_HIP(bf::launch_fit_reset(p, (hipStream_t)stream));
+    if (p->scheme.kind == BIFEAT_VQ) p->vq_seeded = false;
+    else BF_HIP(bf::launch_fit_reset(p, (hipStream_t)stream));
     p->fit_open = true;
     p->fit_rows = 0;
     p->fitted = false;
@@ -170,12 +174,25 @@ int bifeat_fit_reset(bifeat_params *p, void *stream) {
 int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
                       void *stream) {
     if (!p || !dtype_ok(dtype) || rows < 0 || (rows > 0 && !chunk)) return BIFEAT_EINVAL;
-    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
+    if (p->scheme.kind == BIFEAT_VQ && !p->vq_seeded && p->fit_open && rows > 0 &&
+        rows < p->scheme.vq_length)
+        return BIFEAT_EINVAL;  // the first sample chunk seeds `length` entries
+    if (p->scheme.kind == BIFEAT_VQ && !p->fit_open && rows > 0 && rows < p->scheme.vq_length)
+        return BIFEAT_EINVAL;
     if (!p->fit_open) {
         int rc = bifeat_fit_reset(p, stream);
         if (rc) return rc;
     }
     if (rows == 0) return BIFEAT_OK;
+    if (p->scheme.kind == BIFEAT_VQ) {
+        BF_HIP(bf::launch_vq_train(p, chunk, dtype, rows, !p->vq_seeded, p->opt_vq_iters,
+                                   (hipStream_t)stream));
+        p->vq_seeded = true;
+        p->vq_last_rows = rows;
+        p->vq_last_rounds = p->opt_vq_iters;
+        p->fit_rows += rows;
+        return BIFEAT_OK;
+    }
     BF_HIP(bf::launch_fit_update(p, chunk, dtype, rows, (hipStream_t)stream));
     p->fit_rows += rows;
     return BIFEAT_OK;
@@ -183,9 +200,10 @@ int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_
 
 int bifeat_fit_finalize(bifeat_params *p, void *stream) {
     if (!p) return BIFEAT_EINVAL;
-    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
     if (!p->fit_open || p->fit_rows == 0) return BIFEAT_ENOTFIT;
-    if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
+    if (p->scheme.kind == BIFEAT_VQ) {
+        p->host_valid = false;  // codebooks live on the device until asked for
+    } else if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
         BF_HIP(bf::launch_finalize_uniform(p, (hipStream_t)stream));
         p->host_valid = false;
     } else {
@@ -293,7 +311,25 @@ int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks) {
 int bifeat_params_get_codebooks(bifeat_params *p, float *codebooks) {
     if (!p || p->scheme.kind != BIFEAT_VQ) return BIFEAT_EINVAL;
     if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (!p->host_valid) {
+        const size_t n = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
+        p->h_cb.resize(n);
+        BF_HIP(hipDeviceSynchronize());
+        BF_HIP(hipMemcpy(p->h_cb.data(), p->d_cb, 4 * n, hipMemcpyDeviceToHost));
+        p->host_valid = true;
+    }
     if (codebooks) memcpy(codebooks, p->h_cb.data(), 4 * p->h_cb.size());
+    return BIFEAT_OK;
+}
+
+int bifeat_vq_distortion(bifeat_params *p, float *out, int32_t n) {
+    if (!p || p->scheme.kind != BIFEAT_VQ || !out || n < 0) return BIFEAT_EINVAL;
+    if (!p->vq_seeded || p->vq_last_rows == 0) return BIFEAT_ENOTFIT;
+    float tmp[64];
+    BF_HIP(hipDeviceSynchronize());
+    BF_HIP(hipMemcpy(tmp, p->d_dist, sizeof(tmp), hipMemcpyDeviceToHost));
+    for (int k = 0; k < n; k++)
+        out[k] = k < p->vq_last_rounds ? tmp[k] / (float)p->vq_last_rows : 0.0f;
     return BIFEAT_OK;
 }
 

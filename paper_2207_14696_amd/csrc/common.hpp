@@ -29,12 +29,17 @@ struct bifeat_params {
     float *d_block = nullptr;
     float *d_min = nullptr, *d_scale = nullptr, *d_inv = nullptr, *d_max = nullptr;
     float *d_T = nullptr, *d_V = nullptr, *d_cb = nullptr;
+    float *d_train = nullptr;   // vq training scratch: sums [P][len][w], counts [P][len]
+    float *d_dist = nullptr;    // vq training: summed squared distance per Lloyd round (64 slots)
     uint8_t *d_zero = nullptr;  // 64 zero bytes (stand-in row for masked loads)
     int32_t *d_fit = nullptr;  // uniform: ordered-int keys [min D | max D]; log: bits of [mmin, mmax]
 
     bool fitted = false;
     bool fit_open = false;
     int64_t fit_rows = 0;
+    bool vq_seeded = false;     // codebooks initialised from a sample chunk
+    int64_t vq_last_rows = 0;   // rows of the last training chunk
+    int vq_last_rounds = 0;
 
     // launch tuning (0 = automatic)
     int opt_mean_slots = 0;
@@ -42,6 +47,7 @@ struct bifeat_params {
     int opt_max_blocks = 0;    // cap on workgroups of the gather kernels
     int opt_mean_lean = 1;        // 0: never use the short-list kernel
     int opt_mean_max_degree = 0;  // caller's promise: no neighbour list is longer (0 = unknown)
+    int opt_vq_iters = 10;        // Lloyd rounds per training chunk
     int opt_vq_sliced = 1;        // 0: vector codes decode from L2 instead of LDS-resident slices
     int opt_dequant_flat = 0;  // 1: gather_dequant without the LDS-staged tile kernel
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
@@ -57,6 +63,8 @@ hipError_t launch_fit_reset(bifeat_params *p, hipStream_t s);
 hipError_t launch_fit_update(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
                              hipStream_t s);
 hipError_t launch_finalize_uniform(bifeat_params *p, hipStream_t s);
+hipError_t launch_vq_train(bifeat_params *p, const void *chunk, int dtype, int64_t rows, bool init,
+                           int rounds, hipStream_t s);
 hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
                            uint8_t *codes_row0, hipStream_t s);
 hipError_t launch_gather_codes(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
