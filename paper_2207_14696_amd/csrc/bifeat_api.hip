@@ -137,6 +137,7 @@ int bifeat_params_create(const bifeat_scheme *scheme, int64_t D, bifeat_params *
 void bifeat_params_destroy(bifeat_params *p) {
     if (!p) return;
     if (p->d_block) (void)hipFree(p->d_block);
+    if (p->d_scratch) (void)hipFree(p->d_scratch);
     delete p;
 }
 

@@ -31,6 +31,8 @@ struct bifeat_params {
     float *d_T = nullptr, *d_V = nullptr, *d_cb = nullptr;
     float *d_train = nullptr;   // vq training scratch: sums [P][len][w], counts [P][len]
     float *d_dist = nullptr;    // vq training: summed squared distance per Lloyd round (64 slots)
+    uint8_t *d_scratch = nullptr;  // grow-only workspace (vector codes: slice-major code strips)
+    size_t scratch_bytes = 0;
     uint8_t *d_zero = nullptr;  // 64 zero bytes (stand-in row for masked loads)
     int32_t *d_fit = nullptr;  // uniform: ordered-int keys [min D | max D]; log: bits of [mmin, mmax]
 
@@ -82,7 +84,8 @@ void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                      int64_t M, float *out, hipStream_t s);
 bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                                  const int64_t *indices, int64_t V, float *out, hipStream_t s);
+                                  const int64_t *indices, int64_t V, int64_t E, float *out,
+                                  hipStream_t s);
 int lean_capacity(int bits, bool wide);
 bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, float *out, int thr, bool wide,

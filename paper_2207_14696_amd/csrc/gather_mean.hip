@@ -145,7 +145,7 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
         launch_float<MK_UNIFORM>(p, codes, indptr, indices, V, p->d_min, p->d_scale, out, vec, s);
     } else if (kind == BIFEAT_SQ_LOG) {
         launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s);
-    } else if (p->opt_vq_sliced && launch_gather_mean_vq_sliced(p, codes, indptr, indices, V, out, s)) {
+    } else if (p->opt_vq_sliced && launch_gather_mean_vq_sliced(p, codes, indptr, indices, V, E, out, s)) {
         // vector codes, codebook slices in LDS
     } else if (p->scheme.vq_width % 4 == 0 && vec) {
         launch_float<MK_VQ4>(p, codes, indptr, indices, V, p->d_cb, nullptr, out, vec, s);

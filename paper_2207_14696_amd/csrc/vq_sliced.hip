@@ -7,9 +7,11 @@
 // codebooks of all parts do not fit one CU's LDS (786 KB at 96 x 256 x 8), so
 // the table's columns are sliced: a workgroup keeps the codebooks of SP
 // consecutive parts (<= 64 KB) in LDS and produces only those SP*width output
-// columns, for every requested row.  Different slices re-read the same packed
-// rows (SP code bytes each); the rows are small and the slices walk the request
-// list together, so those re-reads hit in L2.
+// columns, for every requested row.  So that a slice does not have to pull a
+// whole cache line out of a random packed row for its SP code bytes, a pre-pass
+// first gathers the requested rows once (whole rows, 16 bytes per lane) and
+// re-lays their codes slice-major into a scratch buffer, strips[s][i][SP]: each
+// slice then streams its own strip.
 //
 // Lane mapping: LPS = SP*width/4 lanes cover one row's slice (4 output columns,
 // one 16-byte LDS read and one 16-byte store each); a wave covers 64/LPS rows
@@ -40,11 +42,73 @@ VqGeom vq_geometry(const bifeat_params *p) {
     while (sp * 2 * len * w * 4 <= 65536 && sp * 2 * w / 4 <= 64 && sp * 2 <= 64) sp *= 2;
     while (sp > P) sp >>= 1;
     if (sp * len * w * 4 > 65536 || sp % 4) return g;  // slice's code bytes are whole dwords
+    if ((int64_t)((P + sp - 1) / sp) * sp > p->rb) return g;  // strips copy whole slices of the padded row
     g.SP = sp;
     g.NS = (P + sp - 1) / sp;
     g.LPS = sp * w / 4;
     g.ok = true;
     return g;
+}
+
+__device__ inline void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// strips[s][i][0..SP) = codes[idx[i]][s*SP .. (s+1)*SP): a wave fetches 64/c16 whole
+// rows (16 bytes per lane), parks them in LDS and writes them out slice-major, each
+// slice's piece of the tile as one contiguous run.
+__global__ __launch_bounds__(kThreads) void vq_strips_kernel(
+    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int SP,
+    int NS, uint32_t *__restrict__ strips) {
+    __shared__ uint4 s_raw[kThreads];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4 *raw = s_raw + wave * 64;
+    const int RT = 64 / c16, r = lane / c16, c = lane - r * c16;
+    const int SPW = SP >> 2, rbw = c16 * 4;  // dwords per slice piece / per row
+    const int64_t tiles = (M + RT - 1) / RT;
+    const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+    for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < tiles; tile += n_waves) {
+        const int64_t row0 = tile * RT;
+        const int nrow = (int)min((int64_t)RT, M - row0);
+        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * c16 + c];
+        wave_sync();
+        const uint32_t *raw32 = reinterpret_cast<const uint32_t *>(raw);
+        const int per_slice = nrow * SPW, total = per_slice * NS;
+        for (int u = lane; u < total; u += 64) {
+            const int sl = u / per_slice, rem = u - sl * per_slice;
+            const int rr = rem / SPW, k = rem - rr * SPW;
+            strips[((int64_t)sl * M + row0) * SPW + rem] = raw32[rr * rbw + sl * SPW + k];
+        }
+        wave_sync();
+    }
+}
+
+bool ensure_scratch(bifeat_params *p, size_t bytes) {
+    if (p->scratch_bytes >= bytes) return true;
+    if (p->d_scratch) (void)hipFree(p->d_scratch);  // waits for work that may still use it
+    p->d_scratch = nullptr;
+    p->scratch_bytes = 0;
+    void *q = nullptr;
+    if (hipMalloc(&q, bytes + bytes / 4) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    p->d_scratch = (uint8_t *)q;
+    p->scratch_bytes = bytes + bytes / 4;
+    return true;
+}
+
+void launch_strips(bifeat_params *p, const uint8_t *codes, const int64_t *idx, int64_t M,
+                   const VqGeom &g, hipStream_t s) {
+    const int c16 = (int)(p->rb / 16), RT = 64 / c16;
+    const int64_t tiles = (M + RT - 1) / RT;
+    int64_t blocks = (tiles + 3) / 4;
+    if (blocks > (1 << 16)) blocks = 1 << 16;
+    if (blocks < 1) blocks = 1;
+    vq_strips_kernel<<<(unsigned)blocks, kThreads, 0, s>>>((const uint4 *)codes, c16, idx, M, g.SP,
+                                                         g.NS, (uint32_t *)p->d_scratch);
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  All
@@ -68,11 +132,10 @@ __device__ inline void load_slice(float *s_cb, const float *__restrict__ cb, int
     __syncthreads();
 }
 
-// out[i, slice columns] = codebook entries of row idx[i]
+// out[i, slice columns] = codebook entries selected by strip s of request i
 __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
-    const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ idx, int64_t M,
-    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
-    float *__restrict__ out) {
+    const uint32_t *__restrict__ strips, int64_t M, int D, int P, int w, int len, int SP, int NS,
+    int lps_log2, const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
     int slice, by, ny;
     slice_and_lane(NS, slice, by, ny);
@@ -81,36 +144,21 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
     const int LPS = 1 << lps_log2, rpw_log2 = 6 - lps_log2;
     const int g = lane & (LPS - 1), r_in = lane >> lps_log2;
     const int pl = (4 * g) / w, dim0 = (4 * g) % w;
-    const int part = slice * SP + pl;
-    const bool active = part < P;
-    const int col = part * w + dim0;
-    const int byte_off = part & ~3, shift = 8 * (part & 3);
+    const bool active = slice * SP + pl < P;
+    const int col = (slice * SP + pl) * w + dim0;
+    const int SPW = SP >> 2, word_off = pl >> 2, shift = 8 * (pl & 3);
+    const uint32_t *strip = strips + (int64_t)slice * M * SPW + word_off;
     const float *entry0 = s_cb + (int64_t)pl * len * w + dim0;
     const int64_t tiles = (M + (1 << rpw_log2) - 1) >> rpw_log2;
     const int64_t stride = (int64_t)ny * nw;
     constexpr int U = BF_VQ_U;  // independent rows in flight per lane
-    // row ids of the next iteration are requested one iteration ahead, so that each
-    // iteration waits for one global round trip (the code words), not two
-    int64_t row[U];
-    const int64_t first = (int64_t)by * nw + wave;
-#pragma unroll
-    for (int u = 0; u < U; u++) {
-        const int64_t i = ((first + u * stride) << rpw_log2) + r_in;
-        row[u] = (active && i < M) ? idx[i] : 0;
-    }
-    for (int64_t t0 = first; t0 < tiles; t0 += stride * U) {
+    for (int64_t t0 = (int64_t)by * nw + wave; t0 < tiles; t0 += stride * U) {
         int64_t i[U];
         uint32_t word[U];
 #pragma unroll
         for (int u = 0; u < U; u++) {
             i[u] = ((t0 + u * stride) << rpw_log2) + r_in;
-            const bool ok = active && i[u] < M;
-            word[u] = ok ? *reinterpret_cast<const uint32_t *>(codes + row[u] * rb + byte_off) : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            const int64_t in = ((t0 + (U + u) * stride) << rpw_log2) + r_in;
-            row[u] = (active && in < M) ? idx[in] : 0;
+            word[u] = (active && i[u] < M) ? strip[i[u] * SPW] : 0u;
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
@@ -125,9 +173,9 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
 
 // out[v, slice columns] = mean over the list of codebook entries
 __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_sliced_kernel(
-    const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int D, int P, int w, int len, int SP,
-    int NS, int lps_log2, const float *__restrict__ cb, float *__restrict__ out) {
+    const uint32_t *__restrict__ strips, int64_t E, const int64_t *__restrict__ indptr, int64_t V,
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
+    float *__restrict__ out) {
     extern __shared__ float s_cb[];
     int slice, by, ny;
     slice_and_lane(NS, slice, by, ny);
@@ -136,10 +184,10 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_sliced_kernel(
     const int LPS = 1 << lps_log2, rpw_log2 = 6 - lps_log2;
     const int g = lane & (LPS - 1), r_in = lane >> lps_log2;
     const int pl = (4 * g) / w, dim0 = (4 * g) % w;
-    const int part = slice * SP + pl;
-    const bool active = part < P;
-    const int col = part * w + dim0;
-    const int byte_off = part & ~3, shift = 8 * (part & 3);
+    const bool active = slice * SP + pl < P;
+    const int col = (slice * SP + pl) * w + dim0;
+    const int SPW = SP >> 2, word_off = pl >> 2, shift = 8 * (pl & 3);
+    const uint32_t *strip = strips + (int64_t)slice * E * SPW + word_off;
     const float *entry0 = s_cb + (int64_t)pl * len * w + dim0;
     const int64_t tiles = (V + (1 << rpw_log2) - 1) >> rpw_log2;
     const int64_t stride = (int64_t)ny * nw;
@@ -156,10 +204,7 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_sliced_kernel(
             for (int64_t e = c0; e < c1; e += U) {
                 uint32_t word[U];
 #pragma unroll
-                for (int u = 0; u < U; u++) {
-                    const int64_t row = indices[min(e + u, c1 - 1)];
-                    word[u] = *reinterpret_cast<const uint32_t *>(codes + row * rb + byte_off);
-                }
+                for (int u = 0; u < U; u++) word[u] = strip[min(e + u, c1 - 1) * SPW];
 #pragma unroll
                 for (int u = 0; u < U; u++) {
                     const int c = (word[u] >> shift) & 0xFF;
@@ -194,7 +239,9 @@ inline int ilog2(int x) {
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                      int64_t M, float *out, hipStream_t s) {
     const VqGeom g = vq_geometry(p);
-    if (!g.ok || (uintptr_t)out % 16) return false;
+    if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
+    if (!ensure_scratch(p, (size_t)g.NS * M * g.SP)) return false;
+    launch_strips(p, codes, idx, M, g, s);
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int rpw = 64 / g.LPS;
     const int64_t tiles = (M + rpw - 1) / rpw;
@@ -204,14 +251,18 @@ bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, con
     by = (by + 7) / 8 * 8;
     const size_t shm = sizeof(float) * (size_t)g.SP * len * w;
     gather_dequant_vq_sliced_kernel<<<(unsigned)(g.NS * by), kVqThreads, shm, s>>>(
-        codes, p->rb, idx, M, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS), p->d_cb, out);
+        (const uint32_t *)p->d_scratch, M, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS),
+        p->d_cb, out);
     return true;
 }
 
 bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                                  const int64_t *indices, int64_t V, float *out, hipStream_t s) {
+                                  const int64_t *indices, int64_t V, int64_t E, float *out,
+                                  hipStream_t s) {
     const VqGeom g = vq_geometry(p);
-    if (!g.ok || (uintptr_t)out % 16) return false;
+    if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
+    if (!ensure_scratch(p, (size_t)g.NS * (E > 0 ? E : 1) * g.SP)) return false;
+    if (E > 0) launch_strips(p, codes, indices, E, g, s);
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int rpw = 64 / g.LPS;
     const int64_t tiles = (V + rpw - 1) / rpw;
@@ -221,7 +272,8 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const 
     by = (by + 7) / 8 * 8;
     const size_t shm = sizeof(float) * (size_t)g.SP * len * w;
     gather_mean_vq_sliced_kernel<<<(unsigned)(g.NS * by), kVqThreads, shm, s>>>(
-        codes, p->rb, indptr, indices, V, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS), p->d_cb, out);
+        (const uint32_t *)p->d_scratch, E, indptr, V, (int)p->D, p->P, w, len, g.SP, g.NS,
+        ilog2(g.LPS), p->d_cb, out);
     return true;
 }
 
