@@ -138,6 +138,11 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
             uint32_t w[U][CW];
 #pragma unroll
             for (int u = 0; u < U; u++) row[u] = ip[min(k + u, cnt - 1)];
+            // keep the U index loads together and unconditional (the compiler would
+            // otherwise sink each one into a branch on its slot's validity and
+            // serialise the row loads behind them)
+#pragma unroll
+            for (int u = 0; u < U; u++) asm volatile("" : "+v"(row[u]));
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 const uint8_t *src = (k + u < cnt) ? codes + (uint64_t)row[u] * rb + coff : zero_row;
