@@ -162,12 +162,12 @@ def _tables(bf, torch, kind, bits, D, N=6007, w=8, length=32, seed=6):
 CASES = [("uniform", 1, 768), ("uniform", 2, 128), ("uniform", 4, 100), ("uniform", 8, 128),
          ("uniform", 4, 37), ("uniform", 8, 5), ("uniform", 1, 70), ("uniform", 2, 1),
          ("log", 1, 64), ("log", 2, 100), ("log", 4, 37), ("log", 8, 16),
-         ("vq", 8, 64), ("vq", 8, 100), ("vq", 8, 23)]
+         ("vq", 8, 64), ("vq", 8, 100), ("vq", 8, 23), ("vq", 8, 96)]
 
 
 @pytest.mark.parametrize("kind,bits,D", CASES)
 def test_gather_codes_and_dequant(bf, torch, kind, bits, D):
-    w = 5 if D == 23 else (4 if D == 100 else 8)
+    w = {23: 5, 100: 4, 96: 16}.get(D, 8)
     q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, w=w)
     rng = np.random.default_rng(0)
     idx = rng.integers(0, codes.shape[0], 3001).astype(np.int64)
@@ -192,7 +192,7 @@ def test_gather_codes_and_dequant(bf, torch, kind, bits, D):
 
 @pytest.mark.parametrize("kind,bits,D", CASES)
 def test_gather_mean(bf, torch, kind, bits, D):
-    w = 5 if D == 23 else (4 if D == 100 else 8)
+    w = {23: 5, 100: 4, 96: 16}.get(D, 8)
     q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, w=w)
     rng = np.random.default_rng(1)
     # long lists cross the integer-accumulator capacity of every bit width
