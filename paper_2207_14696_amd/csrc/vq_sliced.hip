@@ -10,12 +10,14 @@
 // columns, for every requested row.  So that a slice does not have to pull a
 // whole cache line out of a random packed row for its SP code bytes, a pre-pass
 // first gathers the requested rows once (whole rows, 16 bytes per lane) and
-// re-lays their codes slice-major into a scratch buffer, strips[s][i][SP]: each
-// slice then streams its own strip.
+// writes them transposed at dword granularity into a scratch buffer,
+// planes[k][i] = dword k of requested row i: the lane that decodes part p of
+// consecutive requests then streams plane p/4.
 //
 // Lane mapping: LPS = SP*width/4 lanes cover one row's slice (4 output columns,
-// one 16-byte LDS read and one 16-byte store each); a wave covers 64/LPS rows
-// (gather_dequant) or destinations (gather_mean).
+// one 16-byte LDS read and one 16-byte store each; gather_mean: 8 columns where
+// the width allows); a wave covers 64/LPS rows (gather_dequant) or destinations
+// (gather_mean).
 #include "common.hpp"
 
 namespace bf {
@@ -24,6 +26,9 @@ namespace {
 
 #ifndef BF_VQ_U
 #define BF_VQ_U 4
+#endif
+#ifndef BF_VQ_SUB
+#define BF_VQ_SUB 4
 #endif
 constexpr int kVqThreads = 1024;  // 16 waves share one 64 KB codebook slice; two such groups per CU
 
@@ -58,26 +63,26 @@ __device__ inline void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Entries per strip: the request count plus slack, so that kernels may read a
+// Entries per plane: the request count plus slack, so that kernels may read a
 // few entries past the end of a list (and mask them) and the pre-pass may write
-// whole 16-byte chunks; a multiple of 16 keeps every strip 64-byte aligned.
-inline int64_t strip_entries(int64_t M) { return (M + 8 + 15) / 16 * 16; }
+// whole 16-byte chunks; a multiple of 16 keeps every plane 64-byte aligned.
+inline int64_t plane_entries(int64_t M) { return (M + 16 + 15) / 16 * 16; }
 
 constexpr int kStripK = 4;  // row batches per wave tile of the pre-pass
 
-// strips[s][i][0..SP) = codes[idx[i]][s*SP .. (s+1)*SP), strip s starting at entry
-// s*MS.  A wave fetches kStripK batches of 64/c16 whole rows (16 bytes per lane),
-// parks them in LDS and writes each slice's piece of the tile as one contiguous
+// planes[k][i] = dword k of packed row idx[i], k < NPW, plane k starting at dword
+// k*MS.  A wave fetches kStripK batches of 64/c16 whole rows (16 bytes per lane),
+// parks them in LDS and writes each plane's piece of the tile as one contiguous
 // run of 16-byte stores.
-__global__ __launch_bounds__(kThreads) void vq_strips_kernel(
-    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int SP,
-    int NS, int64_t MS, uint32_t *__restrict__ strips) {
+__global__ __launch_bounds__(kThreads) void vq_planes_kernel(
+    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int NPW,
+    int64_t MS, uint32_t *__restrict__ planes) {
     constexpr int K = kStripK;
     __shared__ uint4 s_raw[(kThreads / 64) * K * 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint4 *raw = s_raw + wave * (K * 64);
     const int RT = 64 / c16, r = lane / c16, c = lane - r * c16, TR = RT * K;
-    const int SPW = SP >> 2, spw_log2 = __ffs(SPW) - 1, rbw = c16 * 4;  // dwords per slice piece / per row
+    const int rbw = c16 * 4;  // dwords per packed row
     const int64_t tiles = (M + TR - 1) / TR;
     const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
     for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < tiles; tile += n_waves) {
@@ -95,16 +100,13 @@ __global__ __launch_bounds__(kThreads) void vq_strips_kernel(
         }
         wave_sync();
         const uint32_t *raw32 = reinterpret_cast<const uint32_t *>(raw);
-        const int chunks = (nrow * SPW + 3) >> 2, total = chunks * NS;
+        const int chunks = (nrow + 3) >> 2, total = chunks * NPW;
         for (int u = lane; u < total; u += 64) {
-            const int sl = u / chunks, j = u - sl * chunks;
+            const int pk = u / chunks, j = u - pk * chunks;
             uint32_t d[4];
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
-                const int lin = 4 * j + t, rr = min(lin >> spw_log2, TR - 1), k = lin & (SPW - 1);
-                d[t] = raw32[rr * rbw + sl * SPW + k];
-            }
-            uint4 *dst = reinterpret_cast<uint4 *>(strips + ((int64_t)sl * MS + row0) * SPW) + j;
+            for (int t = 0; t < 4; t++) d[t] = raw32[min(4 * j + t, TR - 1) * rbw + pk];
+            uint4 *dst = reinterpret_cast<uint4 *>(planes + (int64_t)pk * MS + row0) + j;
             *dst = make_uint4(d[0], d[1], d[2], d[3]);
         }
         wave_sync();
@@ -126,27 +128,24 @@ bool ensure_scratch(bifeat_params *p, size_t bytes) {
     return true;
 }
 
-void launch_strips(bifeat_params *p, const uint8_t *codes, const int64_t *idx, int64_t M,
+void launch_planes(bifeat_params *p, const uint8_t *codes, const int64_t *idx, int64_t M,
                    const VqGeom &g, hipStream_t s) {
     const int c16 = (int)(p->rb / 16), TR = (64 / c16) * kStripK;
     const int64_t tiles = (M + TR - 1) / TR;
     int64_t blocks = (tiles + 3) / 4;
     if (blocks > (1 << 16)) blocks = 1 << 16;
     if (blocks < 1) blocks = 1;
-    vq_strips_kernel<<<(unsigned)blocks, kThreads, 0, s>>>((const uint4 *)codes, c16, idx, M, g.SP,
-                                                         g.NS, strip_entries(M),
+    vq_planes_kernel<<<(unsigned)blocks, kThreads, 0, s>>>((const uint4 *)codes, c16, idx, M,
+                                                         g.NS * (g.SP >> 2), plane_entries(M),
                                                          (uint32_t *)p->d_scratch);
 }
 
-// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; the
-// slices that walk the same requests are placed on one XCD, consecutive in its
-// dispatch order, so that what they all read (the list bounds) is fetched into
-// that L2 once.
+// workgroup b serves slice b % NS as that slice's (b / NS)-th of ny workgroups
 __device__ inline void slice_and_lane(int NS, int &slice, int &by, int &ny) {
-    const int b = blockIdx.x, xcd = b & 7, j = b >> 3;
-    slice = j % NS;
-    by = (j / NS) * 8 + xcd;
-    ny = gridDim.x / NS;  // multiple of 8
+    const int b = blockIdx.x;
+    slice = b % NS;
+    by = b / NS;
+    ny = ((int)gridDim.x - slice + NS - 1) / NS;
 }
 
 // LDS layout of a slice: s_cb[c][SP*w] - for each code value c the entries c of
@@ -158,22 +157,29 @@ __device__ inline void slice_and_lane(int NS, int &slice, int &by, int &ny) {
 __device__ inline void load_slice(float *s_cb, const float *__restrict__ cb, int slice, int SP,
                                   int P, int len, int w) {
     const int parts = min(SP, P - slice * SP);
-    const int w4 = w >> 2, per_part = len * w4, n4 = parts * per_part;
+    const int w4 = w >> 2, w4_log2 = __ffs(w4) - 1, per_part = len * w4;
     const float4 *src = reinterpret_cast<const float4 *>(cb + (int64_t)slice * SP * len * w);
     float4 *dst = reinterpret_cast<float4 *>(s_cb);
-    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-        const int pl = i / per_part, rem = i - pl * per_part;
-        const int c = rem / w4, k = rem - c * w4;
-        dst[(c * SP + pl) * w4 + k] = src[i];
+    // thread -> (part, 16-byte piece) without integer division: groups of
+    // `lanes` consecutive threads walk one part
+    int lanes = 1;
+    while (lanes * 2 <= (int)blockDim.x / SP) lanes *= 2;  // SP <= 64 < blockDim.x
+    const int lanes_log2 = __ffs(lanes) - 1;
+    const int pl = threadIdx.x >> lanes_log2, t = threadIdx.x & (lanes - 1);
+    if (pl < parts) {
+        for (int i = t; i < per_part; i += lanes) {
+            const int c = i >> w4_log2, k = i & (w4 - 1);
+            dst[(c * SP + pl) * w4 + k] = src[pl * per_part + i];
+        }
     }
     for (int i = threadIdx.x; i < SP * w4; i += blockDim.x)
         dst[len * SP * w4 + i] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
 }
 
-// out[i, slice columns] = codebook entries selected by strip s of request i
+// out[i, slice columns] = codebook entries selected by the planes of request i
 __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
-    const uint32_t *__restrict__ strips, int64_t M, int64_t MS, int D, int P, int w, int len, int SP,
+    const uint32_t *__restrict__ planes, int64_t M, int64_t MS, int D, int P, int w, int len, int SP,
     int NS, int lps_log2, const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
     int slice, by, ny;
@@ -185,8 +191,8 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
     const int pl = (4 * g) / w, dim0 = (4 * g) % w;
     const bool active = slice * SP + pl < P;
     const int col = (slice * SP + pl) * w + dim0;
-    const int SPW = SP >> 2, word_off = pl >> 2, shift = 8 * (pl & 3);
-    const uint32_t *strip = strips + (int64_t)slice * MS * SPW + word_off;
+    const int SPW = SP >> 2, shift = 8 * (pl & 3);
+    const uint32_t *plane = planes + (int64_t)(slice * SPW + (pl >> 2)) * MS;
     const float *entry0 = s_cb + 4 * g;
     const int cstride = SP * w;
     const int64_t tiles = (M + (1 << rpw_log2) - 1) >> rpw_log2;
@@ -198,7 +204,7 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
 #pragma unroll
         for (int u = 0; u < U; u++) {
             i[u] = ((t0 + u * stride) << rpw_log2) + r_in;
-            word[u] = (active && i[u] < M) ? strip[i[u] * SPW] : 0u;
+            word[u] = (active && i[u] < M) ? plane[i[u]] : 0u;
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
@@ -213,58 +219,66 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
 
 // out[v, slice columns] = mean over the list of codebook entries.  A lane owns
 // CPL consecutive columns of one part (8 when the width allows: half the lanes,
-// strip loads and address arithmetic per neighbour of the 4-column form - the
-// kernel is bound by instruction issue, not by bytes).  The short form takes the
-// lists of at most kRun neighbours - every list of a sampled block whose fan-out
-// is that small - and sums and scales them in fp32; the long form takes the
-// others, fp32 runs of kRun combined in fp64.  Each skips the other's lists.
+// plane loads and address arithmetic per neighbour of the 4-column form) and
+// fetches the codes of four consecutive neighbours with one 16-byte load from
+// its plane.  Two kernels share the work: the short one takes the lists of at
+// most kRun neighbours - every list of a sampled block whose fan-out is that
+// small - and sums and scales them in fp32; the long one takes the others, fp32
+// runs of kRun combined in fp64.  Each skips the other's lists.
 constexpr int kRun = 32;
 
-template <int CPL, bool LONG>
-__global__ __launch_bounds__(kVqThreads) void gather_mean_vq_sliced_kernel(
-    const uint8_t *__restrict__ strips, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
-    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
-    float *__restrict__ out) {
-    extern __shared__ float s_cb[];
-    int slice, by, ny;
-    slice_and_lane(NS, slice, by, ny);
-    load_slice(s_cb, cb, slice, SP, P, len, w);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    const int LPS = 1 << lps_log2, rpw_log2 = 6 - lps_log2;
-    const int g = lane & (LPS - 1), r_in = lane >> lps_log2;
-    const int pl = (CPL * g) / w, dim0 = (CPL * g) % w;
-    const bool active = slice * SP + pl < P;
-    const int col = (slice * SP + pl) * w + dim0;
-    // byte offsets within the slice's strip fit 32 bits (checked by the launcher)
-    const uint8_t *strip = strips + (int64_t)slice * MS * SP;
-    const uint32_t lane_off = (uint32_t)(pl & ~3), shift = 8 * (pl & 3);
-    const uint32_t cstride = (uint32_t)(SP * w) * 4u;  // bytes between entry rows in LDS
-    const uint8_t *entry0 = reinterpret_cast<const uint8_t *>(s_cb + CPL * g);
-    const uint32_t zero_row = (uint32_t)len;
-    const int64_t tiles = (V + (1 << rpw_log2) - 1) >> rpw_log2;
-    const int64_t stride = (int64_t)ny * nw;
-    constexpr int U = BF_VQ_U;  // neighbours in flight per lane
-    constexpr int Q = CPL / 4;
+struct __attribute__((aligned(4))) Words4 {
+    uint32_t w[4];
+};
 
-    // acc += entries selected by neighbours [e0, e1); reads up to U-1 strip entries past e1
-    auto run = [&](uint32_t e0, uint32_t e1, float (&acc)[CPL]) {
-        for (uint32_t e = e0; e < e1; e += U) {
-            const uint32_t boff = e * (uint32_t)SP + lane_off;
-            uint32_t word[U];
+// per-lane constants of the mean kernels
+template <int CPL>
+struct MeanLane {
+    int slice, by, ny, lane, wave, nw, rpw_log2, g, r_in, col, cs_log2;
+    bool active;
+    const uint8_t *base, *lds;
+    uint32_t plane_off, shift, entry0, zero_row;
+
+    __device__ MeanLane(const uint32_t *planes, int64_t MS, const float *s_cb, int P, int w, int len,
+                        int SP, int NS, int lps_log2) {
+        slice_and_lane(NS, slice, by, ny);
+        lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+        rpw_log2 = 6 - lps_log2;
+        g = lane & ((1 << lps_log2) - 1), r_in = lane >> lps_log2;
+        const int pl = (CPL * g) / w, dim0 = (CPL * g) % w;
+        active = slice * SP + pl < P;
+        col = (slice * SP + pl) * w + dim0;
+        // byte offsets into the planes fit 32 bits (checked by the launcher)
+        base = reinterpret_cast<const uint8_t *>(planes);
+        plane_off = (uint32_t)((slice * (SP >> 2) + (pl >> 2)) * MS), shift = 8 * (pl & 3);
+        cs_log2 = __ffs(SP * w * 4) - 1;  // log2 of the bytes between entry rows in LDS
+        lds = reinterpret_cast<const uint8_t *>(s_cb);
+        entry0 = (uint32_t)(CPL * g * 4);
+        zero_row = (uint32_t)len;
+    }
+
+    // codes of neighbours e..e+3 (may run up to 3 entries past a list's end)
+    __device__ Words4 words(uint32_t e) const {
+        return *reinterpret_cast<const Words4 *>(base + ((plane_off + e) << 2));
+    }
+
+    // acc += the entries selected by the first min(rem, 4) codes of t, rem >= 1;
+    // BF_VQ_SUB neighbours' LDS reads in flight at a time
+    __device__ void add4(const Words4 &t, uint32_t rem, float (&acc)[CPL]) const {
+        constexpr int Q = CPL / 4;
 #pragma unroll
-            for (int u = 0; u < U; u++)
-                word[u] = *reinterpret_cast<const uint32_t *>(strip + (boff + (uint32_t)(u * SP)));
-            float4 q[U][Q];
+        for (int h = 0; h < 4; h += BF_VQ_SUB) {
+            float4 q[BF_VQ_SUB][Q];
 #pragma unroll
-            for (int u = 0; u < U; u++) {
-                uint32_t c = (word[u] >> shift) & 0xFFu;
-                c = e + u < e1 ? c : zero_row;
-                const uint8_t *ent = entry0 + c * cstride;
+            for (int u = 0; u < BF_VQ_SUB; u++) {
+                uint32_t c = (t.w[h + u] >> shift) & 0xFFu;
+                if (h + u > 0) c = (uint32_t)(h + u) < rem ? c : zero_row;
+                const uint8_t *ent = lds + ((c << cs_log2) + entry0);
 #pragma unroll
                 for (int k = 0; k < Q; k++) q[u][k] = *reinterpret_cast<const float4 *>(ent + 16 * k);
             }
 #pragma unroll
-            for (int u = 0; u < U; u++) {
+            for (int u = 0; u < BF_VQ_SUB; u++) {
 #pragma unroll
                 for (int k = 0; k < Q; k++) {
                     acc[4 * k + 0] += q[u][k].x;
@@ -273,44 +287,127 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_sliced_kernel(
                     acc[4 * k + 3] += q[u][k].w;
                 }
             }
+            if (BF_VQ_SUB < 4) asm volatile("" ::: "memory");
         }
-    };
+    }
 
-    for (int64_t tile = (int64_t)by * nw + wave; tile < tiles; tile += stride) {
-        const int64_t v = (tile << rpw_log2) + r_in;
-        if (!active || v >= V) continue;
-        const int64_t beg = indptr[v], end = indptr[v + 1];
-        const int64_t n = end - beg;
-        if (LONG ? n <= kRun : n > kRun) continue;
-        float res[CPL];
-        if constexpr (!LONG) {
+    // acc += entries selected by neighbours [e0, e1)
+    __device__ void run(uint32_t e0, uint32_t e1, float (&acc)[CPL]) const {
+        for (uint32_t e = e0; e < e1; e += 4) {
+            Words4 t = words(e);
+            // all four words in registers before the first is used (keeps the
+            // compiler from splitting the load into per-neighbour branches)
+            asm volatile("" : "+v"(t.w[0]), "+v"(t.w[1]), "+v"(t.w[2]), "+v"(t.w[3]));
+            add4(t, e1 - e, acc);
+        }
+    }
+
+    __device__ void store(float *__restrict__ out, int64_t v, int D, const float (&res)[CPL]) const {
+#pragma unroll
+        for (int k = 0; k < CPL / 4; k++)
+            store_stream(reinterpret_cast<float4 *>(out + v * D + col + 4 * k),
+                         make_float4(res[4 * k], res[4 * k + 1], res[4 * k + 2], res[4 * k + 3]));
+    }
+};
+
+// Short lists.  On this hardware a wave's loads return in issue order with its
+// stores, so a load issued after a tile's output stores would wait for them to
+// drain to memory.  The loop is therefore pipelined by hand: the list bounds of
+// the tile after next and the first kPre*4 codes of the next tile are requested
+// before the current tile's stores are issued, and are waited for only after.
+#ifndef BF_VQ_PRE
+#define BF_VQ_PRE 3
+#endif
+constexpr int kPre = BF_VQ_PRE;
+
+template <int CPL>
+__global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
+    const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
+    float *__restrict__ out) {
+    extern __shared__ float s_cb[];
+    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2);
+    load_slice(s_cb, cb, L.slice, SP, P, len, w);
+    const int64_t tiles = (V + (1 << L.rpw_log2) - 1) >> L.rpw_log2;
+    const int64_t stride = (int64_t)L.ny * L.nw;
+    using Pair = HIP_vector_type<long long, 2>;
+    // list bounds of the destination this lane serves in `tile` (clamped: always a valid address)
+    auto bounds = [&](int64_t tile) {
+        const int64_t v = min((tile << L.rpw_log2) + L.r_in, V - 1);
+        return *reinterpret_cast<const Pair *>(indptr + v);
+    };
+    int64_t tile = (int64_t)L.by * L.nw + L.wave;
+    if (tile >= tiles) return;
+    Pair ip = bounds(tile);
+    uint32_t beg = (uint32_t)ip.x, n = (uint32_t)(ip.y - ip.x);
+    Words4 cur[kPre];
+#pragma unroll
+    for (int k = 0; k < kPre; k++) cur[k] = L.words(beg + 4 * k);
+    Pair ip_next = bounds(tile + stride);
+    for (; tile < tiles; tile += stride) {
+        // requests for the tiles ahead, all issued before this tile's stores
+        const uint32_t beg1 = (uint32_t)ip_next.x, n1 = (uint32_t)(ip_next.y - ip_next.x);
+        Words4 nxt[kPre];
+#pragma unroll
+        for (int k = 0; k < kPre; k++) nxt[k] = L.words(beg1 + 4 * k);
+        ip_next = bounds(tile + 2 * stride);
+        asm volatile("" ::: "memory");
+
+        const int64_t v = (tile << L.rpw_log2) + L.r_in;
+        const bool mine = L.active && v < V && n <= (uint32_t)kRun;
+        if (mine) {
             float acc[CPL];
 #pragma unroll
             for (int k = 0; k < CPL; k++) acc[k] = 0.0f;
-            run((uint32_t)beg, (uint32_t)end, acc);
-            const float inv_n = n > 0 ? 1.0f / (float)n : 0.0f;
+#pragma unroll
+            for (int k = 0; k < kPre; k++)
+                if ((uint32_t)(4 * k) < n) L.add4(cur[k], n - 4 * k, acc);
+            if (n > 4 * kPre) L.run(beg + 4 * kPre, beg + n, acc);
+            // 1 ulp reciprocal: far inside the 1e-5 budget
+            const float inv_n = n > 0 ? __builtin_amdgcn_rcpf((float)n) : 0.0f;
+            float res[CPL];
 #pragma unroll
             for (int k = 0; k < CPL; k++) res[k] = acc[k] * inv_n;
-        } else {
-            double total[CPL];
-#pragma unroll
-            for (int k = 0; k < CPL; k++) total[k] = 0.0;
-            for (int64_t c0 = beg; c0 < end; c0 += kRun) {
-                float acc[CPL];
-#pragma unroll
-                for (int k = 0; k < CPL; k++) acc[k] = 0.0f;
-                run((uint32_t)c0, (uint32_t)min(end, c0 + kRun), acc);
-#pragma unroll
-                for (int k = 0; k < CPL; k++) total[k] += (double)acc[k];
-            }
-            const double inv_n = 1.0 / (double)n;
-#pragma unroll
-            for (int k = 0; k < CPL; k++) res[k] = (float)(total[k] * inv_n);
+            L.store(out, v, D, res);
         }
+        asm volatile("" ::: "memory");
+        beg = beg1, n = n1;
 #pragma unroll
-        for (int k = 0; k < Q; k++)
-            store_stream(reinterpret_cast<float4 *>(out + v * D + col + 4 * k),
-                         make_float4(res[4 * k], res[4 * k + 1], res[4 * k + 2], res[4 * k + 3]));
+        for (int k = 0; k < kPre; k++) cur[k] = nxt[k];
+    }
+}
+
+template <int CPL>
+__global__ __launch_bounds__(kVqThreads) void gather_mean_vq_long_kernel(
+    const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
+    float *__restrict__ out) {
+    extern __shared__ float s_cb[];
+    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2);
+    load_slice(s_cb, cb, L.slice, SP, P, len, w);
+    const int64_t tiles = (V + (1 << L.rpw_log2) - 1) >> L.rpw_log2;
+    const int64_t stride = (int64_t)L.ny * L.nw;
+    for (int64_t tile = (int64_t)L.by * L.nw + L.wave; tile < tiles; tile += stride) {
+        const int64_t v = (tile << L.rpw_log2) + L.r_in;
+        if (!L.active || v >= V) continue;
+        const int64_t beg = indptr[v], end = indptr[v + 1];
+        if (end - beg <= kRun) continue;
+        double total[CPL];
+#pragma unroll
+        for (int k = 0; k < CPL; k++) total[k] = 0.0;
+        for (int64_t c0 = beg; c0 < end; c0 += kRun) {
+            float acc[CPL];
+#pragma unroll
+            for (int k = 0; k < CPL; k++) acc[k] = 0.0f;
+            L.run((uint32_t)c0, (uint32_t)min(end, c0 + kRun), acc);
+#pragma unroll
+            for (int k = 0; k < CPL; k++) total[k] += (double)acc[k];
+        }
+        const double inv_n = 1.0 / (double)(end - beg);
+        float res[CPL];
+#pragma unroll
+        for (int k = 0; k < CPL; k++) res[k] = (float)(total[k] * inv_n);
+        L.store(out, v, D, res);
     }
 }
 
@@ -332,6 +429,15 @@ bool allow_lds(Kern kern, size_t bytes) {
     return true;
 }
 
+// workgroups: two fit a CU (LDS, registers); a few per slot so that the last
+// ones to finish leave little of the chip idle, each loading its slice once
+int sliced_grid(int64_t wave_tiles) {
+    int64_t blocks = (wave_tiles + (kVqThreads / 64) - 1) / (kVqThreads / 64);
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
 }  // namespace
 
 // All return false (nothing launched) when the codebook shape is outside what
@@ -341,59 +447,53 @@ bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, con
     const VqGeom g = vq_geometry(p);
     if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
     if (!allow_lds(gather_dequant_vq_sliced_kernel, g.lds)) return false;
-    const int64_t MS = strip_entries(M);
+    const int64_t MS = plane_entries(M);
     if (!ensure_scratch(p, (size_t)g.NS * MS * g.SP)) return false;
-    launch_strips(p, codes, idx, M, g, s);
+    launch_planes(p, codes, idx, M, g, s);
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int rpw = 64 / g.LPS;
     const int64_t tiles = (M + rpw - 1) / rpw;
-    int64_t by = (tiles + (kVqThreads / 64) * 4 - 1) / ((kVqThreads / 64) * 4);
-    const int64_t cap = (512 + g.NS - 1) / g.NS * 4;  // ~2 workgroups per CU, a few rounds
-    if (by > cap) by = cap;
-    by = (by + 7) / 8 * 8;
-    gather_dequant_vq_sliced_kernel<<<(unsigned)(g.NS * by), kVqThreads, g.lds, s>>>(
+    const int grid = sliced_grid((tiles + BF_VQ_U - 1) / BF_VQ_U * g.NS);
+    gather_dequant_vq_sliced_kernel<<<grid, kVqThreads, g.lds, s>>>(
         (const uint32_t *)p->d_scratch, M, MS, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS),
         p->d_cb, out);
     return true;
 }
 
-// max_len: the caller's bound on the list lengths (0 = unknown); with a bound
-// of at most kRun the long-list pass is not launched at all.
+// With the caller's bound on the list lengths (option mean_max_degree) at most
+// kRun, the long-list pass is not launched at all.
 bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                                   const int64_t *indices, int64_t V, int64_t E, float *out,
                                   hipStream_t s) {
     const VqGeom g = vq_geometry(p);
     if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
-    const int64_t MS = strip_entries(E);
-    if (MS * g.SP >= ((int64_t)1 << 32)) return false;  // 32-bit strip offsets
+    const int64_t MS = plane_entries(E);
+    if ((int64_t)g.NS * MS * g.SP >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int cpl = w % 8 == 0 ? 8 : 4;  // columns per lane
     const bool with_long = !(p->opt_mean_max_degree > 0 && p->opt_mean_max_degree <= kRun);
-#define BF_VQM(C, L) gather_mean_vq_sliced_kernel<C, L>
-    if (cpl == 8 ? !(allow_lds(BF_VQM(8, false), g.lds) && allow_lds(BF_VQM(8, true), g.lds))
-                 : !(allow_lds(BF_VQM(4, false), g.lds) && allow_lds(BF_VQM(4, true), g.lds)))
+    if (cpl == 8 ? !(allow_lds(gather_mean_vq_short_kernel<8>, g.lds) &&
+                     allow_lds(gather_mean_vq_long_kernel<8>, g.lds))
+                 : !(allow_lds(gather_mean_vq_short_kernel<4>, g.lds) &&
+                     allow_lds(gather_mean_vq_long_kernel<4>, g.lds)))
         return false;
     if (!ensure_scratch(p, (size_t)g.NS * MS * g.SP)) return false;
-    if (E > 0) launch_strips(p, codes, indices, E, g, s);
+    if (E > 0) launch_planes(p, codes, indices, E, g, s);
     const int lps = g.LPS * 4 / cpl, rpw = 64 / lps;
     const int64_t tiles = (V + rpw - 1) / rpw;
-    int64_t by = (tiles + (kVqThreads / 64) - 1) / (kVqThreads / 64);
-    const int64_t cap = (512 + g.NS - 1) / g.NS * 8;
-    if (by > cap) by = cap;
-    by = (by + 7) / 8 * 8;
-    const dim3 grid((unsigned)(g.NS * by));
-#define BF_VQL(C, L)                                                                          \
-    BF_VQM(C, L)<<<grid, kVqThreads, g.lds, s>>>(p->d_scratch, MS, indptr, V, (int)p->D, p->P, \
-                                                 w, len, g.SP, g.NS, ilog2(lps), p->d_cb, out)
+    const int grid = sliced_grid(tiles * g.NS);
+#define BF_VQL(KERNEL)                                                                       \
+    KERNEL<<<grid, kVqThreads, g.lds, s>>>((const uint32_t *)p->d_scratch, MS, indptr, V,     \
+                                           (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(lps),   \
+                                           p->d_cb, out)
     if (cpl == 8) {
-        BF_VQL(8, false);
-        if (with_long) BF_VQL(8, true);
+        BF_VQL(gather_mean_vq_short_kernel<8>);
+        if (with_long) BF_VQL(gather_mean_vq_long_kernel<8>);
     } else {
-        BF_VQL(4, false);
-        if (with_long) BF_VQL(4, true);
+        BF_VQL(gather_mean_vq_short_kernel<4>);
+        if (with_long) BF_VQL(gather_mean_vq_long_kernel<4>);
     }
 #undef BF_VQL
-#undef BF_VQM
     return true;
 }
 
