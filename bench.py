@@ -209,11 +209,11 @@ def main():
     b_outer = sum(sets[i % B]["bytes_mean"][outer][0] for i in range(args.steps))
     b_inner = sum(sum(x[0] for x in sets[i % B]["bytes_mean"][:outer]) for i in range(args.steps))
 
-    def roof(name, nbytes, ms, extra=None):
+    def roof(name, nbytes, ms, extra=None, profiled=True):
         ach = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         r = {"bound": "hbm", "kernel": name, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
              "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-             "traffic": traffic_from_profile(args.workload, name),
+             "traffic": traffic_from_profile(args.workload, name) if profiled else None,
              "avg_kernel_us": round(ms / args.steps * 1e3, 2),
              "algorithmic_bytes_per_launch": int(nbytes / args.steps)}
         if extra:
@@ -231,7 +231,8 @@ def main():
     }
     if outer > 0:
         kernels["gather_mean_inner_hops"] = roof("gather_mean", b_inner, t_inner,
-                                                 {"block": f"{outer} inner hop(s), one launch each"})
+                                                 {"block": f"{outer} inner hop(s), one launch each"},
+                                                 profiled=False)
     dominant = "gather_dequant" if t_deq > t_outer else "gather_mean"
     roofline = kernels[dominant]
 
