@@ -82,6 +82,12 @@ def row_bytes(ncodes: int, bits: int) -> int:
 
 
 def pack(q: np.ndarray, bits: int) -> np.ndarray:
+    if bits == 16:       # two-byte vector codes
+        q = np.ascontiguousarray(q, dtype=np.uint16)
+        rows, n = q.shape
+        out = np.empty((rows, row_bytes(n, 16)), dtype=np.uint8)
+        lib().orc_pack16(_p(q), C.c_int64(rows), C.c_int64(n), _p(out))
+        return out
     assert bits in (1, 2, 4, 8), "codes never straddle a byte"
     q = _u8(q)
     rows, n = q.shape
@@ -91,6 +97,12 @@ def pack(q: np.ndarray, bits: int) -> np.ndarray:
 
 
 def unpack(packed: np.ndarray, ncodes: int, bits: int) -> np.ndarray:
+    if bits == 16:
+        packed = _u8(packed)
+        assert packed.shape[1] == row_bytes(ncodes, 16)
+        out = np.empty((packed.shape[0], ncodes), dtype=np.uint16)
+        lib().orc_unpack16(_p(packed), C.c_int64(packed.shape[0]), C.c_int64(ncodes), _p(out))
+        return out
     assert bits in (1, 2, 4, 8)
     packed = _u8(packed)
     rows = packed.shape[0]
@@ -190,23 +202,51 @@ def vq_parts(D: int, w: int) -> int:
     return (D + w - 1) // w
 
 
-def vq_assign(x, w: int, cb) -> np.ndarray:
+METRICS = {"l2": 0, "cosine": 1}
+
+
+def vq_code_bits(length: int) -> int:
+    """Bits per stored index: one byte up to 256 entries, two beyond (Appendix D)."""
+    return 8 if length <= 256 else 16
+
+
+def vq_rnorm(cb) -> np.ndarray:
+    """1/|entry| per codebook entry (0 for an all-zero entry), [P, length] fp32."""
+    cb = _f32(cb)
+    P, length, w = cb.shape
+    out = np.empty((P, length), dtype=np.float32)
+    lib().orc_vq_rnorm(_p(cb), C.c_int64(P * length), C.c_int(w), _p(out))
+    return out
+
+
+def vq_assign(x, w: int, cb, metric: str = "l2") -> np.ndarray:
+    """Indices [rows, P]: uint8 for codebooks of up to 256 entries, else uint16."""
     x, cb = _f32(x), _f32(cb)
     rows, D = x.shape
     P, length, w2 = cb.shape
-    assert w2 == w and P == vq_parts(D, w)
+    assert w2 == w and P == vq_parts(D, w) and 2 <= length <= 16384 and w <= 256
+    if metric != "l2" or length > 256:
+        q16 = np.empty((rows, P), dtype=np.uint16)
+        lib().orc_vq_assign16(_p(x), C.c_int64(rows), C.c_int64(D), C.c_int(w), C.c_int(length),
+                              _p(cb), C.c_int(METRICS[metric]), _p(q16))
+        return q16 if length > 256 else q16.astype(np.uint8)
     q = np.empty((rows, P), dtype=np.uint8)
     lib().orc_vq_assign(_p(x), C.c_int64(rows), C.c_int64(D), C.c_int(w), C.c_int(length),
                         _p(cb), _p(q))
     return q
 
 
-def vq_train(sample, w: int, length: int, iters: int = 10):
+def vq_train(sample, w: int, length: int, iters: int = 10, metric: str = "l2"):
     """Returns (codebooks [P, length, w] fp32, distortion per Lloyd round)."""
     sample = _f32(sample)
     ns, D = sample.shape
     cb = np.zeros((vq_parts(D, w), length, w), dtype=np.float32)
     dist = np.zeros(iters, dtype=np.float64)
+    if metric != "l2":
+        lib().orc_vq_train_metric(_p(sample), C.c_int64(ns), C.c_int64(D), C.c_int(w),
+                                  C.c_int(length), C.c_int(iters), C.c_int(METRICS[metric]),
+                                  _p(cb), _p(dist))
+        return cb, dist
     lib().orc_vq_train(_p(sample), C.c_int64(ns), C.c_int64(D), C.c_int(w), C.c_int(length),
                        C.c_int(iters), _p(cb), _p(dist))
     return cb, dist
@@ -228,8 +268,8 @@ class Scheme:
         elif kind == LOG:
             assert self.a.shape == (1 << bits,)
         else:
-            assert self.cb.shape[0] == vq_parts(D, self.w) and self.len <= 256
-            self.bits = 8
+            assert self.cb.shape[0] == vq_parts(D, self.w) and self.len <= 16384
+            self.bits = vq_code_bits(self.len)
         self._c = _Scheme(kind, self.bits, self.D, self.w, self.len,
                           _p(self.a) if self.a is not None else None,
                           _p(self.b) if self.b is not None else None,

@@ -98,6 +98,27 @@ void orc_unpack(const uint8_t *packed, int64_t rows, int64_t ncodes, int bits, u
         }
 }
 
+/* Two-byte codes (vector codes with more than 256 entries per codebook;
+ * Appendix D: align to whole bytes, two bytes up to 16384 entries): code j of a
+ * row sits in bytes 2j (low) and 2j+1 (high); rows padded to 16 bytes as above. */
+void orc_pack16(const uint16_t *q, int64_t rows, int64_t ncodes, uint8_t *packed) {
+    int64_t rb = orc_row_bytes(ncodes, 16);
+    memset(packed, 0, (size_t)(rows * rb));
+    for (int64_t i = 0; i < rows; i++)
+        for (int64_t j = 0; j < ncodes; j++) {
+            packed[i * rb + 2 * j] = (uint8_t)(q[i * ncodes + j] & 0xFFu);
+            packed[i * rb + 2 * j + 1] = (uint8_t)(q[i * ncodes + j] >> 8);
+        }
+}
+
+void orc_unpack16(const uint8_t *packed, int64_t rows, int64_t ncodes, uint16_t *q) {
+    int64_t rb = orc_row_bytes(ncodes, 16);
+    for (int64_t i = 0; i < rows; i++)
+        for (int64_t j = 0; j < ncodes; j++)
+            q[i * ncodes + j] =
+                (uint16_t)(packed[i * rb + 2 * j] | ((unsigned)packed[i * rb + 2 * j + 1] << 8));
+}
+
 /* ------------------------------------------------------- uniform scalar codes
  * Sec. 3.1 names uniform quantization (evenly spaced levels) without a
  * formula.  Reading: per column j, levels min_j + q*scale_j, q = 0..L,
@@ -249,7 +270,8 @@ void orc_log_encode_direct(const float *x, int64_t n, int k, double e_min, doubl
  * Sec. 3.2 / Appendix D: D dims are split into P = ceil(D/w) parts of w dims
  * (a short last part is zero-padded); part p of a row is replaced by the index
  * of its nearest entry in that part's codebook of `len` entries (Euclidean
- * distance; len <= 256, one byte per part as the paper advises).
+ * distance; len <= 256, one byte per part as the paper advises; larger
+ * codebooks and the cosine metric follow further down).
  * The squared distance is accumulated in fp32, dimension ascending, multiply
  * and add rounded separately; ties go to the lowest index. */
 static int vq_nearest(const float *sub, const float *cb, int w, int len, float *best_out) {
@@ -348,6 +370,126 @@ void orc_vq_train(const float *sample, int64_t ns, int64_t D, int w, int len, in
     free(dpart);
 }
 
+/* ---- the variants of Sec. 3.2 / Appendix D beyond one-byte Euclidean codes
+ * Metric.  Sec. 3.2 allows Euclidean distance or cosine similarity for the
+ * nearest-entry search and says no more.  Reading for cosine: the part takes
+ * the entry with the largest (x . C_c) / |C_c|; the row's own norm is a common
+ * positive factor and is left out (an all-zero part scores 0 everywhere and
+ * takes entry 0); an all-zero entry scores 0.  The dot product is accumulated
+ * in fp32, dimension ascending, multiply and add rounded separately, then
+ * multiplied by rnorm_c = fp32(1 / sqrt(sum_d C_cd^2)) with the sum and the
+ * root in fp64; ties go to the lowest index.  Codebook entries stay plain
+ * arithmetic means of their members and decoding returns the entry as it is.
+ * Codebook size.  More than 256 entries (up to 16384) take two bytes per part. */
+enum { ORC_L2 = 0, ORC_COSINE = 1 };
+
+void orc_vq_rnorm(const float *cb, int64_t entries, int w, float *rnorm) {
+    for (int64_t c = 0; c < entries; c++) {
+        double ss = 0.0;
+        for (int d = 0; d < w; d++) ss += (double)cb[c * w + d] * (double)cb[c * w + d];
+        rnorm[c] = (ss > 0.0) ? (float)(1.0 / sqrt(ss)) : 0.0f;
+    }
+}
+
+static int vq_most_similar(const float *sub, const float *cb, const float *rnorm, int w, int len) {
+    int best = 0;
+    float bests = -INFINITY;
+    for (int c = 0; c < len; c++) {
+        float dot = 0.0f;
+        for (int d = 0; d < w; d++) {
+            float pr = sub[d] * cb[c * w + d];
+            dot = dot + pr;
+        }
+        float score = dot * rnorm[c];
+        if (score > bests) {
+            bests = score;
+            best = c;
+        }
+    }
+    return best;
+}
+
+/* codes as 16-bit integers whatever the codebook size; metric: ORC_L2 / ORC_COSINE */
+void orc_vq_assign16(const float *x, int64_t rows, int64_t D, int w, int len, const float *cb,
+                     int metric, uint16_t *q) {
+    int P = (int)((D + w - 1) / w);
+    float *rnorm = NULL;
+    if (metric == ORC_COSINE) {
+        rnorm = (float *)malloc(sizeof(float) * (size_t)P * (size_t)len);
+        orc_vq_rnorm(cb, (int64_t)P * len, w, rnorm);
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; i++) {
+        float sub[256];
+        for (int p = 0; p < P; p++) {
+            const float *C = cb + (int64_t)p * len * w;
+            load_part(x + i * D, D, p, w, sub);
+            q[i * P + p] = (uint16_t)(metric == ORC_COSINE
+                                          ? vq_most_similar(sub, C, rnorm + (int64_t)p * len, w, len)
+                                          : vq_nearest(sub, C, w, len, NULL));
+        }
+    }
+    free(rnorm);
+}
+
+/* Lloyd rounds as orc_vq_train, the assignment step by `metric`.  distortion[it]
+ * is the mean squared Euclidean distance between a part and its assigned entry
+ * (the decoding error), fp64, summed over parts, for either metric. */
+void orc_vq_train_metric(const float *sample, int64_t ns, int64_t D, int w, int len, int iters,
+                         int metric, float *cb, double *distortion) {
+    int P = (int)((D + w - 1) / w);
+    double *dpart = (double *)calloc((size_t)iters * (size_t)P, sizeof(double));
+#pragma omp parallel for schedule(dynamic)
+    for (int p = 0; p < P; p++) {
+        float *C = cb + (int64_t)p * len * w;
+        float sub[256];
+        int have = 0;
+        for (int64_t i = 0; i < ns && have < len; i++) {
+            load_part(sample + i * D, D, p, w, sub);
+            int dup = 0;
+            for (int c = 0; c < have && !dup; c++)
+                dup = (memcmp(C + c * w, sub, sizeof(float) * (size_t)w) == 0);
+            if (!dup) memcpy(C + (have++) * w, sub, sizeof(float) * (size_t)w);
+        }
+        for (int c = have; c < len; c++)
+            memcpy(C + c * w, C + (have - 1) * w, sizeof(float) * (size_t)w);
+
+        double *sum = (double *)malloc(sizeof(double) * (size_t)len * (size_t)w);
+        int64_t *cnt = (int64_t *)malloc(sizeof(int64_t) * (size_t)len);
+        float *rnorm = (float *)malloc(sizeof(float) * (size_t)len);
+        for (int it = 0; it < iters; it++) {
+            memset(sum, 0, sizeof(double) * (size_t)len * (size_t)w);
+            memset(cnt, 0, sizeof(int64_t) * (size_t)len);
+            if (metric == ORC_COSINE) orc_vq_rnorm(C, len, w, rnorm);
+            double dsum = 0.0;
+            for (int64_t i = 0; i < ns; i++) {
+                load_part(sample + i * D, D, p, w, sub);
+                int c = (metric == ORC_COSINE) ? vq_most_similar(sub, C, rnorm, w, len)
+                                               : vq_nearest(sub, C, w, len, NULL);
+                for (int d = 0; d < w; d++) {
+                    double diff = (double)sub[d] - (double)C[c * w + d];
+                    dsum += diff * diff;
+                }
+                cnt[c]++;
+                for (int d = 0; d < w; d++) sum[c * w + d] += (double)sub[d];
+            }
+            for (int c = 0; c < len; c++)
+                if (cnt[c] > 0)
+                    for (int d = 0; d < w; d++)
+                        C[c * w + d] = (float)(sum[c * w + d] / (double)cnt[c]);
+            dpart[(size_t)it * (size_t)P + (size_t)p] = dsum / (double)ns;
+        }
+        free(sum);
+        free(cnt);
+        free(rnorm);
+    }
+    for (int it = 0; it < iters; it++) {
+        distortion[it] = 0.0;
+        for (int p = 0; p < P; p++) distortion[it] += dpart[(size_t)it * (size_t)P + (size_t)p];
+    }
+    free(dpart);
+}
+
 /* ------------------------------------------------------------------ decoding */
 static inline unsigned code_at(const uint8_t *row, int64_t j, int bits) {
     int64_t bit = j * bits;
@@ -364,13 +506,15 @@ static void decode_row(const orc_scheme *s, const uint8_t *row, double *out) {
     } else {
         for (int64_t j = 0; j < s->D; j++) {
             int64_t p = j / s->w, d = j % s->w;
-            out[j] = (double)s->cb[(p * s->len + row[p]) * s->w + d];
+            int64_t q = (s->len > 256) ? (int64_t)(row[2 * p] | ((unsigned)row[2 * p + 1] << 8))
+                                       : (int64_t)row[p];
+            out[j] = (double)s->cb[(p * s->len + q) * s->w + d];
         }
     }
 }
 
 int64_t orc_scheme_row_bytes(const orc_scheme *s) {
-    if (s->kind == ORC_VQ) return orc_row_bytes((s->D + s->w - 1) / s->w, 8);
+    if (s->kind == ORC_VQ) return orc_row_bytes((s->D + s->w - 1) / s->w, s->len > 256 ? 16 : 8);
     return orc_row_bytes(s->D, s->bits);
 }
 
