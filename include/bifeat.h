@@ -26,7 +26,9 @@
  *   - Packed layout (the paper fixes none; Appendix D only advises against
  *     elaborate bit packing): row-major; scalar codes: column j's `bits`-bit
  *     code at bit (j*bits) mod 8 of byte floor(j*bits/8), column 0 in the
- *     least significant bits; vector codes: byte p = codebook index of part p;
+ *     least significant bits; vector codes: byte p = codebook index of part p
+ *     (codebooks of more than 256 entries: bytes 2p, 2p+1 = the index, low
+ *     byte first - the whole-byte alignment of Appendix D);
  *     row stride bifeat_row_bytes() = payload rounded up to 16 bytes, pad = 0.
  */
 #ifndef BIFEAT_H
@@ -59,12 +61,21 @@ typedef enum {
 
 typedef enum { BIFEAT_F32 = 0, BIFEAT_F16 = 1 } bifeat_dtype;
 
+/* Sec. 3.2: the nearest codebook entry is found "by Euclidean distance or
+ * cosine similarity".  Cosine: the entry with the largest (x . C_c)/|C_c| (the
+ * part's own norm is a common positive factor and is left out; an all-zero part
+ * or entry scores 0); entries stay arithmetic means of their members and decode
+ * returns the entry unchanged. */
+typedef enum { BIFEAT_VQ_L2 = 0, BIFEAT_VQ_COSINE = 1 } bifeat_vq_metric;
+
 typedef struct {
     int32_t kind;      /* bifeat_kind */
     int32_t bits;      /* scalar kinds: 1, 2, 4 or 8 bits per value */
-    int32_t vq_width;  /* BIFEAT_VQ: dims per part (1..64); P = ceil(D/width) parts */
-    int32_t vq_length; /* BIFEAT_VQ: entries per codebook (2..256: one byte per part,
-                          the alignment Appendix D recommends) */
+    int32_t vq_width;  /* BIFEAT_VQ: dims per part (1..128); P = ceil(D/width) parts, a short
+                          last part is zero-padded */
+    int32_t vq_length; /* BIFEAT_VQ: entries per codebook: 2..256 stored as one byte per
+                          part, 257..16384 as two (Appendix D) */
+    int32_t vq_metric; /* BIFEAT_VQ: bifeat_vq_metric */
 } bifeat_scheme;
 
 /* Opaque quantizer state: scheme, D, fitted parameters (host + device copies).
@@ -98,9 +109,12 @@ int64_t bifeat_codes_per_row(const bifeat_params *p);
  *   reset seeds every part's codebook with the sub-vectors of its first
  *   `vq_length` rows (it must have at least that many); every update then runs
  *   Lloyd rounds over its chunk (10, option "vq_iters"): nearest entry by the
- *   encoder's distance rule, entry = mean of its members, an entry without
- *   members keeps its value.  Sums are accumulated with fp32 atomics, so the
- *   codebooks are reproducible in distortion, not bit for bit.
+ *   encoder's rule for the scheme's metric, entry = mean of its members, an
+ *   entry without members keeps its value.  Sums are accumulated with fp32
+ *   atomics, so the codebooks are reproducible in distortion, not bit for bit.
+ *   Training a large or cosine codebook uses library scratch (two bytes per
+ *   part and sample row).  finalize synchronises `stream` for the cosine metric
+ *   (the entry norms are evaluated on the host in fp64).
  * finalize without any update returns BIFEAT_ENOTFIT. */
 int bifeat_fit_reset(bifeat_params *p, void *stream);
 int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
@@ -122,9 +136,10 @@ int bifeat_params_set_log(bifeat_params *p, double e_min, double e_max);
 int bifeat_params_get_log(bifeat_params *p, double *e_min, double *e_max, float *T, float *V);
 int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks);
 int bifeat_params_get_codebooks(bifeat_params *p, float *codebooks);
-/* BIFEAT_VQ: mean squared distance (summed over parts) of each Lloyd round's
- * assignment step in the last bifeat_fit_update; out: HOST [n], n <= 64.
- * Synchronises the device. */
+/* BIFEAT_VQ: mean squared Euclidean distance between a part and its assigned
+ * entry (summed over parts, either metric) at each Lloyd round's assignment
+ * step of the last bifeat_fit_update; out: HOST [n], n <= 64.  Synchronises
+ * the device. */
 int bifeat_vq_distortion(bifeat_params *p, float *out, int32_t n);
 
 /* ---- encode + pack one chunk (Sec. 3.1 Eq. (1); Sec. 3.2 nearest entry).
@@ -138,7 +153,9 @@ int bifeat_vq_distortion(bifeat_params *p, float *out, int32_t n);
  *   groups them).
  * BIFEAT_VQ: per part, index of the entry with the smallest squared Euclidean
  *   distance (fp32, dims ascending, multiply and add rounded separately; ties
- *   to the lowest index; a short last part is zero-padded). */
+ *   to the lowest index; a short last part is zero-padded); cosine metric:
+ *   the largest fp32 dot product (same accumulation) times
+ *   fp32(1/sqrt(sum_d C_cd^2)), sum and root in fp64. */
 int bifeat_quantize(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
                     uint8_t *codes, int64_t row0, void *stream);
 

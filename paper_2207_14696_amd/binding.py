@@ -13,6 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("BIFEAT_LIB") or os.path.join(_HERE, "libbifeat.so")
 
 UNIFORM, LOG, VQ = 0, 1, 2
+VQ_L2, VQ_COSINE = 0, 1
 F32, F16 = 0, 1
 OK, EINVAL, ENOTFIT, EHIP, ENOTSUP = 0, -1, -2, -3, -4
 
@@ -25,7 +26,7 @@ class BifeatError(RuntimeError):
 
 class _CScheme(C.Structure):
     _fields_ = [("kind", C.c_int32), ("bits", C.c_int32),
-                ("vq_width", C.c_int32), ("vq_length", C.c_int32)]
+                ("vq_width", C.c_int32), ("vq_length", C.c_int32), ("vq_metric", C.c_int32)]
 
 
 @dataclass(frozen=True)
@@ -34,6 +35,7 @@ class Scheme:
     bits: int = 8
     vq_width: int = 0
     vq_length: int = 0
+    vq_metric: int = 0
 
 
 _lib = None
@@ -117,7 +119,7 @@ class Quantizer:
         self._lib = load_library()
         self.scheme, self.D = scheme, int(D)
         h = C.c_void_p()
-        cs = _CScheme(scheme.kind, scheme.bits, scheme.vq_width, scheme.vq_length)
+        cs = _CScheme(scheme.kind, scheme.bits, scheme.vq_width, scheme.vq_length, scheme.vq_metric)
         _check(self._lib.bifeat_params_create(C.byref(cs), self.D, C.byref(h)))
         self._h = h
 

@@ -29,7 +29,9 @@ bool scheme_ok(const bifeat_scheme *s, int64_t D) {
     if (s->kind == BIFEAT_SQ_UNIFORM || s->kind == BIFEAT_SQ_LOG)
         return s->bits == 1 || s->bits == 2 || s->bits == 4 || s->bits == 8;
     if (s->kind == BIFEAT_VQ)
-        return s->vq_width >= 1 && s->vq_width <= 64 && s->vq_length >= 2 && s->vq_length <= 256;
+        return s->vq_width >= 1 && s->vq_width <= 128 && s->vq_length >= 2 &&
+               s->vq_length <= 16384 &&
+               (s->vq_metric == BIFEAT_VQ_L2 || s->vq_metric == BIFEAT_VQ_COSINE);
     return false;
 }
 
@@ -43,7 +45,7 @@ int ensure_device(bifeat_params *p) {
     size_t nfloat = 0, nfit = 0;
     if (p->scheme.kind == BIFEAT_SQ_UNIFORM) { nfloat = 4 * D; nfit = 2 * D; }
     else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 2; }
-    else nfloat = (size_t)p->P * p->scheme.vq_length * (2 * p->scheme.vq_width + 1) + 64;
+    else nfloat = (size_t)p->P * p->scheme.vq_length * (2 * p->scheme.vq_width + 2) + 64;
     nfloat = (nfloat + 3) / 4 * 4;
     nfit = (nfit + 3) / 4 * 4;
     void *blk = nullptr;
@@ -61,9 +63,11 @@ int ensure_device(bifeat_params *p) {
         p->d_V = p->d_block + 128;
     } else {
         const size_t ncb = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
+        const size_t nent = (size_t)p->P * p->scheme.vq_length;
         p->d_cb = p->d_block;
-        p->d_train = p->d_block + ncb;
-        p->d_dist = p->d_train + ncb + (size_t)p->P * p->scheme.vq_length;
+        p->d_rnorm = p->d_block + ncb;
+        p->d_train = p->d_rnorm + nent;
+        p->d_dist = p->d_train + ncb + nent;
     }
     p->d_fit = reinterpret_cast<int32_t *>(p->d_block + nfloat);
     p->d_zero = reinterpret_cast<uint8_t *>(p->d_fit + nfit);
@@ -107,6 +111,31 @@ int sync_uniform_host(bifeat_params *p) {
     return BIFEAT_OK;
 }
 
+// cosine metric: reciprocal entry norms from the host copy of the codebooks,
+// fp32(1/sqrt(sum of squares)) with the sum and the root in fp64
+int upload_rnorm(bifeat_params *p) {
+    if (p->scheme.vq_metric != BIFEAT_VQ_COSINE) return BIFEAT_OK;
+    const size_t nent = (size_t)p->P * p->scheme.vq_length, w = (size_t)p->scheme.vq_width;
+    p->h_rnorm.resize(nent);
+    for (size_t c = 0; c < nent; c++) {
+        double ss = 0.0;
+        for (size_t d = 0; d < w; d++) ss += (double)p->h_cb[c * w + d] * (double)p->h_cb[c * w + d];
+        p->h_rnorm[c] = ss > 0.0 ? (float)(1.0 / sqrt(ss)) : 0.0f;
+    }
+    BF_HIP(hipMemcpy(p->d_rnorm, p->h_rnorm.data(), 4 * nent, hipMemcpyHostToDevice));
+    return BIFEAT_OK;
+}
+
+int sync_codebooks_host(bifeat_params *p) {
+    if (p->host_valid) return BIFEAT_OK;
+    const size_t n = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
+    p->h_cb.resize(n);
+    BF_HIP(hipDeviceSynchronize());
+    BF_HIP(hipMemcpy(p->h_cb.data(), p->d_cb, 4 * n, hipMemcpyDeviceToHost));
+    p->host_valid = true;
+    return BIFEAT_OK;
+}
+
 bool dtype_ok(int32_t d) { return d == BIFEAT_F32 || d == BIFEAT_F16; }
 
 }  // namespace
@@ -124,8 +153,9 @@ int bifeat_params_create(const bifeat_scheme *scheme, int64_t D, bifeat_params *
     if (scheme->kind == BIFEAT_VQ) {
         p->P = (int)((D + scheme->vq_width - 1) / scheme->vq_width);
         p->ncodes = p->P;
-        p->rb = round16(p->P);
-        p->scheme.bits = 8;
+        p->cbytes = scheme->vq_length <= 256 ? 1 : 2;
+        p->rb = round16((int64_t)p->P * p->cbytes);
+        p->scheme.bits = 8 * p->cbytes;
     } else {
         p->ncodes = D;
         p->rb = round16((D * scheme->bits + 7) / 8);
@@ -204,6 +234,12 @@ int bifeat_fit_finalize(bifeat_params *p, void *stream) {
     if (!p->fit_open || p->fit_rows == 0) return BIFEAT_ENOTFIT;
     if (p->scheme.kind == BIFEAT_VQ) {
         p->host_valid = false;  // codebooks live on the device until asked for
+        if (p->scheme.vq_metric == BIFEAT_VQ_COSINE) {
+            // the encoder's entry norms come from the host, as for injected codebooks
+            int rc = sync_codebooks_host(p);
+            if (!rc) rc = upload_rnorm(p);
+            if (rc) return rc;
+        }
     } else if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
         BF_HIP(bf::launch_finalize_uniform(p, (hipStream_t)stream));
         p->host_valid = false;
@@ -304,6 +340,8 @@ int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks) {
     int rc = ensure_device(p);
     if (rc) return rc;
     BF_HIP(hipMemcpy(p->d_cb, p->h_cb.data(), 4 * n, hipMemcpyHostToDevice));
+    rc = upload_rnorm(p);
+    if (rc) return rc;
     p->host_valid = true;
     p->fitted = true;
     return BIFEAT_OK;
@@ -312,13 +350,8 @@ int bifeat_params_set_codebooks(bifeat_params *p, const float *codebooks) {
 int bifeat_params_get_codebooks(bifeat_params *p, float *codebooks) {
     if (!p || p->scheme.kind != BIFEAT_VQ) return BIFEAT_EINVAL;
     if (!p->fitted) return BIFEAT_ENOTFIT;
-    if (!p->host_valid) {
-        const size_t n = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
-        p->h_cb.resize(n);
-        BF_HIP(hipDeviceSynchronize());
-        BF_HIP(hipMemcpy(p->h_cb.data(), p->d_cb, 4 * n, hipMemcpyDeviceToHost));
-        p->host_valid = true;
-    }
+    int rc = sync_codebooks_host(p);
+    if (rc) return rc;
     if (codebooks) memcpy(codebooks, p->h_cb.data(), 4 * p->h_cb.size());
     return BIFEAT_OK;
 }

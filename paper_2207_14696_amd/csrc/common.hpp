@@ -16,12 +16,14 @@ struct bifeat_params {
     int64_t ncodes = 0;  // codes per row: D, or P for vector codes
     int64_t rb = 0;      // packed bytes per row, multiple of 16
     int P = 0;           // vector codes: number of parts
+    int cbytes = 1;      // vector codes: bytes per stored index (2 beyond 256 entries)
 
     // host copies (valid when host_valid)
     std::vector<float> h_min, h_max, h_scale, h_inv;  // uniform, [D] each
     double e_min = 0.0, e_max = 0.0;                  // log
     std::vector<float> h_T, h_V;                      // log: [H-1], [2^bits]
     std::vector<float> h_cb;                          // vq: [P][len][w]
+    std::vector<float> h_rnorm;                       // vq, cosine metric: 1/|entry|, [P][len]
     bool host_valid = false;
 
     // device block (allocated on first GPU use)
@@ -29,6 +31,7 @@ struct bifeat_params {
     float *d_block = nullptr;
     float *d_min = nullptr, *d_scale = nullptr, *d_inv = nullptr, *d_max = nullptr;
     float *d_T = nullptr, *d_V = nullptr, *d_cb = nullptr;
+    float *d_rnorm = nullptr;   // vq, cosine metric: [P][len]
     float *d_train = nullptr;   // vq training scratch: sums [P][len][w], counts [P][len]
     float *d_dist = nullptr;    // vq training: summed squared distance per Lloyd round (64 slots)
     uint8_t *d_scratch = nullptr;  // grow-only workspace (vector codes: slice-major code strips)
@@ -81,6 +84,15 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
 void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
                              int min_len, hipStream_t s);
+// grow-only library workspace (p->d_scratch); false if the allocation fails
+bool ensure_scratch(bifeat_params *p, size_t bytes);
+// 1/|entry| for every codebook entry, fp64 inside (cosine metric)
+void launch_vq_rnorm(bifeat_params *p, hipStream_t s);
+// nearest-entry search of `rows` rows into codes_row0 (row stride rb bytes, indices of
+// `cbytes` bytes; bytes from P*cbytes to rb are zeroed)
+template <typename T>
+void launch_vq_assign(bifeat_params *p, const T *x, int64_t rows, uint8_t *codes_row0, int64_t rb,
+                      hipStream_t s);
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                      int64_t M, float *out, hipStream_t s);
 bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,

@@ -290,74 +290,125 @@ static void launch_sq(const T *x, int64_t rows, int D, int64_t rb, int bits, Cod
 #undef BF_Q
 }
 
-// ------------------------------------------------------------- vector encoder
-// Block = one part p (its codebook in LDS) x 256 rows; a thread scans all
-// entries for its row.  Distance: fp32, dims ascending, subtract / multiply /
-// add rounded separately; strict < keeps the lowest index on ties.
-template <typename T, int W>
-__global__ __launch_bounds__(kThreads) void vq_assign_kernel(const T *__restrict__ x, int64_t rows,
-                                                            int D, int w_rt, int len, int P,
-                                                            const float *__restrict__ cb,
-                                                            uint8_t *__restrict__ codes,
-                                                            int64_t rb) {
+// Vector codes (Sec. 3.2): workgroup = one part x strips of 256 rows, thread =
+// one row whose sub-vector stays in registers; the part's codebook passes
+// through LDS in chunks of EC entries (all of it at once when it fits), read
+// by all threads at the same address (broadcast).  Euclidean: fp32, dims
+// ascending, subtract / multiply / add rounded separately, strict < keeps the
+// lowest index on ties.  Cosine: fp32 dot product accumulated the same way,
+// times the entry's reciprocal norm, strict > keeps the lowest index.
+// W > 0: the width, known at compile time; W == 0: any width up to WMAX.
+template <typename T, int W, int WMAX, int METRIC, typename CODE>
+__global__ __launch_bounds__(kThreads) void vq_assign_kernel(
+    const T *__restrict__ x, int64_t rows, int D, int w_rt, int len, int P, int EC,
+    const float *__restrict__ cb, const float *__restrict__ rnorm, uint8_t *__restrict__ codes,
+    int64_t rb) {
     extern __shared__ float s_cb[];
     const int w = W > 0 ? W : w_rt;
+    float *s_rn = s_cb + EC * w;
     const int p = blockIdx.x;
-    for (int i = threadIdx.x; i < len * w; i += kThreads) s_cb[i] = cb[(int64_t)p * len * w + i];
-    __syncthreads();
-    for (int64_t r = (int64_t)blockIdx.y * kThreads + threadIdx.x; r < rows;
-         r += (int64_t)gridDim.y * kThreads) {
-        const T *src = x + r * D + (int64_t)p * w;
+    const float *part_cb = cb + (int64_t)p * len * w;
+    const bool single = len <= EC;
+    auto stage = [&](int e0, int ec) {
+        for (int i = threadIdx.x; i < ec * w; i += kThreads) s_cb[i] = part_cb[(int64_t)e0 * w + i];
+        if constexpr (METRIC == BIFEAT_VQ_COSINE)
+            for (int i = threadIdx.x; i < ec; i += kThreads) s_rn[i] = rnorm[(int64_t)p * len + e0 + i];
+    };
+    if (single) {
+        stage(0, len);
+        __syncthreads();
+    }
+    // every thread of the workgroup walks the same strips (the chunk loads synchronise)
+    for (int64_t r0 = (int64_t)blockIdx.y * kThreads; r0 < rows; r0 += (int64_t)gridDim.y * kThreads) {
+        const int64_t r = r0 + threadIdx.x;
+        const bool valid = r < rows;
+        float sub[WMAX];
+#pragma unroll
+        for (int d = 0; d < WMAX; d++)
+            sub[d] = (valid && d < w && p * w + d < D) ? load1(x + r * D + (int64_t)p * w + d) : 0.0f;
         int best = 0;
-        float bestd = INFINITY;
-        if constexpr (W > 0) {
-            float sub[W];
-#pragma unroll
-            for (int d = 0; d < W; d++) sub[d] = (p * W + d < D) ? load1(src + d) : 0.0f;
-            for (int c = 0; c < len; c++) {
-                float dist = 0.0f;
-#pragma unroll
-                for (int d = 0; d < W; d++) {
-                    float diff = __fsub_rn(sub[d], s_cb[c * W + d]);
-                    dist = __fadd_rn(dist, __fmul_rn(diff, diff));
-                }
-                if (dist < bestd) { bestd = dist; best = c; }
+        float bestv = METRIC == BIFEAT_VQ_COSINE ? -INFINITY : INFINITY;
+        for (int e0 = 0; e0 < len; e0 += EC) {
+            const int ec = min(EC, len - e0);
+            if (!single) {
+                __syncthreads();
+                stage(e0, ec);
+                __syncthreads();
             }
-        } else {
-            for (int c = 0; c < len; c++) {
-                float dist = 0.0f;
-                for (int d = 0; d < w; d++) {
-                    float xv = (p * w + d < D) ? load1(src + d) : 0.0f;
-                    float diff = __fsub_rn(xv, s_cb[c * w + d]);
-                    dist = __fadd_rn(dist, __fmul_rn(diff, diff));
+            for (int c = 0; c < ec; c++) {
+                const float *ent = s_cb + c * w;
+                float acc = 0.0f;
+#pragma unroll
+                for (int d = 0; d < WMAX; d++) {
+                    if (W > 0 || d < w) {  // uniform; sub[] stays in registers
+                        if constexpr (METRIC == BIFEAT_VQ_COSINE) {
+                            acc = __fadd_rn(acc, __fmul_rn(sub[d], ent[d]));
+                        } else {
+                            const float diff = __fsub_rn(sub[d], ent[d]);
+                            acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                        }
+                    }
                 }
-                if (dist < bestd) { bestd = dist; best = c; }
+                if constexpr (METRIC == BIFEAT_VQ_COSINE) {
+                    acc = __fmul_rn(acc, s_rn[c]);
+                    if (acc > bestv) { bestv = acc; best = e0 + c; }
+                } else {
+                    if (acc < bestv) { bestv = acc; best = e0 + c; }
+                }
             }
         }
-        codes[r * rb + p] = (uint8_t)best;
-        if (p == 0)
-            for (int64_t b = P; b < rb; b++) codes[r * rb + b] = 0;  // row padding
+        if (valid) {
+            reinterpret_cast<CODE *>(codes + r * rb)[p] = (CODE)best;
+            if (p == 0)
+                for (int64_t b = (int64_t)P * sizeof(CODE); b < rb; b++) codes[r * rb + b] = 0;  // row padding
+        }
     }
 }
 
-template <typename T>
-static void launch_vq(const T *x, int64_t rows, bifeat_params *p, uint8_t *codes, hipStream_t s) {
+template <typename T, int W, int WMAX>
+static void launch_vq_w(bifeat_params *p, const T *x, int64_t rows, uint8_t *codes, int64_t rb,
+                        hipStream_t s) {
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
+    const bool cosine = p->scheme.vq_metric == BIFEAT_VQ_COSINE;
+    int EC = 32768 / (4 * w);  // entries per LDS chunk: 32 KB of entries
+    if (EC > len) EC = len;
     int64_t tiles = (rows + kThreads - 1) / kThreads;
     dim3 grid((unsigned)p->P, (unsigned)(tiles > 4096 ? 4096 : tiles));
-    size_t shm = sizeof(float) * (size_t)len * (size_t)w;
-#define BF_VQ(W) \
-    vq_assign_kernel<T, W><<<grid, kThreads, shm, s>>>(x, rows, (int)p->D, w, len, p->P, p->d_cb, codes, p->rb)
-    switch (w) {
-        case 1: BF_VQ(1); break;
-        case 2: BF_VQ(2); break;
-        case 4: BF_VQ(4); break;
-        case 8: BF_VQ(8); break;
-        case 16: BF_VQ(16); break;
-        default: BF_VQ(0); break;
+    const size_t shm = sizeof(float) * ((size_t)EC * w + (cosine ? EC : 0));
+#define BF_VQ(M, CODE)                                                                   \
+    vq_assign_kernel<T, W, WMAX, M, CODE><<<grid, kThreads, shm, s>>>(                  \
+        x, rows, (int)p->D, w, len, p->P, EC, p->d_cb, p->d_rnorm, codes, rb)
+    if (p->cbytes == 1) {
+        if (cosine) BF_VQ(BIFEAT_VQ_COSINE, uint8_t);
+        else BF_VQ(BIFEAT_VQ_L2, uint8_t);
+    } else {
+        if (cosine) BF_VQ(BIFEAT_VQ_COSINE, uint16_t);
+        else BF_VQ(BIFEAT_VQ_L2, uint16_t);
     }
 #undef BF_VQ
 }
+
+template <typename T>
+void launch_vq_assign(bifeat_params *p, const T *x, int64_t rows, uint8_t *codes, int64_t rb,
+                      hipStream_t s) {
+    const int w = p->scheme.vq_width;
+    switch (w) {
+        case 1: launch_vq_w<T, 1, 1>(p, x, rows, codes, rb, s); break;
+        case 2: launch_vq_w<T, 2, 2>(p, x, rows, codes, rb, s); break;
+        case 4: launch_vq_w<T, 4, 4>(p, x, rows, codes, rb, s); break;
+        case 8: launch_vq_w<T, 8, 8>(p, x, rows, codes, rb, s); break;
+        case 16: launch_vq_w<T, 16, 16>(p, x, rows, codes, rb, s); break;
+        default:
+            if (w <= 32) launch_vq_w<T, 0, 32>(p, x, rows, codes, rb, s);
+            else if (w <= 64) launch_vq_w<T, 0, 64>(p, x, rows, codes, rb, s);
+            else launch_vq_w<T, 0, 128>(p, x, rows, codes, rb, s);
+            break;
+    }
+}
+template void launch_vq_assign<float>(bifeat_params *, const float *, int64_t, uint8_t *, int64_t,
+                                      hipStream_t);
+template void launch_vq_assign<__half>(bifeat_params *, const __half *, int64_t, uint8_t *, int64_t,
+                                       hipStream_t);
 
 hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
                            uint8_t *codes, hipStream_t s) {
@@ -365,8 +416,8 @@ hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64
     const size_t esz = dtype == BIFEAT_F32 ? 4 : 2;
     const bool vec = (D % 4 == 0) && ((uintptr_t)chunk % (4 * esz) == 0);
     if (p->scheme.kind == BIFEAT_VQ) {
-        if (dtype == BIFEAT_F32) launch_vq((const float *)chunk, rows, p, codes, s);
-        else launch_vq((const __half *)chunk, rows, p, codes, s);
+        if (dtype == BIFEAT_F32) launch_vq_assign(p, (const float *)chunk, rows, codes, p->rb, s);
+        else launch_vq_assign(p, (const __half *)chunk, rows, codes, p->rb, s);
     } else if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
         UniformCoder c{p->d_min, p->d_inv, (float)((1u << p->scheme.bits) - 1u)};
         if (dtype == BIFEAT_F32) launch_sq((const float *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);

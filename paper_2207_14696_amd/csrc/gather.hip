@@ -176,8 +176,15 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_tile_kernel(
     }
 }
 
-// vector codes: columns 4g..4g+3 of part p = col / w come from entry q = row[p]
-template <bool W4>
+// vector codes: columns 4g..4g+3 of part p = col / w come from entry q = index p of
+// the row (CB bytes per index)
+template <int CB>
+__device__ inline int vq_index(const uint8_t *row, int part) {
+    if constexpr (CB == 1) return row[part];
+    else return reinterpret_cast<const uint16_t *>(row)[part];
+}
+
+template <bool W4, int CB>
 __global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ idx, int64_t M,
     int D, int w, int len, const float *__restrict__ cb, float *__restrict__ out) {
@@ -199,14 +206,14 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
         const uint8_t *row = codes + idx[i] * rb;
         float v[4];
         if constexpr (W4) {  // w % 4 == 0: the four columns share a part, entry rows 16B aligned
-            const int q = row[part[0]];
+            const int q = vq_index<CB>(row, part[0]);
             float4 c = *reinterpret_cast<const float4 *>(cb + ((int64_t)part[0] * len + q) * w + dim[0]);
             v[0] = c.x; v[1] = c.y; v[2] = c.z; v[3] = c.w;
         } else {
 #pragma unroll
             for (int k = 0; k < 4; k++) {
                 v[k] = 0.f;
-                if (col0 + k < D) v[k] = cb[((int64_t)part[k] * len + row[part[k]]) * w + dim[k]];
+                if (col0 + k < D) v[k] = cb[((int64_t)part[k] * len + vq_index<CB>(row, part[k])) * w + dim[k]];
             }
         }
         store4<W4>(out, i, D, col0, v);
@@ -225,10 +232,16 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
         if (p->opt_vq_sliced && launch_gather_dequant_vq_sliced(p, codes, idx, M, out, s))
             return hipGetLastError();
         const int w = p->scheme.vq_width;
-        if (w % 4 == 0 && vec)
-            gather_dequant_vq_kernel<true><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
-        else
-            gather_dequant_vq_kernel<false><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
+#define BF_GV(W4, CB) \
+    gather_dequant_vq_kernel<W4, CB><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out)
+        if (w % 4 == 0 && vec) {
+            if (p->cbytes == 1) BF_GV(true, 1);
+            else BF_GV(true, 2);
+        } else {
+            if (p->cbytes == 1) BF_GV(false, 1);
+            else BF_GV(false, 2);
+        }
+#undef BF_GV
         return hipGetLastError();
     }
     const int c16 = (int)(p->rb / 16);

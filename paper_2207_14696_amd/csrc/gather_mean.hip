@@ -20,12 +20,19 @@ __device__ inline uint32_t mean_code_bits4(const uint8_t *row, int g) {
     else return (uint32_t)(row[g >> 1] >> (4 * (g & 1))) & 0xFu;
 }
 
+// vector codes: BITS = 8 or 16 is the width of a stored index
+template <int BITS>
+__device__ inline int mean_vq_index(const uint8_t *row, int part) {
+    if constexpr (BITS == 16) return reinterpret_cast<const uint16_t *>(row)[part];
+    else return row[part];
+}
+
 template <int KIND, int BITS, bool VEC>
 __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ pa,
     const float *__restrict__ pb, int w, int len, float *__restrict__ out) {
-    __shared__ float s_lut[KIND == MK_LOG ? (1 << BITS) : 1];
+    __shared__ float s_lut[KIND == MK_LOG ? (1 << (BITS & 15)) : 1];
     if constexpr (KIND == MK_LOG) {
         for (int i = threadIdx.x; i < (1 << BITS); i += kThreads) s_lut[i] = pa[i];
         __syncthreads();
@@ -72,13 +79,13 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
                         else acc[k] += s_lut[q];
                     }
                 } else if constexpr (KIND == MK_VQ4) {
-                    const int q = row[part[0]];
+                    const int q = mean_vq_index<BITS>(row, part[0]);
                     const float4 c = *reinterpret_cast<const float4 *>(pa + ((int64_t)part[0] * len + q) * w + dim[0]);
                     acc[0] += c.x; acc[1] += c.y; acc[2] += c.z; acc[3] += c.w;
                 } else {
 #pragma unroll
                     for (int k = 0; k < 4; k++)
-                        if (col0 + k < D) acc[k] += pa[((int64_t)part[k] * len + row[part[k]]) * w + dim[k]];
+                        if (col0 + k < D) acc[k] += pa[((int64_t)part[k] * len + mean_vq_index<BITS>(row, part[k])) * w + dim[k]];
                 }
             }
 #pragma unroll
@@ -113,11 +120,16 @@ static void launch_float(bifeat_params *p, const uint8_t *codes, const int64_t *
         if (vec) gather_mean_float_kernel<KIND, B, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, out); \
         else gather_mean_float_kernel<KIND, B, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, out);    \
     } while (0)
-    switch (p->scheme.bits) {
-        case 1: BF_FL(1); break;
-        case 2: BF_FL(2); break;
-        case 4: BF_FL(4); break;
-        default: BF_FL(8); break;
+    if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
+        if (p->cbytes == 2) BF_FL(16);
+        else BF_FL(8);
+    } else {
+        switch (p->scheme.bits) {
+            case 1: BF_FL(1); break;
+            case 2: BF_FL(2); break;
+            case 4: BF_FL(4); break;
+            default: BF_FL(8); break;
+        }
     }
 #undef BF_FL
 }

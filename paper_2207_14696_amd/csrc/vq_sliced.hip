@@ -43,7 +43,7 @@ struct VqGeom {
 VqGeom vq_geometry(const bifeat_params *p) {
     VqGeom g{0, 0, 0, 0, false};
     const int w = p->scheme.vq_width, len = p->scheme.vq_length, P = p->P;
-    if (w % 4 || (w & (w - 1)) || p->D % w) return g;  // 16-byte granules, whole parts
+    if (w % 4 || (w & (w - 1)) || p->D % w || p->cbytes != 1) return g;  // 16-byte granules, whole parts, one-byte codes
     int sp = 1;
     while (sp * 2 * len * w * 4 <= 65536 && sp * 2 * w / 4 <= 64 && sp * 2 <= 64) sp *= 2;
     while (sp > P) sp >>= 1;
@@ -111,21 +111,6 @@ __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
         }
         wave_sync();
     }
-}
-
-bool ensure_scratch(bifeat_params *p, size_t bytes) {
-    if (p->scratch_bytes >= bytes) return true;
-    if (p->d_scratch) (void)hipFree(p->d_scratch);  // waits for work that may still use it
-    p->d_scratch = nullptr;
-    p->scratch_bytes = 0;
-    void *q = nullptr;
-    if (hipMalloc(&q, bytes + bytes / 4) != hipSuccess) {
-        (void)hipGetLastError();
-        return false;
-    }
-    p->d_scratch = (uint8_t *)q;
-    p->scratch_bytes = bytes + bytes / 4;
-    return true;
 }
 
 void launch_planes(bifeat_params *p, const uint8_t *codes, const int64_t *idx, int64_t M,

@@ -3,13 +3,17 @@
 //
 // Lloyd rounds on a sample chunk resident in GPU memory: initial entries = the
 // sample's first `length` rows (per part); each round assigns every sample
-// sub-vector to its nearest entry (the same fp32 distance rule as the encoder,
-// so a trained codebook encodes exactly as it was fitted), accumulates per-entry
-// sums and counts - first in LDS per workgroup, then with global atomics - and
-// replaces each non-empty entry by the mean of its members (an entry without
-// members keeps its value).  fp32 atomic accumulation makes the result depend
-// on the order of additions in the last bits; it is judged on distortion, not
-// bit for bit.
+// sub-vector to its nearest entry (the same fp32 rule as the encoder, so a
+// trained codebook encodes exactly as it was fitted), accumulates per-entry
+// sums and counts and replaces each non-empty entry by the mean of its members
+// (an entry without members keeps its value).  fp32 atomic accumulation makes
+// the result depend on the order of additions in the last bits; it is judged on
+// distortion, not bit for bit.
+// Two forms: Euclidean one-byte codebooks small enough for LDS fuse the search
+// with the accumulation (sums first in LDS per workgroup, then global atomics);
+// everything else (cosine metric, up to 16384 entries, wide parts) runs the
+// encoder's own kernel into a scratch code array and accumulates from that with
+// global atomics.
 #include "common.hpp"
 
 namespace bf {
@@ -130,7 +134,83 @@ void lloyd_round(bifeat_params *p, const T *x, int64_t rows, float *dist_slot, h
     vq_lloyd_update_kernel<<<256, 256, 0, s>>>(p->d_cb, sums, counts, w, n);
 }
 
+// rnorm[i] = fp32(1 / sqrt(sum_d C_id^2)), 0 for an all-zero entry; sum and root in fp64
+__global__ void vq_rnorm_kernel(const float *__restrict__ cb, int64_t entries, int w,
+                                float *__restrict__ rnorm) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < entries;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        double ss = 0.0;
+        for (int d = 0; d < w; d++) ss += (double)cb[i * w + d] * (double)cb[i * w + d];
+        rnorm[i] = ss > 0.0 ? (float)(1.0 / sqrt(ss)) : 0.0f;
+    }
+}
+
+// sums / counts / squared distance from a dense code array codes[r][p]
+template <typename T, typename CODE>
+__global__ __launch_bounds__(kThreads) void vq_accumulate_codes_kernel(
+    const T *__restrict__ x, int64_t rows, int D, int w, int len, int P,
+    const CODE *__restrict__ codes, const float *__restrict__ cb, float *__restrict__ sums,
+    float *__restrict__ counts, float *__restrict__ distortion) {
+    const int64_t items = rows * P;
+    float dsum = 0.0f;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < items;
+         i += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = i / P;
+        const int p = (int)(i - r * P);
+        const int64_t e = (int64_t)p * len + codes[i], ent = e * w;
+        for (int d = 0; d < w; d++) {
+            const int col = p * w + d;
+            const float xv = col < D ? load1(x + r * D + col) : 0.0f;
+            atomicAdd(&sums[ent + d], xv);
+            const float diff = xv - cb[ent + d];
+            dsum += diff * diff;
+        }
+        atomicAdd(&counts[e], 1.0f);
+    }
+    for (int o = 32; o > 0; o >>= 1) dsum += __shfl_xor(dsum, o);
+    if ((threadIdx.x & 63) == 0) atomicAdd(distortion, dsum);
+}
+
+template <typename T>
+void lloyd_round_generic(bifeat_params *p, const T *x, int64_t rows, float *dist_slot, hipStream_t s) {
+    const int w = p->scheme.vq_width, len = p->scheme.vq_length, P = p->P;
+    const int64_t n = (int64_t)P * len * w;
+    float *sums = p->d_train, *counts = p->d_train + n;
+    vq_zero_kernel<<<1024, 256, 0, s>>>(p->d_train, n + (int64_t)P * len);
+    if (p->scheme.vq_metric == BIFEAT_VQ_COSINE) launch_vq_rnorm(p, s);
+    launch_vq_assign(p, x, rows, p->d_scratch, (int64_t)P * p->cbytes, s);
+    const int blocks = blocks_for(rows * P, 8192);
+    if (p->cbytes == 1)
+        vq_accumulate_codes_kernel<T, uint8_t><<<blocks, kThreads, 0, s>>>(
+            x, rows, (int)p->D, w, len, P, (const uint8_t *)p->d_scratch, p->d_cb, sums, counts, dist_slot);
+    else
+        vq_accumulate_codes_kernel<T, uint16_t><<<blocks, kThreads, 0, s>>>(
+            x, rows, (int)p->D, w, len, P, (const uint16_t *)p->d_scratch, p->d_cb, sums, counts, dist_slot);
+    vq_lloyd_update_kernel<<<1024, 256, 0, s>>>(p->d_cb, sums, counts, w, n);
+}
+
 }  // namespace
+
+bool ensure_scratch(bifeat_params *p, size_t bytes) {
+    if (p->scratch_bytes >= bytes) return true;
+    if (p->d_scratch) (void)hipFree(p->d_scratch);  // waits for work that may still use it
+    p->d_scratch = nullptr;
+    p->scratch_bytes = 0;
+    void *q = nullptr;
+    if (hipMalloc(&q, bytes + bytes / 4) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    p->d_scratch = (uint8_t *)q;
+    p->scratch_bytes = bytes + bytes / 4;
+    return true;
+}
+
+void launch_vq_rnorm(bifeat_params *p, hipStream_t s) {
+    const int64_t entries = (int64_t)p->P * p->scheme.vq_length;
+    vq_rnorm_kernel<<<blocks_for(entries), kThreads, 0, s>>>(p->d_cb, entries, p->scheme.vq_width,
+                                                            p->d_rnorm);
+}
 
 // rounds Lloyd iterations over the sample chunk; init = true first seeds the
 // codebooks from the chunk's first `length` rows.  d_dist[k] receives the summed
@@ -138,6 +218,9 @@ void lloyd_round(bifeat_params *p, const T *x, int64_t rows, float *dist_slot, h
 hipError_t launch_vq_train(bifeat_params *p, const void *chunk, int dtype, int64_t rows, bool init,
                            int rounds, hipStream_t s) {
     const int w = p->scheme.vq_width, len = p->scheme.vq_length, P = p->P;
+    const bool fused = p->scheme.vq_metric == BIFEAT_VQ_L2 && p->cbytes == 1 &&
+                       sizeof(float) * ((size_t)2 * len * w + len) <= 65536;
+    if (!fused && !ensure_scratch(p, (size_t)rows * P * p->cbytes)) return hipErrorOutOfMemory;
     if (init) {
         if (dtype == BIFEAT_F32)
             vq_init_kernel<float><<<256, 256, 0, s>>>((const float *)chunk, (int)p->D, w, len, P, p->d_cb);
@@ -146,8 +229,13 @@ hipError_t launch_vq_train(bifeat_params *p, const void *chunk, int dtype, int64
     }
     vq_zero_kernel<<<1, 64, 0, s>>>(p->d_dist, rounds);
     for (int k = 0; k < rounds; k++) {
-        if (dtype == BIFEAT_F32) lloyd_round(p, (const float *)chunk, rows, p->d_dist + k, s);
-        else lloyd_round(p, (const __half *)chunk, rows, p->d_dist + k, s);
+        if (fused) {
+            if (dtype == BIFEAT_F32) lloyd_round(p, (const float *)chunk, rows, p->d_dist + k, s);
+            else lloyd_round(p, (const __half *)chunk, rows, p->d_dist + k, s);
+        } else {
+            if (dtype == BIFEAT_F32) lloyd_round_generic(p, (const float *)chunk, rows, p->d_dist + k, s);
+            else lloyd_round_generic(p, (const __half *)chunk, rows, p->d_dist + k, s);
+        }
     }
     return hipGetLastError();
 }

@@ -37,8 +37,13 @@ def test_sizes_and_scheme_validation(bf):
     assert bf.Quantizer(bf.Scheme(bf.LOG, 1), 768).row_bytes == 96
     v = bf.Quantizer(bf.Scheme(bf.VQ, 8, 8, 256), 768)
     assert (v.row_bytes, v.codes_per_row) == (96, 96)
+    # more than 256 entries: two bytes per part (Appendix D)
+    v2 = bf.Quantizer(bf.Scheme(bf.VQ, 8, 16, 2048, bf.VQ_COSINE), 128)
+    assert (v2.row_bytes, v2.codes_per_row) == (16, 8)
+    assert bf.Quantizer(bf.Scheme(bf.VQ, 8, 100, 16384), 602).row_bytes == 16
     for bad in [bf.Scheme(bf.UNIFORM, 3), bf.Scheme(bf.LOG, 16), bf.Scheme(bf.VQ, 8, 0, 256),
-                bf.Scheme(bf.VQ, 8, 8, 1000), bf.Scheme(7, 4)]:
+                bf.Scheme(bf.VQ, 8, 8, 16385), bf.Scheme(bf.VQ, 8, 129, 16),
+                bf.Scheme(bf.VQ, 8, 8, 16, 2), bf.Scheme(7, 4)]:
         with pytest.raises(bf.BifeatError) as e:
             bf.Quantizer(bad, 100)
         assert e.value.status == -1

@@ -311,3 +311,73 @@ def test_vq_codebook_training_matches_oracle_distortion(bf, torch, D, w, length,
     # a table encoded with the trained codebooks: codes equal the oracle's for those codebooks
     codes = gpu_build_table(q, _dev_table(spec), spec.N, 2500, fit=False)
     assert np.array_equal(codes.cpu().numpy(), orc.pack(orc.vq_assign(x, w, gcb), 8))
+
+
+# ------------------------------------- vector-code variants: cosine metric, two-byte indices
+VQ_VARIANTS = [(64, 16, 2048, "l2", "f32"), (48, 16, 600, "cosine", "f32"),
+               (207, 100, 300, "l2", "f32"), (64, 8, 64, "cosine", "f16"),
+               (40, 5, 7, "cosine", "f32"), (70, 40, 20, "cosine", "f32")]
+
+
+@pytest.mark.parametrize("D,w,length,metric,dtype", VQ_VARIANTS)
+def test_vq_variant_codes_bit_exact(bf, torch, D, w, length, metric, dtype):
+    spec = FeatureSpec(3001, D, 15, dtype)
+    x = feature_chunk(spec, 0, spec.N).astype(np.float32)
+    cb, _ = orc.vq_train(x[:max(length, 800)], w, length, iters=2, metric=metric)
+    bits = orc.vq_code_bits(length)
+    want = orc.pack(orc.vq_assign(x, w, cb, metric=metric), bits)
+    q = bf.Quantizer(scheme_of("vq", 8, w, length, metric), D)
+    assert q.row_bytes == want.shape[1]
+    q.params_set_codebooks(cb)
+    got = gpu_build_table(q, _dev_table(spec), spec.N, 1300, fit=False)
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("D,w,length", [(64, 8, 700), (100, 4, 1000), (46, 23, 300)])
+def test_two_byte_codes_gather(bf, torch, D, w, length):
+    spec = FeatureSpec(5003, D, 16)
+    x = feature_chunk(spec, 0, spec.N)
+    cb, _ = orc.vq_train(x[:1200], w, length, iters=2)
+    s = orc.Scheme.vq(D, cb)
+    codes = orc.pack(orc.vq_assign(x, w, cb), 16)
+    q = bf.Quantizer(scheme_of("vq", 8, w, length), D)
+    q.params_set_codebooks(cb)
+    dcodes = torch.from_numpy(codes).cuda()
+    rng = np.random.default_rng(3)
+    idx = rng.integers(0, spec.N, 2001).astype(np.int64)
+    didx = torch.from_numpy(idx).cuda()
+    assert np.array_equal(q.gather_codes(dcodes, didx).cpu().numpy(), orc.gather_codes(codes, idx))
+    assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), orc.gather_dequant(s, codes, idx), s)
+    indptr, indices = random_csr(901, spec.N, 20, rng, hubs=(200,))
+    got = q.gather_mean(dcodes, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda())
+    assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, indptr, indices), s, "gather_mean")
+
+
+@pytest.mark.parametrize("D,w,length,metric", [(64, 8, 32, "cosine"), (32, 4, 512, "l2"),
+                                               (60, 20, 300, "cosine")])
+def test_vq_variant_training_matches_oracle_distortion(bf, torch, D, w, length, metric):
+    spec = FeatureSpec(6000, D, 17)
+    x = feature_chunk(spec, 0, spec.N).astype(np.float32)
+    sample, held = x[:4000], x[4000:]
+    ocb, odist = orc.vq_train(sample, w, length, iters=6, metric=metric)
+    if metric == "l2":      # the metric entry reports distortion the same way for both metrics
+        odist = orc.vq_train(sample, w, length, iters=6)[1]
+    q = bf.Quantizer(scheme_of("vq", 8, w, length, metric), D)
+    q.set_option("vq_iters", 6)
+    q.fit_update(_dev_table(spec).chunk(0, 4000))
+    q.fit_finalize()
+    gcb = q.params_get_codebooks()
+    gdist = q.vq_distortion(6)
+    assert np.isfinite(gcb).all()
+    assert np.allclose(gdist, odist, rtol=5e-3)        # same trajectory as the oracle
+    bits = orc.vq_code_bits(length)
+
+    def distortion(cb):
+        s = orc.Scheme.vq(D, cb)
+        dec = orc.gather_dequant(s, orc.pack(orc.vq_assign(held, w, cb, metric=metric), bits),
+                                 np.arange(len(held)))
+        return ((dec.astype(np.float64) - held) ** 2).sum(1).mean()
+    assert distortion(gcb) <= 1.02 * distortion(ocb)
+    codes = gpu_build_table(q, _dev_table(spec), spec.N, 2500, fit=False)
+    assert np.array_equal(codes.cpu().numpy(),
+                          orc.pack(orc.vq_assign(x, w, gcb, metric=metric), bits))
