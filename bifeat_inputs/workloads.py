@@ -31,6 +31,7 @@ class Workload:
     cap: int = 10_000
     vq_width: int = 8
     vq_length: int = 256
+    vq_metric: str = "l2"       # "l2" | "cosine"
     seed: int = 0
 
     @property
@@ -52,6 +53,10 @@ WORKLOADS = {
     "largest4": Workload("largest4", 244_000_000, 768, "f16", "uniform", 4, "powerlaw", 12,
                          (25, 15), 1024),
     "vq": Workload("vq", 100_000_000, 768, "f32", "vq", 8, "powerlaw", 15, (25, 10), 4096),
+    # the paper's large-graph vector setting (Appendix B: width 16, length 2048, i.e.
+    # two-byte indices, cosine search) on the "large" table and sampling
+    "vq2k": Workload("vq2k", 111_000_000, 128, "f32", "vq", 8, "powerlaw", 15, (15, 10, 5), 1024,
+                     seed_mode="degree", vq_width=16, vq_length=2048, vq_metric="cosine"),
 }
 
 
@@ -63,7 +68,8 @@ def make_graph(w: Workload):
 
 # minibatches concatenated into one launch by default (what a prefetching
 # loader hands over); 1 = a single minibatch per launch
-BATCHES_PER_STEP = {"tiny": 64, "mid": 64, "large": 8, "largest1": 32, "largest4": 32, "vq": 8}
+BATCHES_PER_STEP = {"tiny": 64, "mid": 64, "large": 8, "largest1": 32, "largest4": 32, "vq": 8,
+                    "vq2k": 8}
 
 
 def launch_set(w: Workload, graph, set_index: int, L: int):

@@ -4,7 +4,7 @@
  *
  * The library keeps a node-feature table in compressed form in GPU memory and
  * serves minibatch iterations from it:
- *   - one-time preprocessing (paper Sec. 3.3 "before training"): fit the
+ *   - one-time preprocessing (paper Sec. 3.3: done once, ahead of training): fit the
  *     quantizer to the table, chunk by chunk, then encode + pack each chunk;
  *   - per iteration (Sec. 3.3): gather the compressed rows of the sampled
  *     nodes and decode them to fp32, optionally fused with the first layer's
@@ -23,12 +23,12 @@
  *     failure on the calling thread).
  *   - Row indices must satisfy 0 <= idx < N and indptr must be non-decreasing;
  *     this is the caller's contract and is not checked on the GPU.
- *   - Packed layout (the paper fixes none; Appendix D only advises against
+ *   - Packed layout (the paper fixes none; Appendix C only advises against
  *     elaborate bit packing): row-major; scalar codes: column j's `bits`-bit
  *     code at bit (j*bits) mod 8 of byte floor(j*bits/8), column 0 in the
  *     least significant bits; vector codes: byte p = codebook index of part p
  *     (codebooks of more than 256 entries: bytes 2p, 2p+1 = the index, low
- *     byte first - the whole-byte alignment of Appendix D);
+ *     byte first - the whole-byte alignment of Appendix C);
  *     row stride bifeat_row_bytes() = payload rounded up to 16 bytes, pad = 0.
  */
 #ifndef BIFEAT_H
@@ -49,8 +49,8 @@ typedef enum {
 } bifeat_status;
 
 typedef enum {
-    /* evenly spaced levels between per-column min and max - the "commonly
-     * used uniform quantization" of Sec. 3.1 */
+    /* evenly spaced levels between per-column min and max - the ordinary
+     * uniform quantization that Sec. 3.1 starts from */
     BIFEAT_SQ_UNIFORM = 0,
     /* BiFeat-SQ: sign-split uniform quantization of clipped log2|x|,
      * Sec. 3.1 Eq. (1), decoded by Eq. (2) */
@@ -61,8 +61,8 @@ typedef enum {
 
 typedef enum { BIFEAT_F32 = 0, BIFEAT_F16 = 1 } bifeat_dtype;
 
-/* Sec. 3.2: the nearest codebook entry is found "by Euclidean distance or
- * cosine similarity".  Cosine: the entry with the largest (x . C_c)/|C_c| (the
+/* Sec. 3.2 allows two rules for the nearest codebook entry: Euclidean distance
+ * or cosine similarity.  Cosine: the entry with the largest (x . C_c)/|C_c| (the
  * part's own norm is a common positive factor and is left out; an all-zero part
  * or entry scores 0); entries stay arithmetic means of their members and decode
  * returns the entry unchanged. */
@@ -74,7 +74,7 @@ typedef struct {
     int32_t vq_width;  /* BIFEAT_VQ: dims per part (1..128); P = ceil(D/width) parts, a short
                           last part is zero-padded */
     int32_t vq_length; /* BIFEAT_VQ: entries per codebook: 2..256 stored as one byte per
-                          part, 257..16384 as two (Appendix D) */
+                          part, 257..16384 as two (Appendix C) */
     int32_t vq_metric; /* BIFEAT_VQ: bifeat_vq_metric */
 } bifeat_scheme;
 
@@ -91,7 +91,7 @@ int64_t bifeat_row_bytes(const bifeat_params *p);
 /* Codes per row: D (scalar kinds) or the number of parts (BIFEAT_VQ). */
 int64_t bifeat_codes_per_row(const bifeat_params *p);
 
-/* ---- fitting (Sec. 3.1: e_min/e_max "of binary logarithm ... after clipping";
+/* ---- fitting (Sec. 3.1: e_min/e_max bound log2|x| once outliers are clipped;
  *      uniform: per-column range).  Streaming: reset, update per chunk, finalize.
  * chunk: DEVICE, [rows x D] row-major, `dtype` elements.
  * SQ_UNIFORM: per-column min and max over all chunks (NaNs skipped, a zero
@@ -104,7 +104,7 @@ int64_t bifeat_codes_per_row(const bifeat_params *p);
  *   magnitudes come back to the host, where log2/exp2 are evaluated in fp64).
  *   Tail clipping is not fitted here: pass a clipped pair to
  *   bifeat_params_set_log instead.
- * BIFEAT_VQ (Sec. 3.2 k-means per part; Appendix E: on a uniform row sample,
+ * BIFEAT_VQ (Sec. 3.2 k-means per part; Appendix D: on a uniform row sample,
  *   which is what the caller passes as the chunk): the first chunk after a
  *   reset seeds every part's codebook with the sub-vectors of its first
  *   `vq_length` rows (it must have at least that many); every update then runs

@@ -161,7 +161,7 @@ def log_range(state) -> tuple[float, float]:
 
 def log_range_clipped(x, p: float) -> tuple[float, float]:
     """(e_min, e_max) with a fraction p of the nonzero magnitudes clipped at
-    each tail (Sec. 3.1 "after clipping outlier values"; Appendix D calls the
+    each tail (Sec. 3.1 takes the range after outliers are clipped; Appendix C calls the
     fraction a minor setting): the order statistics of |x| at ranks
     floor(p*(n-1)) and ceil((1-p)*(n-1)), by a full sort."""
     m = np.abs(_f32(x).reshape(-1))
@@ -206,7 +206,7 @@ METRICS = {"l2": 0, "cosine": 1}
 
 
 def vq_code_bits(length: int) -> int:
-    """Bits per stored index: one byte up to 256 entries, two beyond (Appendix D)."""
+    """Bits per stored index: one byte up to 256 entries, two beyond (Appendix C)."""
     return 8 if length <= 256 else 16
 
 

@@ -8,10 +8,10 @@
  *
  * What is defined by the paper, and where:
  *   - logarithmic scalar codes and their decoding     Sec. 3.1, Eq. (1), Eq. (2)
- *   - 1-bit codes ("positive or not", zero with the negatives)    Sec. 3.1
+ *   - 1-bit codes (sign only, zero on the negative side)          Sec. 3.1
  *   - uniform scalar codes (evenly spaced levels), named in        Sec. 3.1
  *   - vector codes: split into parts of `width` dims, one k-means codebook of
- *     `length` entries per part, store the index      Sec. 3.2, Appendix D
+ *     `length` entries per part, store the index      Sec. 3.2, Appendix C
  *   - per-iteration load = rows of the sampled nodes, decoded      Sec. 3.3
  *   - neighbourhood mean  g_i = (1/|N(i)|) sum_{j in N(i)} g_j     Appendix A.1
  * Where the paper is silent (bit packing, the uniform scheme's exact rounding,
@@ -68,7 +68,7 @@ int orc_max_threads(void) {
 }
 
 /* ------------------------------------------------------------------ packing
- * The paper does not fix a bit layout (Appendix D only advises against
+ * The paper does not fix a bit layout (Appendix C only advises against
  * elaborate packing).  Layout used: row-major; column j's `bits`-bit code sits
  * at bit offset (j*bits) mod 8 of byte floor(j*bits/8) (column 0 in the least
  * significant bits); a row occupies ceil(D*bits/8) bytes rounded up to a
@@ -99,7 +99,7 @@ void orc_unpack(const uint8_t *packed, int64_t rows, int64_t ncodes, int bits, u
 }
 
 /* Two-byte codes (vector codes with more than 256 entries per codebook;
- * Appendix D: align to whole bytes, two bytes up to 16384 entries): code j of a
+ * Appendix C: align to whole bytes, two bytes up to 16384 entries): code j of a
  * row sits in bytes 2j (low) and 2j+1 (high); rows padded to 16 bytes as above. */
 void orc_pack16(const uint16_t *q, int64_t rows, int64_t ncodes, uint8_t *packed) {
     int64_t rb = orc_row_bytes(ncodes, 16);
@@ -267,7 +267,7 @@ void orc_log_encode_direct(const float *x, int64_t n, int k, double e_min, doubl
 }
 
 /* ------------------------------------------------------------- vector codes
- * Sec. 3.2 / Appendix D: D dims are split into P = ceil(D/w) parts of w dims
+ * Sec. 3.2 / Appendix C: D dims are split into P = ceil(D/w) parts of w dims
  * (a short last part is zero-padded); part p of a row is replaced by the index
  * of its nearest entry in that part's codebook of `len` entries (Euclidean
  * distance; len <= 256, one byte per part as the paper advises; larger
@@ -314,7 +314,7 @@ void orc_vq_assign(const float *x, int64_t rows, int64_t D, int w, int len, cons
 }
 
 /* Codebook training.  The paper says k-means on a uniform row sample
- * (Sec. 3.2, Appendix E) and nothing more.  Reading: per part, initial
+ * (Sec. 3.2, Appendix D) and nothing more.  Reading: per part, initial
  * entries = the first `len` pairwise distinct sub-vectors of the sample in
  * sample order (if fewer exist the rest repeat the last one and stay unused);
  * then `iters` Lloyd rounds {assign as above; entry = fp64 mean of its members
@@ -370,7 +370,7 @@ void orc_vq_train(const float *sample, int64_t ns, int64_t D, int w, int len, in
     free(dpart);
 }
 
-/* ---- the variants of Sec. 3.2 / Appendix D beyond one-byte Euclidean codes
+/* ---- the variants of Sec. 3.2 / Appendix C beyond one-byte Euclidean codes
  * Metric.  Sec. 3.2 allows Euclidean distance or cosine similarity for the
  * nearest-entry search and says no more.  Reading for cosine: the part takes
  * the entry with the largest (x . C_c) / |C_c|; the row's own norm is a common

@@ -1,5 +1,5 @@
 // Codebook training for the vector codes (paper Sec. 3.2: k-means per part;
-// Appendix E: on a uniform row sample, "more efficient to use the GPU").
+// Appendix D: on a uniform row sample, and names the GPU as the place to run it).
 //
 // Lloyd rounds on a sample chunk resident in GPU memory: initial entries = the
 // sample's first `length` rows (per part); each round assigns every sample

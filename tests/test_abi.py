@@ -37,7 +37,7 @@ def test_sizes_and_scheme_validation(bf):
     assert bf.Quantizer(bf.Scheme(bf.LOG, 1), 768).row_bytes == 96
     v = bf.Quantizer(bf.Scheme(bf.VQ, 8, 8, 256), 768)
     assert (v.row_bytes, v.codes_per_row) == (96, 96)
-    # more than 256 entries: two bytes per part (Appendix D)
+    # more than 256 entries: two bytes per part (Appendix C)
     v2 = bf.Quantizer(bf.Scheme(bf.VQ, 8, 16, 2048, bf.VQ_COSINE), 128)
     assert (v2.row_bytes, v2.codes_per_row) == (16, 8)
     assert bf.Quantizer(bf.Scheme(bf.VQ, 8, 100, 16384), 602).row_bytes == 16

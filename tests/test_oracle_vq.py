@@ -1,4 +1,4 @@
-"""Pins for the oracle's vector codes (Sec. 3.2, Appendix D)."""
+"""Pins for the oracle's vector codes (Sec. 3.2, Appendix C)."""
 import numpy as np
 import pytest
 
@@ -93,7 +93,7 @@ def test_against_library_kmeans_from_same_start():
     assert abs(inertia(cb[0]) - inertia(km.cluster_centers_)) <= 0.02 * inertia(km.cluster_centers_)
 
 
-# ------------------------------------------------- the variants of Sec. 3.2 / Appendix D
+# ------------------------------------------------- the variants of Sec. 3.2 / Appendix C
 def _margin_filter(score, q, rtol):
     """Rows whose best and second-best scores are clearly apart."""
     part = np.partition(score, -2, axis=1)
