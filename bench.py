@@ -35,7 +35,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="mid",
-                    choices=["tiny", "mid", "large", "largest1", "largest4", "vq"])
+                    choices=["tiny", "mid", "large", "largest1", "largest4", "vq", "vq2k"])
     ap.add_argument("--rows", type=int, default=0, help="override N (debugging)")
     ap.add_argument("--batches", type=int, default=0, help="distinct pre-sampled launch-sets")
     ap.add_argument("--batches-per-step", type=int, default=0)
@@ -88,7 +88,8 @@ def main():
     # ------------------------------------------------------------ the table
     kind = {"uniform": bf.UNIFORM, "log": bf.LOG, "vq": bf.VQ}[w.kind]
     q = bf.Quantizer(bf.Scheme(kind, w.bits, w.vq_width if w.kind == "vq" else 0,
-                               w.vq_length if w.kind == "vq" else 0), w.D)
+                               w.vq_length if w.kind == "vq" else 0,
+                               bf.VQ_COSINE if w.vq_metric == "cosine" else bf.VQ_L2), w.D)
     for opt in ("mean_slots", "mean_blocks", "max_blocks"):
         if getattr(args, opt):
             q.set_option(opt, getattr(args, opt))
@@ -262,7 +263,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "D": w.D, "scheme": w.kind,
                    "bits": w.bits if w.kind != "vq" else None,
-                   "vq": [w.vq_width, w.vq_length] if w.kind == "vq" else None,
+                   "vq": [w.vq_width, w.vq_length, w.vq_metric] if w.kind == "vq" else None,
                    "row_bytes": rb, "graph": w.graph, "avg_degree": w.avg_degree,
                    "fanouts": list(w.fanouts), "batch": w.batch, "batches_per_step": L,
                    "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B},
@@ -309,9 +310,10 @@ def cpu_baseline(w, g, seconds: float):
             s = orc.Scheme.vq(w.D, cb)
             # nearest-entry search of every touched row would take minutes per minibatch on
             # the host; the timed gathers do not depend on the code values
-            head = orc.vq_assign(x[:4096], w.vq_width, cb)
+            head = orc.vq_assign(x[:4096], w.vq_width, cb, metric=w.vq_metric)
             rest = np.random.default_rng(bi).integers(0, w.vq_length, (x.shape[0] - head.shape[0], P))
-            codes = orc.pack(np.concatenate([head, rest.astype(head.dtype)]), 8)
+            codes = orc.pack(np.concatenate([head, rest.astype(head.dtype)]),
+                             orc.vq_code_bits(w.vq_length))
             note = "; vector codes beyond each sub-table's first 4096 rows drawn at random"
         idx = np.arange(inputs.shape[0], dtype=np.int64)
         csr = [(b.indptr, remap(b.indices)) for b in blocks]

@@ -6,8 +6,9 @@
 // request per 32..64 bytes, as many requests as the fp32 output itself.  The
 // codebooks of all parts do not fit one CU's LDS (786 KB at 96 x 256 x 8), so
 // the table's columns are sliced: a workgroup keeps the codebooks of SP
-// consecutive parts (<= 64 KB) in LDS and produces only those SP*width output
-// columns, for every requested row.  So that a slice does not have to pull a
+// consecutive parts in LDS (as many as 64 KB hold, so that two workgroups share
+// a CU; a single part of up to ~150 KB when one part alone is larger) and
+// produces only those SP*width output columns, for every requested row.  So that a slice does not have to pull a
 // whole cache line out of a random packed row for its SP code bytes, a pre-pass
 // first gathers the requested rows once (whole rows, 16 bytes per lane) and
 // writes them transposed at dword granularity into a scratch buffer,
@@ -43,12 +44,16 @@ struct VqGeom {
 VqGeom vq_geometry(const bifeat_params *p) {
     VqGeom g{0, 0, 0, 0, false};
     const int w = p->scheme.vq_width, len = p->scheme.vq_length, P = p->P;
-    if (w % 4 || (w & (w - 1)) || p->D % w || p->cbytes != 1) return g;  // 16-byte granules, whole parts, one-byte codes
+    if (w % 4 || (w & (w - 1)) || p->D % w) return g;  // 16-byte granules, whole parts
+    const size_t part_bytes = sizeof(float) * (size_t)len * w;
     int sp = 1;
-    while (sp * 2 * len * w * 4 <= 65536 && sp * 2 * w / 4 <= 64 && sp * 2 <= 64) sp *= 2;
-    while (sp > P) sp >>= 1;
-    if (sp * len * w * 4 > 65536 || sp % 4) return g;  // slice's code bytes are whole dwords
-    if ((int64_t)((P + sp - 1) / sp) * sp > p->rb) return g;  // strips copy whole slices of the padded row
+    if (part_bytes <= 65536) {
+        // as many parts as 64 KB hold: two workgroups per CU
+        while ((size_t)sp * 2 * part_bytes <= 65536 && sp * 2 * w / 4 <= 64 && sp * 2 <= 64) sp *= 2;
+        while (sp > P) sp >>= 1;
+    } else if (part_bytes + sizeof(float) * w > 156 * 1024) {
+        return g;  // one part's codebook does not fit a CU's LDS
+    }
     g.SP = sp;
     g.NS = (P + sp - 1) / sp;
     g.LPS = sp * w / 4;
@@ -114,14 +119,14 @@ __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
 }
 
 void launch_planes(bifeat_params *p, const uint8_t *codes, const int64_t *idx, int64_t M,
-                   const VqGeom &g, hipStream_t s) {
+                   hipStream_t s) {
     const int c16 = (int)(p->rb / 16), TR = (64 / c16) * kStripK;
     const int64_t tiles = (M + TR - 1) / TR;
     int64_t blocks = (tiles + 3) / 4;
     if (blocks > (1 << 16)) blocks = 1 << 16;
     if (blocks < 1) blocks = 1;
     vq_planes_kernel<<<(unsigned)blocks, kThreads, 0, s>>>((const uint4 *)codes, c16, idx, M,
-                                                         g.NS * (g.SP >> 2), plane_entries(M),
+                                                         (int)(p->rb / 4), plane_entries(M),
                                                          (uint32_t *)p->d_scratch);
 }
 
@@ -165,7 +170,7 @@ __device__ inline void load_slice(float *s_cb, const float *__restrict__ cb, int
 // out[i, slice columns] = codebook entries selected by the planes of request i
 __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
     const uint32_t *__restrict__ planes, int64_t M, int64_t MS, int D, int P, int w, int len, int SP,
-    int NS, int lps_log2, const float *__restrict__ cb, float *__restrict__ out) {
+    int NS, int lps_log2, int cbytes, const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
     int slice, by, ny;
     slice_and_lane(NS, slice, by, ny);
@@ -176,8 +181,10 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
     const int pl = (4 * g) / w, dim0 = (4 * g) % w;
     const bool active = slice * SP + pl < P;
     const int col = (slice * SP + pl) * w + dim0;
-    const int SPW = SP >> 2, shift = 8 * (pl & 3);
-    const uint32_t *plane = planes + (int64_t)(slice * SPW + (pl >> 2)) * MS;
+    // the part's index: cbytes bytes at byte (part * cbytes) of the packed row
+    const int boff = (slice * SP + pl) * cbytes, shift = 8 * (boff & 3);
+    const uint32_t cmask = cbytes == 1 ? 0xFFu : 0xFFFFu;
+    const uint32_t *plane = planes + (int64_t)(boff >> 2) * MS;
     const float *entry0 = s_cb + 4 * g;
     const int cstride = SP * w;
     const int64_t tiles = (M + (1 << rpw_log2) - 1) >> rpw_log2;
@@ -194,7 +201,7 @@ __global__ __launch_bounds__(kVqThreads) void gather_dequant_vq_sliced_kernel(
 #pragma unroll
         for (int u = 0; u < U; u++) {
             if (active && i[u] < M) {
-                const int c = (word[u] >> shift) & 0xFF;
+                const int c = (int)((word[u] >> shift) & cmask);
                 const float4 v = *reinterpret_cast<const float4 *>(entry0 + c * cstride);
                 store_stream(reinterpret_cast<float4 *>(out + i[u] * D + col), v);
             }
@@ -222,10 +229,10 @@ struct MeanLane {
     int slice, by, ny, lane, wave, nw, rpw_log2, g, r_in, col, cs_log2;
     bool active;
     const uint8_t *base, *lds;
-    uint32_t plane_off, shift, entry0, zero_row;
+    uint32_t plane_off, shift, cmask, entry0, zero_row;
 
     __device__ MeanLane(const uint32_t *planes, int64_t MS, const float *s_cb, int P, int w, int len,
-                        int SP, int NS, int lps_log2) {
+                        int SP, int NS, int lps_log2, int cbytes) {
         slice_and_lane(NS, slice, by, ny);
         lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
         rpw_log2 = 6 - lps_log2;
@@ -235,7 +242,10 @@ struct MeanLane {
         col = (slice * SP + pl) * w + dim0;
         // byte offsets into the planes fit 32 bits (checked by the launcher)
         base = reinterpret_cast<const uint8_t *>(planes);
-        plane_off = (uint32_t)((slice * (SP >> 2) + (pl >> 2)) * MS), shift = 8 * (pl & 3);
+        // the part's index: cbytes bytes at byte (part * cbytes) of the packed row
+        const int boff = (slice * SP + pl) * cbytes;
+        plane_off = (uint32_t)((boff >> 2) * MS), shift = 8 * (boff & 3);
+        cmask = cbytes == 1 ? 0xFFu : 0xFFFFu;
         cs_log2 = __ffs(SP * w * 4) - 1;  // log2 of the bytes between entry rows in LDS
         lds = reinterpret_cast<const uint8_t *>(s_cb);
         entry0 = (uint32_t)(CPL * g * 4);
@@ -256,7 +266,7 @@ struct MeanLane {
             float4 q[BF_VQ_SUB][Q];
 #pragma unroll
             for (int u = 0; u < BF_VQ_SUB; u++) {
-                uint32_t c = (t.w[h + u] >> shift) & 0xFFu;
+                uint32_t c = (t.w[h + u] >> shift) & cmask;
                 if (h + u > 0) c = (uint32_t)(h + u) < rem ? c : zero_row;
                 const uint8_t *ent = lds + ((c << cs_log2) + entry0);
 #pragma unroll
@@ -308,10 +318,10 @@ constexpr int kPre = BF_VQ_PRE;
 template <int CPL>
 __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
     const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
-    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
-    float *__restrict__ out) {
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes,
+    const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
-    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2);
+    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2, cbytes);
     load_slice(s_cb, cb, L.slice, SP, P, len, w);
     const int64_t tiles = (V + (1 << L.rpw_log2) - 1) >> L.rpw_log2;
     const int64_t stride = (int64_t)L.ny * L.nw;
@@ -365,10 +375,10 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
 template <int CPL>
 __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_long_kernel(
     const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
-    int D, int P, int w, int len, int SP, int NS, int lps_log2, const float *__restrict__ cb,
-    float *__restrict__ out) {
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes,
+    const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
-    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2);
+    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2, cbytes);
     load_slice(s_cb, cb, L.slice, SP, P, len, w);
     const int64_t tiles = (V + (1 << L.rpw_log2) - 1) >> L.rpw_log2;
     const int64_t stride = (int64_t)L.ny * L.nw;
@@ -432,17 +442,20 @@ bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, con
                                      int64_t M, float *out, hipStream_t s) {
     const VqGeom g = vq_geometry(p);
     if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
+    // a slice narrower than 256 bytes of output per row makes the stores too fine-grained
+    // (measured: slower than decoding from L2 with whole rows per wave)
+    if (g.LPS < 16) return false;
     if (!allow_lds(gather_dequant_vq_sliced_kernel, g.lds)) return false;
     const int64_t MS = plane_entries(M);
-    if (!ensure_scratch(p, (size_t)g.NS * MS * g.SP)) return false;
-    launch_planes(p, codes, idx, M, g, s);
+    if (!ensure_scratch(p, (size_t)p->rb * MS)) return false;
+    launch_planes(p, codes, idx, M, s);
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int rpw = 64 / g.LPS;
     const int64_t tiles = (M + rpw - 1) / rpw;
     const int grid = sliced_grid(p, (tiles + BF_VQ_U - 1) / BF_VQ_U * g.NS, 2048);
     gather_dequant_vq_sliced_kernel<<<grid, kVqThreads, g.lds, s>>>(
         (const uint32_t *)p->d_scratch, M, MS, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS),
-        p->d_cb, out);
+        p->cbytes, p->d_cb, out);
     return true;
 }
 
@@ -454,7 +467,7 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const 
     const VqGeom g = vq_geometry(p);
     if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
     const int64_t MS = plane_entries(E);
-    if ((int64_t)g.NS * MS * g.SP >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
+    if (p->rb * MS >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int cpl = w % 8 == 0 ? 8 : 4;  // columns per lane
     const bool with_long = !(p->opt_mean_max_degree > 0 && p->opt_mean_max_degree <= kRun);
@@ -463,15 +476,15 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const 
                  : !(allow_lds(gather_mean_vq_short_kernel<4>, g.lds) &&
                      allow_lds(gather_mean_vq_long_kernel<4>, g.lds)))
         return false;
-    if (!ensure_scratch(p, (size_t)g.NS * MS * g.SP)) return false;
-    if (E > 0) launch_planes(p, codes, indices, E, g, s);
+    if (!ensure_scratch(p, (size_t)p->rb * MS)) return false;
+    if (E > 0) launch_planes(p, codes, indices, E, s);
     const int lps = g.LPS * 4 / cpl, rpw = 64 / lps;
     const int64_t tiles = (V + rpw - 1) / rpw;
     const int grid = sliced_grid(p, tiles * g.NS, 1024);
 #define BF_VQL(KERNEL)                                                                       \
     KERNEL<<<grid, kVqThreads, g.lds, s>>>((const uint32_t *)p->d_scratch, MS, indptr, V,     \
                                            (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(lps),   \
-                                           p->d_cb, out)
+                                           p->cbytes, p->d_cb, out)
     if (cpl == 8) {
         BF_VQL(gather_mean_vq_short_kernel<8>);
         if (with_long) BF_VQL(gather_mean_vq_long_kernel<8>);

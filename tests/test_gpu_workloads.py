@@ -201,3 +201,25 @@ def test_vq_96x256(torch, bf):
         encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb), 8))
     del codes
     torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(900)
+def test_vq_16x2048_cosine_two_byte(torch, bf):
+    # the vector setting the paper reports for its large graphs (Appendix B): width 16,
+    # 2048 entries (two-byte indices), cosine search
+    w = WORKLOADS["vq2k"]
+    from bifeat_inputs.features import mix64, stream_key, STREAM_MISC
+    ids = (mix64(stream_key(w.seed, STREAM_MISC) + np.arange(8192, dtype=np.uint64))
+           % np.uint64(w.N)).astype(np.int64)
+    cb, _ = orc.vq_train(feature_rows(w.spec, ids).astype(np.float32), w.vq_width, w.vq_length, 4,
+                         metric=w.vq_metric)
+    q = bf.Quantizer(scheme_of("vq", 8, w.vq_width, w.vq_length, w.vq_metric), w.D)
+    assert q.row_bytes == 16
+    q.params_set_codebooks(cb)
+    (codes,), *_ = _stream_table(torch, w, [q], fit=False)
+    _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.vq(w.D, cb),
+        encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb, metric=w.vq_metric), 16))
+    del codes
+    torch.cuda.empty_cache()
