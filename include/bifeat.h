@@ -41,6 +41,9 @@ extern "C" {
 #endif
 
 typedef enum {
+    /* bifeat_fit_finalize only: the fit needs another pass over the same data -
+     * call bifeat_fit_update for every chunk again, then finalize again */
+    BIFEAT_FIT_AGAIN = 1,
     BIFEAT_OK = 0,
     BIFEAT_EINVAL = -1,  /* bad argument (null pointer, unsupported bits, size <= 0, ...) */
     BIFEAT_ENOTFIT = -2, /* quantizer parameters not fitted / set yet */
@@ -102,8 +105,15 @@ int64_t bifeat_codes_per_row(const bifeat_params *p);
  *   sets e_min/e_max to their log2 and builds the tables of
  *   bifeat_params_set_log.  finalize synchronises `stream` (the two
  *   magnitudes come back to the host, where log2/exp2 are evaluated in fp64).
- *   Tail clipping is not fitted here: pass a clipped pair to
- *   bifeat_params_set_log instead.
+ *   With a clip fraction p > 0 (bifeat_fit_set_log_clip) the range ends are
+ *   instead the exact order statistics of the n finite nonzero magnitudes at
+ *   ranks floor(p (n-1)) and ceil((1-p) (n-1)) (Sec. 3.1 clips outliers before
+ *   taking the range; Appendix C leaves the fraction open).  They are found
+ *   by radix selection in three passes: finalize returns BIFEAT_FIT_AGAIN
+ *   after the first and second pass, and the caller streams the same chunks
+ *   through bifeat_fit_update again (a pass over different data ends the fit
+ *   with BIFEAT_EINVAL); the third finalize returns BIFEAT_OK.  Each finalize
+ *   synchronises `stream`.
  * BIFEAT_VQ (Sec. 3.2 k-means per part; Appendix D: on a uniform row sample,
  *   which is what the caller passes as the chunk): the first chunk after a
  *   reset seeds every part's codebook with the sub-vectors of its first
@@ -117,6 +127,9 @@ int64_t bifeat_codes_per_row(const bifeat_params *p);
  *   (the entry norms are evaluated on the host in fp64).
  * finalize without any update returns BIFEAT_ENOTFIT. */
 int bifeat_fit_reset(bifeat_params *p, void *stream);
+/* SQ_LOG: clip fraction for the fits that follow, 0 <= fraction < 0.5 (0 = the
+ * plain fit of the extreme magnitudes).  Not while a fit is open. */
+int bifeat_fit_set_log_clip(bifeat_params *p, double fraction);
 int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
                       void *stream);
 int bifeat_fit_finalize(bifeat_params *p, void *stream);

@@ -16,6 +16,7 @@ UNIFORM, LOG, VQ = 0, 1, 2
 VQ_L2, VQ_COSINE = 0, 1
 F32, F16 = 0, 1
 OK, EINVAL, ENOTFIT, EHIP, ENOTSUP = 0, -1, -2, -3, -4
+FIT_AGAIN = 1
 
 
 class BifeatError(RuntimeError):
@@ -48,6 +49,7 @@ _SIGNATURES = {
     "bifeat_fit_reset": (C.c_int, [C.c_void_p, C.c_void_p]),
     "bifeat_fit_update": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p]),
     "bifeat_fit_finalize": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_fit_set_log_clip": (C.c_int, [C.c_void_p, C.c_double]),
     "bifeat_params_set_uniform": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "bifeat_params_get_uniform": (C.c_int, [C.c_void_p] + [C.c_void_p] * 4),
     "bifeat_params_set_log": (C.c_int, [C.c_void_p, C.c_double, C.c_double]),
@@ -158,8 +160,17 @@ class Quantizer:
         _check(self._lib.bifeat_fit_update(self._h, _dev_ptr(chunk), self._dtype(chunk), rows,
                                            _stream()))
 
-    def fit_finalize(self) -> None:
-        _check(self._lib.bifeat_fit_finalize(self._h, _stream()))
+    def fit_set_log_clip(self, fraction: float) -> None:
+        _check(self._lib.bifeat_fit_set_log_clip(self._h, float(fraction)))
+
+    def fit_finalize(self) -> bool:
+        """True when the fit needs another pass over the same chunks (clipped
+        logarithmic range: three passes), False when the parameters are ready."""
+        status = self._lib.bifeat_fit_finalize(self._h, _stream())
+        if status == FIT_AGAIN:
+            return True
+        _check(status)
+        return False
 
     # ---- parameters (host numpy arrays)
     def params_set_uniform(self, mn, mx) -> None:

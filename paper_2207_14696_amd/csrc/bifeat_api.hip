@@ -44,7 +44,7 @@ int ensure_device(bifeat_params *p) {
     const int64_t D = p->D;
     size_t nfloat = 0, nfit = 0;
     if (p->scheme.kind == BIFEAT_SQ_UNIFORM) { nfloat = 4 * D; nfit = 2 * D; }
-    else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 2; }
+    else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 4 + 2 * 2 * bf::kLogHistBins; }
     else nfloat = (size_t)p->P * p->scheme.vq_length * (2 * p->scheme.vq_width + 2) + 64;
     nfloat = (nfloat + 3) / 4 * 4;
     nfit = (nfit + 3) / 4 * 4;
@@ -70,6 +70,7 @@ int ensure_device(bifeat_params *p) {
         p->d_dist = p->d_train + ncb + nent;
     }
     p->d_fit = reinterpret_cast<int32_t *>(p->d_block + nfloat);
+    if (p->scheme.kind == BIFEAT_SQ_LOG) p->d_hist = reinterpret_cast<unsigned long long *>(p->d_fit + 4);
     p->d_zero = reinterpret_cast<uint8_t *>(p->d_fit + nfit);
     return BIFEAT_OK;
 }
@@ -136,6 +137,79 @@ int sync_codebooks_host(bifeat_params *p) {
     return BIFEAT_OK;
 }
 
+// first bin whose cumulative count exceeds `rank`; `before` = count below that bin
+bool walk_histogram(const unsigned long long *h, int bins, unsigned long long rank, uint32_t *bin,
+                    unsigned long long *before) {
+    unsigned long long cum = 0;
+    for (int b = 0; b < bins; b++) {
+        if (rank < cum + h[b]) {
+            *bin = (uint32_t)b;
+            *before = cum;
+            return true;
+        }
+        cum += h[b];
+    }
+    return false;
+}
+
+int finish_log(bifeat_params *p) {
+    build_log_tables(p);
+    int rc = upload_log(p);
+    if (rc) return rc;
+    p->host_valid = true;
+    p->fit_open = false;
+    p->fitted = true;
+    return BIFEAT_OK;
+}
+
+// one step of the three-pass radix selection (digits of 11, 11 and 9 bits)
+int finalize_log_clipped(bifeat_params *p, hipStream_t s) {
+    std::vector<unsigned long long> h((size_t)2 * bf::kLogHistBins);
+    BF_HIP(hipMemcpyAsync(h.data(), p->d_hist, sizeof(unsigned long long) * h.size(),
+                          hipMemcpyDeviceToHost, s));
+    BF_HIP(hipStreamSynchronize(s));
+    const unsigned long long *h0 = h.data(), *h1 = h.data() + bf::kLogHistBins;
+    unsigned long long before = 0;
+    uint32_t bin = 0;
+    if (p->fit_pass == 0) {
+        unsigned long long n = 0;
+        for (int b = 0; b < bf::kLogHistBins; b++) n += h0[b];
+        if (n == 0) {  // nothing but zeros / non-finite values
+            p->e_min = p->e_max = 0.0;
+            return finish_log(p);
+        }
+        const double f = p->clip_fraction;
+        p->clip_rank[0] = (unsigned long long)floor(f * (double)(n - 1));
+        p->clip_rank[1] = (unsigned long long)ceil((1.0 - f) * (double)(n - 1));
+        for (int t = 0; t < 2; t++) {
+            if (!walk_histogram(h0, bf::kLogHistBins, p->clip_rank[t], &bin, &before)) return BIFEAT_EINVAL;
+            p->clip_prefix[t] = bin;
+            p->clip_rank[t] -= before;
+        }
+    } else {
+        const int bins = p->fit_pass == 1 ? bf::kLogHistBins : 512, shift = p->fit_pass == 1 ? 11 : 9;
+        for (int t = 0; t < 2; t++) {
+            if (!walk_histogram(t ? h1 : h0, bins, p->clip_rank[t], &bin, &before)) {
+                p->fit_open = false;  // the passes did not see the same data
+                return BIFEAT_EINVAL;
+            }
+            p->clip_prefix[t] = (p->clip_prefix[t] << shift) | bin;
+            p->clip_rank[t] -= before;
+        }
+        if (p->fit_pass == 2) {
+            float lo, hi;
+            memcpy(&lo, &p->clip_prefix[0], 4);
+            memcpy(&hi, &p->clip_prefix[1], 4);
+            p->e_min = log2((double)lo);
+            p->e_max = log2((double)hi);
+            return finish_log(p);
+        }
+    }
+    p->fit_pass++;
+    bf::launch_log_hist_reset(p, s);
+    return BIFEAT_FIT_AGAIN;
+}
+
 bool dtype_ok(int32_t d) { return d == BIFEAT_F32 || d == BIFEAT_F16; }
 
 }  // namespace
@@ -195,6 +269,11 @@ int bifeat_fit_reset(bifeat_params *p, void *stream) {
     if (rc) return rc;
     if (p->scheme.kind == BIFEAT_VQ) p->vq_seeded = false;
     else BF_HIP(bf::launch_fit_reset(p, (hipStream_t)stream));
+    if (p->scheme.kind == BIFEAT_SQ_LOG && p->clip_fraction > 0.0) {
+        p->fit_pass = 0;
+        p->clip_prefix[0] = p->clip_prefix[1] = 0;
+        bf::launch_log_hist_reset(p, (hipStream_t)stream);
+    }
     p->fit_open = true;
     p->fit_rows = 0;
     p->fitted = false;
@@ -224,8 +303,20 @@ int bifeat_fit_update(bifeat_params *p, const void *chunk, int32_t dtype, int64_
         p->fit_rows += rows;
         return BIFEAT_OK;
     }
+    if (p->scheme.kind == BIFEAT_SQ_LOG && p->clip_fraction > 0.0) {
+        BF_HIP(bf::launch_log_hist_update(p, chunk, dtype, rows, (hipStream_t)stream));
+        if (p->fit_pass == 0) p->fit_rows += rows;
+        return BIFEAT_OK;
+    }
     BF_HIP(bf::launch_fit_update(p, chunk, dtype, rows, (hipStream_t)stream));
     p->fit_rows += rows;
+    return BIFEAT_OK;
+}
+
+int bifeat_fit_set_log_clip(bifeat_params *p, double fraction) {
+    if (!p || p->scheme.kind != BIFEAT_SQ_LOG || !(fraction >= 0.0) || !(fraction < 0.5) || p->fit_open)
+        return BIFEAT_EINVAL;
+    p->clip_fraction = fraction;
     return BIFEAT_OK;
 }
 
@@ -243,6 +334,8 @@ int bifeat_fit_finalize(bifeat_params *p, void *stream) {
     } else if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
         BF_HIP(bf::launch_finalize_uniform(p, (hipStream_t)stream));
         p->host_valid = false;
+    } else if (p->clip_fraction > 0.0) {
+        return finalize_log_clipped(p, (hipStream_t)stream);
     } else {
         uint32_t st[2];
         BF_HIP(hipMemcpyAsync(st, p->d_fit, sizeof(st), hipMemcpyDeviceToHost, (hipStream_t)stream));

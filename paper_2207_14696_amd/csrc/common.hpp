@@ -38,6 +38,13 @@ struct bifeat_params {
     size_t scratch_bytes = 0;
     uint8_t *d_zero = nullptr;  // 64 zero bytes (stand-in row for masked loads)
     int32_t *d_fit = nullptr;  // uniform: ordered-int keys [min D | max D]; log: bits of [mmin, mmax]
+    unsigned long long *d_hist = nullptr;  // log, clipped fit: digit histograms [2][kLogHistBins]
+
+    // log scheme, clipped fit: three radix-selection passes over the data
+    double clip_fraction = 0.0;  // 0 = plain fit of the extreme magnitudes
+    int fit_pass = 0;
+    uint32_t clip_prefix[2] = {0, 0};      // digits fixed so far for the low / high rank
+    unsigned long long clip_rank[2] = {0, 0};  // rank still to find inside that prefix
 
     bool fitted = false;
     bool fit_open = false;
@@ -61,6 +68,7 @@ struct bifeat_params {
 namespace bf {
 
 constexpr int kThreads = 256;
+constexpr int kLogHistBins = 2048;  // 11-bit digits of the clipped log fit
 // number of workgroups that fills the chip a few times over: 256 CUs x 8
 constexpr int kMaxBlocks = 2048;
 
@@ -68,6 +76,9 @@ hipError_t launch_fit_reset(bifeat_params *p, hipStream_t s);
 hipError_t launch_fit_update(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
                              hipStream_t s);
 hipError_t launch_finalize_uniform(bifeat_params *p, hipStream_t s);
+void launch_log_hist_reset(bifeat_params *p, hipStream_t s);
+hipError_t launch_log_hist_update(bifeat_params *p, const void *chunk, int dtype, int64_t rows,
+                                  hipStream_t s);
 hipError_t launch_vq_train(bifeat_params *p, const void *chunk, int dtype, int64_t rows, bool init,
                            int rounds, hipStream_t s);
 hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64_t rows,

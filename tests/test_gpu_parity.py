@@ -381,3 +381,61 @@ def test_vq_variant_training_matches_oracle_distortion(bf, torch, D, w, length, 
     codes = gpu_build_table(q, _dev_table(spec), spec.N, 2500, fit=False)
     assert np.array_equal(codes.cpu().numpy(),
                           orc.pack(orc.vq_assign(x, w, gcb, metric=metric), bits))
+
+
+# ---------------------------------------------- clipped logarithmic range fitted on the GPU
+@pytest.mark.parametrize("D,dtype,frac,chunk", [(37, "f32", 0.01, 700), (128, "f16", 0.001, 1024),
+                                                (64, "f32", 0.25, 5000), (5, "f32", 0.0625, 333)])
+def test_clipped_log_range_is_the_exact_order_statistic(bf, torch, D, dtype, frac, chunk):
+    spec = FeatureSpec(5000, D, 21, dtype)
+    x = feature_chunk(spec, 0, spec.N).astype(np.float32)
+    want = orc.log_range_clipped(x, frac)
+    q = bf.Quantizer(scheme_of("log", 2), D)
+    q.fit_set_log_clip(frac)
+    table = _dev_table(spec)
+    passes = 0
+    again = True
+    q.fit_reset()
+    while again:
+        for r0 in range(0, spec.N, chunk):
+            q.fit_update(table.chunk(r0, min(chunk, spec.N - r0)))
+        again = q.fit_finalize()
+        passes += 1
+    assert passes == 3
+    e_min, e_max, T, V = q.params_get_log()
+    assert (e_min, e_max) == want                 # same magnitudes, same log2
+    oT, oV = orc.log_tables(*want, 2)
+    assert np.array_equal(T, oT) and np.array_equal(V, oV)
+    codes = gpu_build_table(q, table, spec.N, 1700, fit=False)
+    assert np.array_equal(codes.cpu().numpy(), orc.pack(orc.log_encode(x, 2, oT), 2))
+
+
+def test_clipped_log_fit_special_values_and_errors(bf, torch):
+    x = np.zeros((64, 8), np.float32)
+    x[3, 2], x[5, 5], x[7, 1], x[9, 9 % 8] = np.inf, np.nan, -3.5, 0.25
+    x[20:40] = np.linspace(-2, 2, 160, dtype=np.float32).reshape(20, 8)
+    want = orc.log_range_clipped(x, 0.1)
+    q = bf.Quantizer(scheme_of("log", 4), 8)
+    q.fit_set_log_clip(0.1)
+    dx = torch.from_numpy(x).cuda()
+    q.fit_reset()
+    for _ in range(3):
+        q.fit_update(dx)
+        again = q.fit_finalize()
+    assert not again
+    e_min, e_max, _, _ = q.params_get_log()
+    assert (e_min, e_max) == want
+    # a table of zeros: no magnitudes to rank, range (0, 0) after the first pass
+    q.fit_reset()
+    q.fit_update(torch.zeros((10, 8), device="cuda"))
+    assert q.fit_finalize() is False
+    assert q.params_get_log()[:2] == (0.0, 0.0)
+    # different data in a later pass is refused
+    q.fit_reset()
+    q.fit_update(dx)
+    assert q.fit_finalize() is True
+    q.fit_update(torch.zeros((64, 8), device="cuda"))
+    with pytest.raises(bf.BifeatError):
+        q.fit_finalize()
+    with pytest.raises(bf.BifeatError):
+        q.fit_set_log_clip(0.5)
