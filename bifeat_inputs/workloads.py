@@ -32,6 +32,7 @@ class Workload:
     vq_width: int = 8
     vq_length: int = 256
     vq_metric: str = "l2"       # "l2" | "cosine"
+    log_clip: float = 0.0       # "log": fraction of the magnitudes clipped at each tail
     seed: int = 0
 
     @property
@@ -53,6 +54,12 @@ WORKLOADS = {
     "largest4": Workload("largest4", 244_000_000, 768, "f16", "uniform", 4, "powerlaw", 12,
                          (25, 15), 1024),
     "vq": Workload("vq", 100_000_000, 768, "f32", "vq", 8, "powerlaw", 15, (25, 10), 4096),
+    # the paper's headline scalar setting (Appendix B: 1 bit, sign only) on the "largest" table
+    "log1": Workload("log1", 244_000_000, 768, "f16", "log", 1, "powerlaw", 12, (25, 15), 1024),
+    # the paper's own scalar codes at 2 bits with tail clipping (Sec. 3.1, Appendix C) on the
+    # "large" table and sampling
+    "log2": Workload("log2", 111_000_000, 128, "f32", "log", 2, "powerlaw", 15, (15, 10, 5), 1024,
+                     seed_mode="degree", log_clip=0.01),
     # the paper's large-graph vector setting (Appendix B: width 16, length 2048, i.e.
     # two-byte indices, cosine search) on the "large" table and sampling
     "vq2k": Workload("vq2k", 111_000_000, 128, "f32", "vq", 8, "powerlaw", 15, (15, 10, 5), 1024,
@@ -69,7 +76,7 @@ def make_graph(w: Workload):
 # minibatches concatenated into one launch by default (what a prefetching
 # loader hands over); 1 = a single minibatch per launch
 BATCHES_PER_STEP = {"tiny": 64, "mid": 64, "large": 8, "largest1": 32, "largest4": 32, "vq": 8,
-                    "vq2k": 8}
+                    "vq2k": 8, "log2": 8, "log1": 32}
 
 
 def launch_set(w: Workload, graph, set_index: int, L: int):

@@ -44,7 +44,12 @@ int ensure_device(bifeat_params *p) {
     const int64_t D = p->D;
     size_t nfloat = 0, nfit = 0;
     if (p->scheme.kind == BIFEAT_SQ_UNIFORM) { nfloat = 4 * D; nfit = 2 * D; }
-    else if (p->scheme.kind == BIFEAT_SQ_LOG) { nfloat = 128 + 256; nfit = 4 + 2 * 2 * bf::kLogHistBins; }
+    else if (p->scheme.kind == BIFEAT_SQ_LOG) {
+        // bin edges, decode table and, for 1-bit codes, the table again as a per-column
+        // affine map (decode = V[0] + q*(V[1]-V[0])) for the integer-sum mean kernels
+        nfloat = 128 + 256 + (p->scheme.bits == 1 ? 2 * D : 0);
+        nfit = 4 + 2 * 2 * bf::kLogHistBins;
+    }
     else nfloat = (size_t)p->P * p->scheme.vq_length * (2 * p->scheme.vq_width + 2) + 64;
     nfloat = (nfloat + 3) / 4 * 4;
     nfit = (nfit + 3) / 4 * 4;
@@ -61,6 +66,10 @@ int ensure_device(bifeat_params *p) {
     } else if (p->scheme.kind == BIFEAT_SQ_LOG) {
         p->d_T = p->d_block;
         p->d_V = p->d_block + 128;
+        if (p->scheme.bits == 1) {
+            p->d_min = p->d_V + 256;
+            p->d_scale = p->d_min + D;
+        }
     } else {
         const size_t ncb = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
         const size_t nent = (size_t)p->P * p->scheme.vq_length;
@@ -95,6 +104,15 @@ int upload_log(bifeat_params *p) {
     if (!p->h_T.empty())
         BF_HIP(hipMemcpy(p->d_T, p->h_T.data(), sizeof(float) * p->h_T.size(), hipMemcpyHostToDevice));
     BF_HIP(hipMemcpy(p->d_V, p->h_V.data(), sizeof(float) * p->h_V.size(), hipMemcpyHostToDevice));
+    if (p->scheme.bits == 1) {
+        // V[1] = -V[0]: the difference and V[0] + 1*(V[1]-V[0]) are exact
+        std::vector<float> col((size_t)2 * p->D);
+        for (int64_t j = 0; j < p->D; j++) {
+            col[j] = p->h_V[0];
+            col[p->D + j] = p->h_V[1] - p->h_V[0];
+        }
+        BF_HIP(hipMemcpy(p->d_min, col.data(), sizeof(float) * col.size(), hipMemcpyHostToDevice));
+    }
     return BIFEAT_OK;
 }
 

@@ -140,7 +140,10 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
     const int D = (int)p->D;
     const int vec = (D % 4 == 0) && ((uintptr_t)out % 16 == 0);
     const int kind = p->scheme.kind;
-    if (kind == BIFEAT_SQ_UNIFORM && !p->opt_mean_generic && D <= 2048) {
+    // 1-bit logarithmic codes (Sec. 3.1: sign only) decode affinely, V[0] + q*(V[1]-V[0]),
+    // so they take the integer-sum kernels of the uniform codes with that map per column
+    const bool affine = kind == BIFEAT_SQ_UNIFORM || (kind == BIFEAT_SQ_LOG && p->scheme.bits == 1);
+    if (affine && !p->opt_mean_generic && D <= 2048) {
         // Short lists (sampled blocks) go to the lean kernel, anything longer to the
         // general one; each skips the other's destinations.  The caller's bound on
         // the list length (or, without one, twice the average) picks the lean

@@ -161,7 +161,7 @@ def _tables(bf, torch, kind, bits, D, N=6007, w=8, length=32, seed=6):
 
 CASES = [("uniform", 1, 768), ("uniform", 2, 128), ("uniform", 4, 100), ("uniform", 8, 128),
          ("uniform", 4, 37), ("uniform", 8, 5), ("uniform", 1, 70), ("uniform", 2, 1),
-         ("log", 1, 64), ("log", 2, 100), ("log", 4, 37), ("log", 8, 16),
+         ("log", 1, 64), ("log", 1, 768), ("log", 2, 100), ("log", 4, 37), ("log", 8, 16),
          ("vq", 8, 64), ("vq", 8, 100), ("vq", 8, 23), ("vq", 8, 96)]
 
 

@@ -223,3 +223,49 @@ def test_vq_16x2048_cosine_two_byte(torch, bf):
         encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb, metric=w.vq_metric), 16))
     del codes
     torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(900)
+def test_log_2bit_clipped(torch, bf):
+    # The paper's own scalar codes at 2 bits, range clipped at both tails (Sec. 3.1,
+    # Appendix C).  The oracle cannot sort 14 G magnitudes, so the fitted range is pinned
+    # by the defining property of an order statistic, counted with library reductions:
+    # #{m < value} <= rank < #{m <= value}.
+    from bifeat_inputs.device import DeviceTable
+    w = WORKLOADS["log2"]
+    q = bf.Quantizer(scheme_of("log", w.bits), w.D)
+    q.fit_set_log_clip(w.log_clip)
+    table = DeviceTable(w.spec)
+    buf = torch.empty((CHUNK, w.D), dtype=table.torch_dtype, device="cuda")
+    q.fit_reset()
+    passes, again = 0, True
+    while again:
+        for r0 in range(0, w.N, CHUNK):
+            n = min(CHUNK, w.N - r0)
+            q.fit_update(table.chunk(r0, n, buf[:n]))
+        again = q.fit_finalize()
+        passes += 1
+    assert passes == 3
+    e_min, e_max, T, V = q.params_get_log()
+    lo, hi = np.float32(2.0 ** e_min), np.float32(2.0 ** e_max)
+    assert np.log2(np.float64(lo)) == e_min and np.log2(np.float64(hi)) == e_max
+    cnt = np.zeros(5, dtype=np.int64)        # n, <lo, <=lo, <hi, <=hi
+    for r0 in range(0, w.N, CHUNK):
+        n = min(CHUNK, w.N - r0)
+        m = table.chunk(r0, n, buf[:n]).abs()
+        ok = torch.isfinite(m) & (m > 0)
+        cnt += np.array([int(ok.sum()), int((ok & (m < float(lo))).sum()), int((ok & (m <= float(lo))).sum()),
+                         int((ok & (m < float(hi))).sum()), int((ok & (m <= float(hi))).sum())])
+    k_lo = int(np.floor(w.log_clip * (cnt[0] - 1)))
+    k_hi = int(np.ceil((1.0 - w.log_clip) * (cnt[0] - 1)))
+    assert cnt[1] <= k_lo < cnt[2] and cnt[3] <= k_hi < cnt[4]
+    oT, oV = orc.log_tables(e_min, e_max, w.bits)
+    assert np.array_equal(T, oT) and np.array_equal(V, oV)
+    del buf
+    (codes,), *_ = _stream_table(torch, w, [q], fit=False)
+    _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
+        encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
+    del codes
+    torch.cuda.empty_cache()
