@@ -319,3 +319,12 @@ def gather_mean(s: Scheme, codes, indptr, indices) -> np.ndarray:
     out = np.empty((V, s.D), dtype=np.float32)
     lib().orc_gather_mean(C.byref(s._c), _p(codes), _p(indptr), _p(indices), C.c_int64(V), _p(out))
     return out
+
+
+def gather_sum(s: Scheme, codes, indptr, indices) -> np.ndarray:
+    codes, indptr, indices = _u8(codes), _i64(indptr), _i64(indices)
+    assert codes.shape[1] == s.row_bytes
+    V = indptr.shape[0] - 1
+    out = np.empty((V, s.D), dtype=np.float32)
+    lib().orc_gather_sum(C.byref(s._c), _p(codes), _p(indptr), _p(indices), C.c_int64(V), _p(out))
+    return out

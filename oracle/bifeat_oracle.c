@@ -540,6 +540,31 @@ void orc_gather_dequant(const orc_scheme *s, const uint8_t *codes, const int64_t
     }
 }
 
+/* The unnormalised form of the aggregation below (the sum aggregator of
+ * GraphSAGE-style layers; Appendix A.1 analyses the mean): out[v] = sum over the
+ * listed neighbours of their decoded rows, in list order, fp64, one rounding to
+ * fp32; an empty list gives a zero row. */
+void orc_gather_sum(const orc_scheme *s, const uint8_t *codes, const int64_t *indptr,
+                    const int64_t *indices, int64_t V, float *out) {
+    int64_t rb = orc_scheme_row_bytes(s), D = s->D;
+#pragma omp parallel
+    {
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)D);
+        double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(dynamic, 64)
+        for (int64_t v = 0; v < V; v++) {
+            for (int64_t j = 0; j < D; j++) acc[j] = 0.0;
+            for (int64_t e = indptr[v]; e < indptr[v + 1]; e++) {
+                decode_row(s, codes + indices[e] * rb, tmp);
+                for (int64_t j = 0; j < D; j++) acc[j] += tmp[j];
+            }
+            for (int64_t j = 0; j < D; j++) out[v * D + j] = (float)acc[j];
+        }
+        free(tmp);
+        free(acc);
+    }
+}
+
 /* Appendix A.1: out[v] = (1/|N(v)|) * sum over the listed neighbours of their
  * decoded rows, in list order, fp64, one rounding to fp32.  The list is taken
  * as given (repeats count with multiplicity; a self-loop is present only if

@@ -90,3 +90,43 @@ def test_rounding_errors_cancel_under_averaging():
     rms_row = np.sqrt(((dec - x) ** 2).mean(0))
     rms_mean = np.sqrt(((mean_q - mean_x) ** 2).mean(0))
     assert np.allclose(rms_mean, rms_row / np.sqrt(n), rtol=0.1)
+
+
+# ------------------------------------------- other aggregators over the same compressed rows
+@pytest.mark.parametrize("bits", [1, 4])
+def test_sum_matches_sparse_matrix_product(bits):
+    x, s, codes = _quantized(bits=bits)
+    rng = np.random.default_rng(40 + bits)
+    indptr, indices = _random_csr(150, x.shape[0], 12, rng)
+    got = orc.gather_sum(s, codes, indptr, indices)
+    dec = orc.gather_dequant(s, codes, np.arange(x.shape[0])).astype(np.float64)
+    A = sp.csr_matrix((np.ones(len(indices)), indices, indptr), shape=(150, x.shape[0]))
+    want = A @ dec                                           # repeats add up in the CSR product
+    assert np.allclose(got, want, rtol=1e-6, atol=1e-6)
+    assert not got[0].any()
+    # mean = sum / count wherever the list is not empty
+    n = np.diff(indptr)[:, None]
+    mean = orc.gather_mean(s, codes, indptr, indices)
+    assert np.allclose(mean[n[:, 0] > 0], (got / np.maximum(n, 1))[n[:, 0] > 0], rtol=1e-6, atol=1e-7)
+
+
+def test_mean_with_self_in_the_list_is_the_self_loop_normalisation():
+    # Appendix A.1 writes the layer with D^-1 (A + I): listing v among its own
+    # neighbours turns the plain mean into that operator
+    x, s, codes = _quantized(rows=300)
+    rng = np.random.default_rng(77)
+    N = x.shape[0]
+    deg = rng.integers(0, 9, N)
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    indices = rng.integers(0, N, indptr[-1]).astype(np.int64)
+    # lists with the destination itself appended
+    ptr2 = indptr + np.arange(N + 1)
+    idx2 = np.empty(ptr2[-1], np.int64)
+    for v in range(N):
+        idx2[ptr2[v]:ptr2[v + 1] - 1] = indices[indptr[v]:indptr[v + 1]]
+        idx2[ptr2[v + 1] - 1] = v
+    got = orc.gather_mean(s, codes, ptr2, idx2)
+    dec = orc.gather_dequant(s, codes, np.arange(N)).astype(np.float64)
+    A = sp.csr_matrix((np.ones(len(indices)), indices, indptr), shape=(N, N)) + sp.identity(N)
+    want = sp.diags(1.0 / np.asarray(A.sum(1)).ravel()) @ (A @ dec)
+    assert np.allclose(got, want, rtol=1e-6, atol=1e-7)
