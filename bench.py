@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--mean-slots", type=int, default=0)
     ap.add_argument("--mean-blocks", type=int, default=0)
     ap.add_argument("--max-blocks", type=int, default=0)
+    ap.add_argument("--aggregator", default="mean", choices=["mean", "sum"],
+                    help="which fused aggregation the hops run (the metric's workload is mean)")
     return ap.parse_args()
 
 
@@ -173,6 +175,8 @@ def main():
     out_h = [torch.empty((v, w.D), dtype=torch.float32, device=dev) for v in max_v]
     outer = len(w.fanouts) - 1
 
+    aggregate = q.gather_sum if args.aggregator == "sum" else q.gather_mean
+
     def step(i, timed=None):
         s = sets[i % B]
         if timed is not None:
@@ -185,7 +189,7 @@ def main():
                 timed[2].record()
             # the sampler's contract: no list of hop h is longer than its fan-out
             q.set_option("mean_max_degree", w.fanouts[h])
-            q.gather_mean(codes, dp, di, out_h[h][:dp.shape[0] - 1])
+            aggregate(codes, dp, di, out_h[h][:dp.shape[0] - 1])
         if timed is not None:
             timed[3].record()
 
@@ -272,7 +276,8 @@ def main():
                    "vq": [w.vq_width, w.vq_length, w.vq_metric] if w.kind == "vq" else None,
                    "row_bytes": rb, "graph": w.graph, "avg_degree": w.avg_degree,
                    "fanouts": list(w.fanouts), "batch": w.batch, "batches_per_step": L,
-                   "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B},
+                   "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B,
+                   "aggregator": args.aggregator},
         "rows_per_step": int(rows_total / args.steps),
         "uncompressed_equiv_GBps": round(value * w.D * esz / 1e9, 1),
         "roofline": roofline,

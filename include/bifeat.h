@@ -192,6 +192,15 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
 int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                        const int64_t *indices, int64_t V, int64_t E, float *out, void *stream);
 
+/* ---- the same without the division: the sum aggregator.  out[v, :] = sum over
+ * the list of decode(codes[indices[e]]) (Appendix A.1 analyses the mean; the
+ * sum is its unnormalised form, and with v listed among its own neighbours
+ * bifeat_gather_mean is the self-loop normalisation D^-1 (A + I) written
+ * there).  Arguments as bifeat_gather_mean; fp32 result within
+ * 1e-5 * max(|exact|, n_v * A_j), n_v the list length. */
+int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                      const int64_t *indices, int64_t V, int64_t E, float *out, void *stream);
+
 const char *bifeat_strerror(int status);
 
 /* Launch tuning for measurements (no effect on results): "mean_slots" = lanes

@@ -65,6 +65,8 @@ _SIGNATURES = {
                                         C.c_void_p, C.c_void_p]),
     "bifeat_gather_mean": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_gather_sum": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_strerror": (C.c_char_p, [C.c_int]),
     "bifeat_set_option": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int]),
 }
@@ -245,16 +247,20 @@ class Quantizer:
                                                _dev_ptr(out, (torch.float32,)), _stream()))
         return out
 
-    def gather_mean(self, codes, indptr, indices, out=None):
+    def _aggregate(self, fn, codes, indptr, indices, out):
         import torch
         V = indptr.shape[0] - 1
         if out is None:
             out = torch.empty((V, self.D), dtype=torch.float32, device=codes.device)
         elif out.shape != (V, self.D):
             raise ValueError("out must be [V, D]")
-        _check(self._lib.bifeat_gather_mean(self._h, _dev_ptr(codes, (torch.uint8,)),
-                                            codes.shape[0], _dev_ptr(indptr, (torch.int64,)),
-                                            _dev_ptr(indices, (torch.int64,)), V,
-                                            indices.shape[0],
-                                            _dev_ptr(out, (torch.float32,)), _stream()))
+        _check(fn(self._h, _dev_ptr(codes, (torch.uint8,)), codes.shape[0],
+                  _dev_ptr(indptr, (torch.int64,)), _dev_ptr(indices, (torch.int64,)), V,
+                  indices.shape[0], _dev_ptr(out, (torch.float32,)), _stream()))
         return out
+
+    def gather_mean(self, codes, indptr, indices, out=None):
+        return self._aggregate(self._lib.bifeat_gather_mean, codes, indptr, indices, out)
+
+    def gather_sum(self, codes, indptr, indices, out=None):
+        return self._aggregate(self._lib.bifeat_gather_sum, codes, indptr, indices, out)

@@ -521,6 +521,15 @@ int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const 
     return BIFEAT_OK;
 }
 
+int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                      const int64_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+    if (!p) return BIFEAT_EINVAL;
+    p->agg_sum = 1;
+    const int rc = bifeat_gather_mean(p, codes, N, indptr, indices, V, E, out, stream);
+    p->agg_sum = 0;
+    return rc;
+}
+
 const char *bifeat_strerror(int status) {
     switch (status) {
         case BIFEAT_OK: return "ok";

@@ -53,6 +53,8 @@ struct bifeat_params {
     int64_t vq_last_rows = 0;   // rows of the last training chunk
     int vq_last_rounds = 0;
 
+    int agg_sum = 0;  // 1 while a gather_sum call is being launched: no division by the list length
+
     // launch tuning (0 = automatic)
     int opt_mean_slots = 0;
     int opt_mean_blocks = 0;

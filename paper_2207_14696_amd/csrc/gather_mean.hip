@@ -31,7 +31,7 @@ template <int KIND, int BITS, bool VEC>
 __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ pa,
-    const float *__restrict__ pb, int w, int len, float *__restrict__ out) {
+    const float *__restrict__ pb, int w, int len, int agg_sum, float *__restrict__ out) {
     __shared__ float s_lut[KIND == MK_LOG ? (1 << (BITS & 15)) : 1];
     if constexpr (KIND == MK_LOG) {
         for (int i = threadIdx.x; i < (1 << BITS); i += kThreads) s_lut[i] = pa[i];
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
 #pragma unroll
             for (int k = 0; k < 4; k++) total[k] += (double)acc[k];
         }
-        const double inv_nd = end > beg ? 1.0 / (double)(end - beg) : 0.0;
+        const double inv_nd = agg_sum ? 1.0 : (end > beg ? 1.0 / (double)(end - beg) : 0.0);
         float acc[4];
 #pragma unroll
         for (int k = 0; k < 4; k++) acc[k] = (float)(total[k] * inv_nd);
@@ -117,8 +117,8 @@ static void launch_float(bifeat_params *p, const uint8_t *codes, const int64_t *
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
 #define BF_FL(B)                                                                                         \
     do {                                                                                                 \
-        if (vec) gather_mean_float_kernel<KIND, B, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, out); \
-        else gather_mean_float_kernel<KIND, B, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, out);    \
+        if (vec) gather_mean_float_kernel<KIND, B, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, out); \
+        else gather_mean_float_kernel<KIND, B, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, out);    \
     } while (0)
     if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
         if (p->cbytes == 2) BF_FL(16);

@@ -77,7 +77,9 @@ constexpr int kWaves = kThreads / 64;
 #define BF_LEAN_WPE 6
 #endif
 
-template <int BITS, int CW, bool WIDE>
+// SUM: the sum aggregator (no division by the list length): meta carries n and
+// the column minimum is scaled by it instead
+template <int BITS, int CW, bool WIDE, bool SUM>
 __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel(
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
@@ -126,7 +128,8 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
         const int64_t n64 = end - beg;
         const bool mine = d_local < ndst && n64 <= thr;  // longer lists: the general kernel
         const int n = mine ? (int)n64 : 0;
-        if (lane_chunk == 0) meta[d_local] = mine ? (n > 0 ? 1.0f / (float)n : 0.0f) : -1.0f;
+        if (lane_chunk == 0)
+            meta[d_local] = mine ? (n > 0 ? (SUM ? (float)n : 1.0f / (float)n) : 0.0f) : -1.0f;
 
         uint32_t acc[R];
 #pragma unroll
@@ -194,10 +197,17 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
             const float4 b = *reinterpret_cast<const float4 *>(s_mn + j0);
             const bool some = md > 0.0f;  // md == 0: empty list, zero row
             float4 val;
-            val.x = some ? fmaf(a.x, (float)sum[0] * md, b.x) : 0.0f;
-            val.y = some ? fmaf(a.y, (float)sum[1] * md, b.y) : 0.0f;
-            val.z = some ? fmaf(a.z, (float)sum[2] * md, b.z) : 0.0f;
-            val.w = some ? fmaf(a.w, (float)sum[3] * md, b.w) : 0.0f;
+            if constexpr (SUM) {
+                val.x = some ? fmaf(a.x, (float)sum[0], b.x * md) : 0.0f;
+                val.y = some ? fmaf(a.y, (float)sum[1], b.y * md) : 0.0f;
+                val.z = some ? fmaf(a.z, (float)sum[2], b.z * md) : 0.0f;
+                val.w = some ? fmaf(a.w, (float)sum[3], b.w * md) : 0.0f;
+            } else {
+                val.x = some ? fmaf(a.x, (float)sum[0] * md, b.x) : 0.0f;
+                val.y = some ? fmaf(a.y, (float)sum[1] * md, b.y) : 0.0f;
+                val.z = some ? fmaf(a.z, (float)sum[2] * md, b.z) : 0.0f;
+                val.w = some ? fmaf(a.w, (float)sum[3] * md, b.w) : 0.0f;
+            }
             if (md >= 0.0f) store_stream(&span[m], val);  // md < 0: not this kernel's destination
             d += step_d;
             f += step_f;
@@ -250,9 +260,16 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
     const int R = cw * W::kN;
     const size_t shm = sizeof(uint32_t) * ((size_t)2 * D + 64 * kWaves + (size_t)kWaves * 64 * R);
 #define BF_LN(CWV)                                                                               \
-    gather_mean_lean_kernel<BITS, CWV, WIDE><<<blocks, kThreads, shm, s>>>(                            \
-        codes, (uint32_t)rb, indptr, indices, V, D, p->d_min, p->d_scale, p->d_zero, out,        \
-        ilog2(lpr), chunks, thr)
+    do {                                                                                         \
+        if (p->agg_sum)                                                                          \
+            gather_mean_lean_kernel<BITS, CWV, WIDE, true><<<blocks, kThreads, shm, s>>>(        \
+                codes, (uint32_t)rb, indptr, indices, V, D, p->d_min, p->d_scale, p->d_zero,     \
+                out, ilog2(lpr), chunks, thr);                                                   \
+        else                                                                                     \
+            gather_mean_lean_kernel<BITS, CWV, WIDE, false><<<blocks, kThreads, shm, s>>>(       \
+                codes, (uint32_t)rb, indptr, indices, V, D, p->d_min, p->d_scale, p->d_zero,     \
+                out, ilog2(lpr), chunks, thr);                                                   \
+    } while (0)
     switch (cw) {
         case 4: BF_LN(4); break;
         case 3: BF_LN(3); break;

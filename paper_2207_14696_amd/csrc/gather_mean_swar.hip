@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
     const float *__restrict__ sc, float *__restrict__ out, int lpr_log2, int s_log2, int chunks,
-    int long_thr, int min_len) {
+    int long_thr, int min_len, int agg_sum) {
     using W = Swar<BITS>;
     constexpr bool kTwoLevel = W::kF1 != W::kF0;
     constexpr int R0 = CW * W::kN0, R1 = CW * W::kN1;
@@ -166,7 +166,8 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
             const bool is_long = mode == 0 && (scan ? !is_short : n > long_thr);
             if (mode == 0) hubs = __ballot(valid && is_long && lig == 0);
             if (mode == 0 && scan) continue;  // nothing is accumulated in the scan pass
-            const float inv_n = n > 0 ? 1.0f / (float)n : 0.0f;
+            // mean: 1/n, applied to the code sum; sum aggregator: n, applied to the column minimum
+            const float inv_n = agg_sum ? (float)n : (n > 0 ? 1.0f / (float)n : 0.0f);
             if (is_long || is_short) end = beg;  // whole wave afterwards / other kernel
 
             for (int cbase = 0; cbase < chunks; cbase += LPR) {
@@ -325,10 +326,11 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                             }
                             const bool empty = fl & F_EMPTY;  // empty list: zero row
                             float4 val;
-                            val.x = empty ? 0.f : fmaf(a.x, (float)sum[0] * md.x, b.x);
-                            val.y = empty ? 0.f : fmaf(a.y, (float)sum[1] * md.x, b.y);
-                            val.z = empty ? 0.f : fmaf(a.z, (float)sum[2] * md.x, b.z);
-                            val.w = empty ? 0.f : fmaf(a.w, (float)sum[3] * md.x, b.w);
+                            const float ms = agg_sum ? 1.0f : md.x, mb = agg_sum ? md.x : 1.0f;
+                            val.x = empty ? 0.f : fmaf(a.x, (float)sum[0] * ms, b.x * mb);
+                            val.y = empty ? 0.f : fmaf(a.y, (float)sum[1] * ms, b.y * mb);
+                            val.z = empty ? 0.f : fmaf(a.z, (float)sum[2] * ms, b.z * mb);
+                            val.w = empty ? 0.f : fmaf(a.w, (float)sum[3] * ms, b.w * mb);
                             if constexpr (kRounds) {
                                 if (fl & F_MORE)
                                     val = make_float4(__uint_as_float(sum[0]), __uint_as_float(sum[1]),
@@ -396,6 +398,7 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                                     float val;
                                     if (fl & F_MORE) val = __uint_as_float(sx);
                                     else if (fl & F_EMPTY) val = 0.f;
+                                    else if (agg_sum) val = fmaf(s_sc[j0 + x], (float)sx, s_mn[j0 + x] * md.x);
                                     else val = fmaf(s_sc[j0 + x], (float)sx * md.x, s_mn[j0 + x]);
                                     dst[x] = val;
                                 }
@@ -469,11 +472,11 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
         if (vec)                                                                                   \
             gather_mean_swar_kernel<BITS, CWV, true><<<blocks, kThreads, shm, s>>>(                \
                 codes, rb, indptr, indices, V, (int)p->D, p->d_min, p->d_scale, out, ilog2(lpr),   \
-                ilog2(S), chunks, long_thr, min_len);                                                       \
+                ilog2(S), chunks, long_thr, min_len, p->agg_sum);                                                       \
         else                                                                                       \
             gather_mean_swar_kernel<BITS, CWV, false><<<blocks, kThreads, shm, s>>>(               \
                 codes, rb, indptr, indices, V, (int)p->D, p->d_min, p->d_scale, out, ilog2(lpr),   \
-                ilog2(S), chunks, long_thr, min_len);                                                       \
+                ilog2(S), chunks, long_thr, min_len, p->agg_sum);                                                       \
     } while (0)
     switch (cw) {
         case 4: BF_SW(4); break;

@@ -318,7 +318,7 @@ constexpr int kPre = BF_VQ_PRE;
 template <int CPL>
 __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
     const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
-    int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes,
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes, int agg_sum,
     const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
     const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2, cbytes);
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
                 if ((uint32_t)(4 * k) < n) L.add4(cur[k], n - 4 * k, acc);
             if (n > 4 * kPre) L.run(beg + 4 * kPre, beg + n, acc);
             // 1 ulp reciprocal: far inside the 1e-5 budget
-            const float inv_n = n > 0 ? __builtin_amdgcn_rcpf((float)n) : 0.0f;
+            const float inv_n = agg_sum ? 1.0f : (n > 0 ? __builtin_amdgcn_rcpf((float)n) : 0.0f);
             float res[CPL];
 #pragma unroll
             for (int k = 0; k < CPL; k++) res[k] = acc[k] * inv_n;
@@ -375,7 +375,7 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
 template <int CPL>
 __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_long_kernel(
     const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
-    int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes,
+    int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes, int agg_sum,
     const float *__restrict__ cb, float *__restrict__ out) {
     extern __shared__ float s_cb[];
     const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2, cbytes);
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_long_kernel(
 #pragma unroll
             for (int k = 0; k < CPL; k++) total[k] += (double)acc[k];
         }
-        const double inv_n = 1.0 / (double)(end - beg);
+        const double inv_n = agg_sum ? 1.0 : 1.0 / (double)(end - beg);
         float res[CPL];
 #pragma unroll
         for (int k = 0; k < CPL; k++) res[k] = (float)(total[k] * inv_n);
@@ -484,7 +484,7 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const 
 #define BF_VQL(KERNEL)                                                                       \
     KERNEL<<<grid, kVqThreads, g.lds, s>>>((const uint32_t *)p->d_scratch, MS, indptr, V,     \
                                            (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(lps),   \
-                                           p->cbytes, p->d_cb, out)
+                                           p->cbytes, p->agg_sum, p->d_cb, out)
     if (cpl == 8) {
         BF_VQL(gather_mean_vq_short_kernel<8>);
         if (with_long) BF_VQL(gather_mean_vq_long_kernel<8>);

@@ -439,3 +439,50 @@ def test_clipped_log_fit_special_values_and_errors(bf, torch):
         q.fit_finalize()
     with pytest.raises(bf.BifeatError):
         q.fit_set_log_clip(0.5)
+
+
+# ------------------------------------------------------------------- sum aggregator
+def _assert_sum_close(got, want, s, n, what=""):
+    """|gpu - oracle| <= 1e-5 * max(|oracle|, n_v * A_j): a sum of n_v terms of size A_j."""
+    from helpers import column_magnitude, REL_TOL
+    A = column_magnitude(s).astype(np.float64)[None, :] * np.maximum(n, 1)[:, None]
+    bound = REL_TOL * np.maximum(np.abs(want.astype(np.float64)), A)
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert not (err > bound).any(), f"{what}: worst err/bound = {(err / bound).max():.3g}"
+
+
+@pytest.mark.parametrize("kind,bits,D", CASES)
+def test_gather_sum(bf, torch, kind, bits, D):
+    w = {23: 5, 100: 4, 96: 16}.get(D, 8)
+    q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, w=w)
+    rng = np.random.default_rng(2)
+    hubs = (90, 300, 700, 4500) if kind == "uniform" else (300,)
+    indptr, indices = random_csr(1201, codes.shape[0], 30, rng, hubs=hubs)
+    want = orc.gather_sum(s, codes, indptr, indices)
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    got = q.gather_sum(dcodes, dptr, dind).cpu().numpy()
+    assert not got[0].any()
+    _assert_sum_close(got, want, s, np.diff(indptr), "gather_sum")
+    # the mean entry point is unaffected by a sum call before it
+    assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), orc.gather_mean(s, codes, indptr, indices), s)
+    # short lists with the caller's bound: the short-list kernels alone
+    indptr, indices = random_csr(801, codes.shape[0], 10, rng)
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    q.set_option("mean_max_degree", 10)
+    got = q.gather_sum(dcodes, dptr, dind).cpu().numpy()
+    q.set_option("mean_max_degree", 0)
+    _assert_sum_close(got, orc.gather_sum(s, codes, indptr, indices), s, np.diff(indptr), "short lists")
+
+
+def test_mean_with_self_loops_on_the_gpu(bf, torch):
+    # D^-1 (A + I) of Appendix A.1: the destination listed among its own neighbours
+    q, s, codes, dcodes = _tables(bf, torch, "uniform", 4, 100)
+    rng = np.random.default_rng(8)
+    V, N = 700, codes.shape[0]
+    dst_rows = rng.choice(N, V, replace=False)
+    deg = rng.integers(0, 12, V)
+    ptr = np.concatenate([[0], np.cumsum(deg + 1)]).astype(np.int64)
+    idx = rng.integers(0, N, ptr[-1]).astype(np.int64)
+    idx[ptr[1:] - 1] = dst_rows                      # last entry of every list: the destination
+    got = q.gather_mean(dcodes, torch.from_numpy(ptr).cuda(), torch.from_numpy(idx).cuda())
+    assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, ptr, idx), s)
