@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--mean-slots", type=int, default=0)
     ap.add_argument("--mean-blocks", type=int, default=0)
     ap.add_argument("--max-blocks", type=int, default=0)
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each launch-set's step from a captured HIP graph (whole-step "
+                         "timing; per-kernel figures still come from an eager pass)")
     ap.add_argument("--aggregator", default="mean", choices=["mean", "sum"],
                     help="which fused aggregation the hops run (the metric's workload is mean)")
     return ap.parse_args()
@@ -209,6 +212,23 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall = t1 - t0
+    if args.graph:
+        # launch-bound steps (one minibatch per launch): the same launches replayed from
+        # captured graphs, one per launch-set; the eager pass above keeps the per-kernel events
+        graphs = []
+        for i in range(B):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                step(i)
+            graphs.append(gr)
+        for i in range(args.warmup):
+            graphs[i % B].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % B].replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     say(f"timed region done: {args.steps} steps in {wall * 1e3:.1f} ms")
     rows_total = sum(sets[i % B]["rows"] for i in range(args.steps))
     ms_per_step = wall / args.steps * 1e3
@@ -277,7 +297,7 @@ def main():
                    "row_bytes": rb, "graph": w.graph, "avg_degree": w.avg_degree,
                    "fanouts": list(w.fanouts), "batch": w.batch, "batches_per_step": L,
                    "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B,
-                   "aggregator": args.aggregator},
+                   "aggregator": args.aggregator, "hip_graph": bool(args.graph)},
         "rows_per_step": int(rows_total / args.steps),
         "uncompressed_equiv_GBps": round(value * w.D * esz / 1e9, 1),
         "roofline": roofline,

@@ -486,3 +486,30 @@ def test_mean_with_self_loops_on_the_gpu(bf, torch):
     idx[ptr[1:] - 1] = dst_rows                      # last entry of every list: the destination
     got = q.gather_mean(dcodes, torch.from_numpy(ptr).cuda(), torch.from_numpy(idx).cuda())
     assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, ptr, idx), s)
+
+
+def test_calls_replay_from_a_captured_graph(bf, torch):
+    # the per-iteration calls enqueue kernels only (no allocation, no memset, no
+    # synchronisation), so a step can be captured once and replayed; every replay must
+    # reproduce the eager result, with eager work in between
+    q, s, codes, dcodes = _tables(bf, torch, "uniform", 4, 100)
+    rng = np.random.default_rng(12)
+    idx = torch.from_numpy(rng.integers(0, codes.shape[0], 1500).astype(np.int64)).cuda()
+    indptr, indices = random_csr(400, codes.shape[0], 10, rng, hubs=(120,))
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    eager_a = q.gather_dequant(dcodes, idx).clone()
+    eager_b = q.gather_mean(dcodes, dptr, dind).clone()
+    out_a, out_b = torch.empty_like(eager_a), torch.empty_like(eager_b)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        q.gather_dequant(dcodes, idx, out_a)
+        q.gather_mean(dcodes, dptr, dind, out_b)
+    for rep in range(3):
+        out_a.fill_(-1.0)
+        out_b.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, eager_a) and torch.equal(out_b, eager_b), f"replay {rep}"
+        # eager work between replays
+        assert torch.equal(q.gather_mean(dcodes, dptr, dind), eager_b)
