@@ -47,7 +47,7 @@ int ensure_device(bifeat_params *p) {
     else if (p->scheme.kind == BIFEAT_SQ_LOG) {
         // bin edges, decode table and, for 1-bit codes, the table again as a per-column
         // affine map (decode = V[0] + q*(V[1]-V[0])) for the integer-sum mean kernels
-        nfloat = 128 + 256 + (p->scheme.bits == 1 ? 2 * D : 0);
+        nfloat = 128 + 256 + (p->scheme.bits == 1 ? 2 * D : p->scheme.bits == 2 ? 4 * D : 0);
         nfit = 4 + 2 * 2 * bf::kLogHistBins;
     }
     else nfloat = (size_t)p->P * p->scheme.vq_length * (2 * p->scheme.vq_width + 2) + 64;
@@ -69,6 +69,9 @@ int ensure_device(bifeat_params *p) {
         if (p->scheme.bits == 1) {
             p->d_min = p->d_V + 256;
             p->d_scale = p->d_min + D;
+        } else if (p->scheme.bits == 2) {  // per bit column: 2*D entries each
+            p->d_min = p->d_V + 256;
+            p->d_scale = p->d_min + 2 * D;
         }
     } else {
         const size_t ncb = (size_t)p->P * p->scheme.vq_length * p->scheme.vq_width;
@@ -110,6 +113,18 @@ int upload_log(bifeat_params *p) {
         for (int64_t j = 0; j < p->D; j++) {
             col[j] = p->h_V[0];
             col[p->D + j] = p->h_V[1] - p->h_V[0];
+        }
+        BF_HIP(hipMemcpy(p->d_min, col.data(), sizeof(float) * col.size(), hipMemcpyHostToDevice));
+    } else if (p->scheme.bits == 2) {
+        // decoded sum = (v1 - v0)*S0 - n*v1 + (v0 + v1)*S1 over the two bit planes of a column
+        // (V = [-v1, -v0, v0, v1]): bit column 2t maps S0, bit column 2t+1 maps S1
+        const double v0 = p->h_V[2], v1 = p->h_V[3];
+        std::vector<float> col((size_t)4 * p->D);
+        for (int64_t j = 0; j < p->D; j++) {
+            col[2 * j] = (float)-v1;
+            col[2 * j + 1] = 0.0f;
+            col[2 * p->D + 2 * j] = (float)(v1 - v0);
+            col[2 * p->D + 2 * j + 1] = (float)(v0 + v1);
         }
         BF_HIP(hipMemcpy(p->d_min, col.data(), sizeof(float) * col.size(), hipMemcpyHostToDevice));
     }

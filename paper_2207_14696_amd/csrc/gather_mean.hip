@@ -31,7 +31,8 @@ template <int KIND, int BITS, bool VEC>
 __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ pa,
-    const float *__restrict__ pb, int w, int len, int agg_sum, float *__restrict__ out) {
+    const float *__restrict__ pb, int w, int len, int agg_sum, int min_len,
+    float *__restrict__ out) {
     __shared__ float s_lut[KIND == MK_LOG ? (1 << (BITS & 15)) : 1];
     if constexpr (KIND == MK_LOG) {
         for (int i = threadIdx.x; i < (1 << BITS); i += kThreads) s_lut[i] = pa[i];
@@ -60,6 +61,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
     constexpr uint32_t mask = (1u << BITS) - 1u;
     for (int64_t v = t / G; v < V; v += per_pass) {
         const int64_t beg = indptr[v], end = indptr[v + 1];
+        if (end - beg <= min_len) continue;  // a short-list kernel's destination
         // fp32 sums over runs of kRun neighbours, runs combined in fp64: keeps the
         // rounding error of very long lists far below the 1e-5 budget
         constexpr int kRun = 32;
@@ -110,15 +112,15 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
 template <int KIND>
 static void launch_float(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                          const int64_t *indices, int64_t V, const float *pa, const float *pb,
-                         float *out, int vec, hipStream_t s) {
+                         float *out, int vec, hipStream_t s, int min_len = -1) {
     const int D = (int)p->D, G = (D + 3) / 4;
     int blocks = blocks_for(V * G);
     if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
 #define BF_FL(B)                                                                                         \
     do {                                                                                                 \
-        if (vec) gather_mean_float_kernel<KIND, B, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, out); \
-        else gather_mean_float_kernel<KIND, B, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, out);    \
+        if (vec) gather_mean_float_kernel<KIND, B, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, min_len, out); \
+        else gather_mean_float_kernel<KIND, B, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, min_len, out);    \
     } while (0)
     if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
         if (p->cbytes == 2) BF_FL(16);
@@ -158,6 +160,18 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
         if (!all_short) launch_gather_mean_swar(p, codes, indptr, indices, V, E, out, vec, lean ? thr : -1, s);
     } else if (kind == BIFEAT_SQ_UNIFORM) {
         launch_float<MK_UNIFORM>(p, codes, indptr, indices, V, p->d_min, p->d_scale, out, vec, s);
+    } else if (kind == BIFEAT_SQ_LOG && p->scheme.bits == 2 && vec && D <= 1024 && !p->opt_mean_generic) {
+        // short lists: the two bit planes summed as integers by the 1-bit short-list kernel;
+        // longer lists: the table look-up kernel, each skipping the other's destinations
+        const int64_t avg = V > 0 ? E / V : 0;
+        const int64_t need = p->opt_mean_max_degree > 0 ? p->opt_mean_max_degree : 2 * avg;
+        const bool wide = need > lean_capacity(1, false);
+        const int thr = lean_capacity(1, wide);
+        const bool lean = p->opt_mean_lean && V > 0 && need <= thr &&
+                          launch_gather_mean_lean_log2(p, codes, indptr, indices, V, out, thr, wide, s);
+        const bool all_short = lean && p->opt_mean_max_degree > 0;
+        if (!all_short)
+            launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, lean ? thr : -1);
     } else if (kind == BIFEAT_SQ_LOG) {
         launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s);
     } else if (p->opt_vq_sliced && launch_gather_mean_vq_sliced(p, codes, indptr, indices, V, E, out, s)) {

@@ -78,11 +78,16 @@ constexpr int kWaves = kThreads / 64;
 #endif
 
 // SUM: the sum aggregator (no division by the list length): meta carries n and
-// the column minimum is scaled by it instead
-template <int BITS, int CW, bool WIDE, bool SUM>
+// the column minimum is scaled by it instead.
+// PAIR (1-bit fields only): the table is read as 2*D one-bit columns and output
+// column t is the sum of the affine maps of bit columns 2t and 2t+1 - the
+// 2-bit logarithmic codes, whose decoded sum is linear in the two bit-plane
+// sums (see launch_gather_mean_lean_log2).  Dp = number of parameter columns
+// (D, or 2*D with PAIR).
+template <int BITS, int CW, bool WIDE, bool SUM, bool PAIR>
 __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel(
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
+    const int64_t *__restrict__ indices, int64_t V, int D, int Dp, const float *__restrict__ mn,
     const float *__restrict__ sc, const uint8_t *__restrict__ zero_row, float *__restrict__ out,
     int lpr_log2, int chunks, int thr) {
     using W = LeanSwar<BITS, WIDE>;
@@ -93,12 +98,12 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
     constexpr uint32_t FMAX = (1u << W::kF) - 1u;
 
     extern __shared__ uint32_t smem[];
-    float *s_sc = reinterpret_cast<float *>(smem);  // [scale D | min D], D % 4 == 0
-    float *s_mn = s_sc + D;
+    float *s_sc = reinterpret_cast<float *>(smem);  // [scale Dp | min Dp], Dp % 4 == 0
+    float *s_mn = s_sc + Dp;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *meta = reinterpret_cast<float *>(smem + 2 * D) + wave * 64;
-    uint32_t *stage = smem + 2 * D + 64 * kWaves + wave * (64 * R);
-    for (int i = threadIdx.x; i < D; i += kThreads) {
+    float *meta = reinterpret_cast<float *>(smem + 2 * Dp) + wave * 64;
+    uint32_t *stage = smem + 2 * Dp + 64 * kWaves + wave * (64 * R);
+    for (int i = threadIdx.x; i < Dp; i += kThreads) {
         s_sc[i] = sc[i];
         s_mn[i] = mn[i];
     }
@@ -173,6 +178,46 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
 #pragma unroll 2
         for (int m = lane; m < ngran; m += 64) {
             const float md = meta[d];
+            const bool some = md > 0.0f;  // md == 0: empty list, zero row
+            float4 val;
+            if constexpr (PAIR) {
+                // 8 consecutive bit columns -> 4 output columns
+                const int j0 = 8 * f;
+                const int lc = j0 / CPL, jj = j0 % CPL;
+                const int k = jj / CPW, c = jj % CPW;  // c % 8 == 0
+                const uint32_t *sp = stage + (((d << lpr_log2) + lc) * CW + k) * W::kN;
+                uint32_t sum[8];
+                if constexpr (W::kN == 4) {  // codes c..c+3 in field c/4, c+4..c+7 in the next
+                    const uint4 q = *reinterpret_cast<const uint4 *>(sp);
+                    const int sh = W::kF * (c / 4);
+                    sum[0] = (q.x >> sh) & FMAX; sum[1] = (q.y >> sh) & FMAX;
+                    sum[2] = (q.z >> sh) & FMAX; sum[3] = (q.w >> sh) & FMAX;
+                    sum[4] = (q.x >> (sh + W::kF)) & FMAX; sum[5] = (q.y >> (sh + W::kF)) & FMAX;
+                    sum[6] = (q.z >> (sh + W::kF)) & FMAX; sum[7] = (q.w >> (sh + W::kF)) & FMAX;
+                } else {  // kN == 8: codes c..c+7 in registers 0..7, field c/8
+                    const uint4 qa = *reinterpret_cast<const uint4 *>(sp);
+                    const uint4 qb = *reinterpret_cast<const uint4 *>(sp + 4);
+                    const int sh = W::kF * (c / 8);
+                    sum[0] = (qa.x >> sh) & FMAX; sum[1] = (qa.y >> sh) & FMAX;
+                    sum[2] = (qa.z >> sh) & FMAX; sum[3] = (qa.w >> sh) & FMAX;
+                    sum[4] = (qb.x >> sh) & FMAX; sum[5] = (qb.y >> sh) & FMAX;
+                    sum[6] = (qb.z >> sh) & FMAX; sum[7] = (qb.w >> sh) & FMAX;
+                }
+                const float4 a0 = *reinterpret_cast<const float4 *>(s_sc + j0);
+                const float4 a1 = *reinterpret_cast<const float4 *>(s_sc + j0 + 4);
+                const float4 b0 = *reinterpret_cast<const float4 *>(s_mn + j0);
+                const float4 b1 = *reinterpret_cast<const float4 *>(s_mn + j0 + 4);
+                const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; i++)
+                    v[i] = SUM ? fmaf(a[i], (float)sum[i], b[i] * md) : fmaf(a[i], (float)sum[i] * md, b[i]);
+                val.x = some ? v[0] + v[1] : 0.0f;
+                val.y = some ? v[2] + v[3] : 0.0f;
+                val.z = some ? v[4] + v[5] : 0.0f;
+                val.w = some ? v[6] + v[7] : 0.0f;
+            } else {
             const int j0 = 4 * f;
             const int lc = j0 / CPL, jj = j0 % CPL;
             const int k = jj / CPW, c = jj % CPW;
@@ -195,8 +240,6 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
             }
             const float4 a = *reinterpret_cast<const float4 *>(s_sc + j0);
             const float4 b = *reinterpret_cast<const float4 *>(s_mn + j0);
-            const bool some = md > 0.0f;  // md == 0: empty list, zero row
-            float4 val;
             if constexpr (SUM) {
                 val.x = some ? fmaf(a.x, (float)sum[0], b.x * md) : 0.0f;
                 val.y = some ? fmaf(a.y, (float)sum[1], b.y * md) : 0.0f;
@@ -207,6 +250,7 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
                 val.y = some ? fmaf(a.y, (float)sum[1] * md, b.y) : 0.0f;
                 val.z = some ? fmaf(a.z, (float)sum[2] * md, b.z) : 0.0f;
                 val.w = some ? fmaf(a.w, (float)sum[3] * md, b.w) : 0.0f;
+            }
             }
             if (md >= 0.0f) store_stream(&span[m], val);  // md < 0: not this kernel's destination
             d += step_d;
@@ -231,9 +275,10 @@ inline int ilog2(int x) {
     return l;
 }
 
-template <int BITS, bool WIDE>
+template <int BITS, bool WIDE, bool PAIR>
 bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                      const int64_t *indices, int64_t V, float *out, int thr, hipStream_t s) {
+                      const int64_t *indices, int64_t V, float *out, int thr, const float *mn,
+                      const float *sc, hipStream_t s) {
     using W = LeanSwar<BITS, WIDE>;
     const int64_t rb = p->rb;
     int cw = 0;
@@ -256,19 +301,19 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
     const int64_t cap = p->opt_mean_blocks > 0 ? p->opt_mean_blocks : (1 << 16);
     int64_t want = (tiles + kWaves - 1) / kWaves;
     const int blocks = (int)(want < cap ? (want < 1 ? 1 : want) : cap);
-    const int D = (int)p->D;
+    const int D = (int)p->D, Dp = PAIR ? 2 * D : D;
     const int R = cw * W::kN;
-    const size_t shm = sizeof(uint32_t) * ((size_t)2 * D + 64 * kWaves + (size_t)kWaves * 64 * R);
+    const size_t shm = sizeof(uint32_t) * ((size_t)2 * Dp + 64 * kWaves + (size_t)kWaves * 64 * R);
 #define BF_LN(CWV)                                                                               \
     do {                                                                                         \
         if (p->agg_sum)                                                                          \
-            gather_mean_lean_kernel<BITS, CWV, WIDE, true><<<blocks, kThreads, shm, s>>>(        \
-                codes, (uint32_t)rb, indptr, indices, V, D, p->d_min, p->d_scale, p->d_zero,     \
-                out, ilog2(lpr), chunks, thr);                                                   \
+            gather_mean_lean_kernel<BITS, CWV, WIDE, true, PAIR><<<blocks, kThreads, shm, s>>>(  \
+                codes, (uint32_t)rb, indptr, indices, V, D, Dp, mn, sc, p->d_zero, out,          \
+                ilog2(lpr), chunks, thr);                                                        \
         else                                                                                     \
-            gather_mean_lean_kernel<BITS, CWV, WIDE, false><<<blocks, kThreads, shm, s>>>(       \
-                codes, (uint32_t)rb, indptr, indices, V, D, p->d_min, p->d_scale, p->d_zero,     \
-                out, ilog2(lpr), chunks, thr);                                                   \
+            gather_mean_lean_kernel<BITS, CWV, WIDE, false, PAIR><<<blocks, kThreads, shm, s>>>( \
+                codes, (uint32_t)rb, indptr, indices, V, D, Dp, mn, sc, p->d_zero, out,          \
+                ilog2(lpr), chunks, thr);                                                        \
     } while (0)
     switch (cw) {
         case 4: BF_LN(4); break;
@@ -288,16 +333,33 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
 bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, float *out, int thr, bool wide,
                              hipStream_t s) {
+    const float *mn = p->d_min, *sc = p->d_scale;
     switch (p->scheme.bits) {
         case 1:
-            return wide ? launch_lean_bits<1, true>(p, codes, indptr, indices, V, out, thr, s)
-                        : launch_lean_bits<1, false>(p, codes, indptr, indices, V, out, thr, s);
-        case 2: return launch_lean_bits<2, false>(p, codes, indptr, indices, V, out, thr, s);
+            return wide ? launch_lean_bits<1, true, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s)
+                        : launch_lean_bits<1, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
+        case 2: return launch_lean_bits<2, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
         case 4:
-            return wide ? launch_lean_bits<4, true>(p, codes, indptr, indices, V, out, thr, s)
-                        : launch_lean_bits<4, false>(p, codes, indptr, indices, V, out, thr, s);
-        default: return launch_lean_bits<8, false>(p, codes, indptr, indices, V, out, thr, s);
+            return wide ? launch_lean_bits<4, true, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s)
+                        : launch_lean_bits<4, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
+        default: return launch_lean_bits<8, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
     }
+}
+
+// 2-bit logarithmic codes (Sec. 3.1 Eq. (1)/(2) with k = 2): code q = 2*b1 + b0 decodes to
+// -v1, -v0, +v0, +v1, so the decoded sum over a list of n rows is
+//   v0*(S1 - S0) + v1*(S1 + S0 - n),   S0 = sum of b0, S1 = sum of b1,
+// i.e. (v1 - v0)*S0 - n*v1  +  (v0 + v1)*S1: linear in the two bit-plane sums.  The packed row
+// is therefore read as 2*D one-bit columns (bit 2t = b0, bit 2t+1 = b1 of column t) by the
+// 1-bit kernel, with those two affine maps as per-bit-column parameters (p->d_min / d_scale,
+// 2*D entries each), and the epilogue adds each pair.
+bool launch_gather_mean_lean_log2(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                                  const int64_t *indices, int64_t V, float *out, int thr, bool wide,
+                                  hipStream_t s) {
+    return wide ? launch_lean_bits<1, true, true>(p, codes, indptr, indices, V, out, thr, p->d_min,
+                                                  p->d_scale, s)
+                : launch_lean_bits<1, false, true>(p, codes, indptr, indices, V, out, thr, p->d_min,
+                                                   p->d_scale, s);
 }
 
 }  // namespace bf
