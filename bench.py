@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--mean-slots", type=int, default=0)
     ap.add_argument("--mean-blocks", type=int, default=0)
     ap.add_argument("--max-blocks", type=int, default=0)
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
+                    help="library launch option (bifeat_set_option), repeatable")
     ap.add_argument("--graph", action="store_true",
                     help="replay each launch-set's step from a captured HIP graph (whole-step "
                          "timing; per-kernel figures still come from an eager pass)")
@@ -98,6 +100,9 @@ def main():
     for opt in ("mean_slots", "mean_blocks", "max_blocks"):
         if getattr(args, opt):
             q.set_option(opt, getattr(args, opt))
+    for kv in args.opt:
+        name, value = kv.split("=")
+        q.set_option(name, int(value))
     table = DeviceTable(w.spec)
     rb = q.row_bytes
     codes = torch.empty((w.N, rb), dtype=torch.uint8, device=dev)

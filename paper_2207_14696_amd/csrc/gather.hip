@@ -220,6 +220,63 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_vq_kernel(
     }
 }
 
+// Tile form for vector codes whose codebooks stay in L2 (width % 4 == 0, output
+// rows 16-byte aligned): as gather_dequant_tile_kernel, a wavefront fetches the
+// packed rows of RT = 64/c16 consecutive requests with one 16-byte load per lane
+// and parks them in LDS; granule m of the tile's contiguous output span is then
+// one 16-byte read of a codebook entry - kVqInFlight of them in flight per lane,
+// the lanes of a part reading one contiguous entry - and one streaming store.
+constexpr int kVqInFlight = 8;
+
+template <int CB>
+__global__ __launch_bounds__(kThreads) void gather_dequant_vq_tile_kernel(
+    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int D,
+    int w, int len, const float *__restrict__ cb, float *__restrict__ out) {
+    __shared__ uint4 s_raw[kThreads];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4 *raw = s_raw + wave * 64;
+    const int RT = 64 / c16;
+    const int r = lane / c16, c = lane - r * c16;
+    const int nf4 = D >> 2;
+    const int step_d = 64 / nf4, step_f = 64 % nf4;
+    const int lane_d = lane / nf4, lane_f = lane % nf4;
+    const int rb = c16 * 16;
+    const int64_t tiles = (M + RT - 1) / RT;
+    const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+    constexpr int U = kVqInFlight;
+    for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < tiles; tile += n_waves) {
+        const int64_t row0 = tile * RT;
+        const int nrow = (int)min((int64_t)RT, M - row0);
+        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * c16 + c];  // lane = r*c16 + c
+        wave_sync();
+        float4 *span = reinterpret_cast<float4 *>(out + row0 * D);
+        const int ngran = nrow * nf4;
+        int d = lane_d, f = lane_f;
+        for (int m0 = lane; m0 < ngran; m0 += 64 * U) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                // granules past the tile's end re-read its last granule's entry (in bounds)
+                const bool in = m0 + 64 * u < ngran;
+                const int dd = in ? d : nrow - 1, ff = in ? f : nf4 - 1;
+                const int col = 4 * ff, part = col / w, dim = col - part * w;
+                const int q = vq_index<CB>(reinterpret_cast<const uint8_t *>(raw) + dd * rb, part);
+                v[u] = *reinterpret_cast<const float4 *>(cb + ((int64_t)part * len + q) * w + dim);
+                d += step_d;
+                f += step_f;
+                if (f >= nf4) {
+                    f -= nf4;
+                    d++;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                if (m0 + 64 * u < ngran) store_stream(&span[m0 + 64 * u], v[u]);
+        }
+        wave_sync();  // raw is rewritten by the next tile
+    }
+}
+
 hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                  int64_t M, float *out, hipStream_t s) {
     const int D = (int)p->D;
@@ -232,6 +289,19 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
         if (p->opt_vq_sliced && launch_gather_dequant_vq_sliced(p, codes, idx, M, out, s))
             return hipGetLastError();
         const int w = p->scheme.vq_width;
+        const int c16v = (int)(p->rb / 16);
+        if (w % 4 == 0 && vec && c16v <= 64 && !p->opt_dequant_flat) {
+            const int RT = 64 / c16v;
+            const int64_t tiles = (M + RT - 1) / RT;
+            const int64_t cap = p->opt_max_blocks > 0 ? p->opt_max_blocks : (1 << 16);
+            const int64_t want = (tiles + 3) / 4;
+            const int tb = (int)(want < cap ? want : cap);
+            if (p->cbytes == 1)
+                gather_dequant_vq_tile_kernel<1><<<tb, kThreads, 0, s>>>((const uint4 *)codes, c16v, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
+            else
+                gather_dequant_vq_tile_kernel<2><<<tb, kThreads, 0, s>>>((const uint4 *)codes, c16v, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
+            return hipGetLastError();
+        }
 #define BF_GV(W4, CB) \
     gather_dequant_vq_kernel<W4, CB><<<blocks, kThreads, 0, s>>>(codes, p->rb, idx, M, D, w, p->scheme.vq_length, p->d_cb, out)
         if (w % 4 == 0 && vec) {

@@ -182,7 +182,10 @@ def test_gather_codes_and_dequant(bf, torch, kind, bits, D):
         q.set_option("dequant_flat", 0)
     else:                       # codebooks from L2 instead of LDS-resident slices
         q.set_option("vq_sliced", 0)
-        assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant L2")
+        assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant L2 tiles")
+        q.set_option("dequant_flat", 1)
+        assert_close(q.gather_dequant(dcodes, didx).cpu().numpy(), want, s, "gather_dequant L2 flat")
+        q.set_option("dequant_flat", 0)
         q.set_option("vq_sliced", 1)
     # empty request
     empty = torch.empty(0, dtype=torch.int64, device="cuda")
