@@ -10,7 +10,13 @@ L = 1 is one 1,024-seed minibatch per launch.  The one-time fit + quantize pass
 that builds the table runs before the timed region and is reported separately
 under "preprocess".
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line on stdout: metric / value / unit (whole-step rows per
+second), ms_per_step, config (the workload), "roofline" for the kernel with the
+most time in the step (algorithmic bytes over its HIP-event duration against the
+8 TB/s HBM peak; "traffic" = counter-measured bytes per launch when a profile
+summary for this workload is present), "kernels" (the same for every call of
+the step), "cpu_baseline" (the CPU oracle on the host cores, a bounded sample)
+and "preprocess".  Progress lines go to stderr.
 """
 from __future__ import annotations
 

@@ -21,6 +21,10 @@
  *     errors are detected before any GPU call is made.  bifeat_strerror()
  *     gives a description (for BIFEAT_EHIP: the HIP error text of the last
  *     failure on the calling thread).
+ *   - Calls on one bifeat_params handle must not overlap in time (they share
+ *     its fit state and, for vector codes, its scratch buffer: the transposed
+ *     codes of the rows a call requests, grown with hipMalloc when a larger
+ *     request arrives).  Different handles are independent.
  *   - Row indices must satisfy 0 <= idx < N and indptr must be non-decreasing;
  *     this is the caller's contract and is not checked on the GPU.
  *   - Packed layout (the paper fixes none; Appendix C only advises against
