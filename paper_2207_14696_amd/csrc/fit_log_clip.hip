@@ -44,8 +44,11 @@ __global__ __launch_bounds__(kThreads) void log_hist_kernel(const T *__restrict_
         }
     };
     if constexpr (VEC) {
-        const int64_t n4 = n >> 2, stride = (int64_t)gridDim.x * kThreads;
-        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
+        // every workgroup streams one contiguous piece of the chunk
+        const int64_t n4 = n >> 2, per_block = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t i0 = (int64_t)blockIdx.x * per_block, i1 = min(n4, i0 + per_block);
+#pragma unroll 2
+        for (int64_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
             const float4 v = load4(x + 4 * i);
             take(v.x);
             take(v.y);

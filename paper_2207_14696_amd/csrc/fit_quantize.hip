@@ -93,18 +93,35 @@ __global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restric
 
 // smallest nonzero and largest finite magnitude of a chunk (log scheme);
 // positive floats order like their bit patterns
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(kThreads) void fit_log_kernel(const T *__restrict__ x, int64_t n,
                                                           int32_t *state) {
     uint32_t mmin = 0x7F800000u, mmax = 0u;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-#pragma unroll 4
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
-        uint32_t m = __float_as_uint(fabsf(load1(x + i)));
+    auto take = [&](float v) {
+        const uint32_t m = __float_as_uint(fabsf(v));
         if (m < 0x7F800000u) {  // finite
             if (m != 0u && m < mmin) mmin = m;
             if (m > mmax) mmax = m;
         }
+    };
+    if constexpr (VEC) {
+        // every workgroup streams one contiguous piece of the chunk, 4 elements per lane
+        const int64_t n4 = n >> 2, per_block = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t i0 = (int64_t)blockIdx.x * per_block, i1 = min(n4, i0 + per_block);
+#pragma unroll 4
+        for (int64_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
+            const float4 v = load4(x + 4 * i);
+            take(v.x);
+            take(v.y);
+            take(v.z);
+            take(v.w);
+        }
+        if (blockIdx.x == 0 && threadIdx.x < (n & 3)) take(load1(x + 4 * n4 + threadIdx.x));
+    } else {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+#pragma unroll 4
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
+            take(load1(x + i));
     }
     for (int o = 32; o > 0; o >>= 1) {
         mmin = min(mmin, (uint32_t)__shfl_xor((int)mmin, o));
@@ -121,11 +138,15 @@ hipError_t launch_fit_update(bifeat_params *p, const void *chunk, int dtype, int
     const int D = (int)p->D;
     if (p->scheme.kind == BIFEAT_SQ_LOG) {
         int64_t n = rows * D;
-        int blocks = blocks_for((n + 3) / 4);
-        if (dtype == BIFEAT_F32)
-            fit_log_kernel<float><<<blocks, kThreads, 0, s>>>((const float *)chunk, n, p->d_fit);
-        else
-            fit_log_kernel<__half><<<blocks, kThreads, 0, s>>>((const __half *)chunk, n, p->d_fit);
+        int blocks = blocks_for((n + 31) / 32);
+        const bool vec4 = (uintptr_t)chunk % (dtype == BIFEAT_F32 ? 16 : 8) == 0;
+        if (dtype == BIFEAT_F32) {
+            if (vec4) fit_log_kernel<float, true><<<blocks, kThreads, 0, s>>>((const float *)chunk, n, p->d_fit);
+            else fit_log_kernel<float, false><<<blocks, kThreads, 0, s>>>((const float *)chunk, n, p->d_fit);
+        } else {
+            if (vec4) fit_log_kernel<__half, true><<<blocks, kThreads, 0, s>>>((const __half *)chunk, n, p->d_fit);
+            else fit_log_kernel<__half, false><<<blocks, kThreads, 0, s>>>((const __half *)chunk, n, p->d_fit);
+        }
         return hipGetLastError();
     }
     const size_t esz = dtype == BIFEAT_F32 ? 4 : 2;
