@@ -97,14 +97,13 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
         float acc[4];
 #pragma unroll
         for (int k = 0; k < 4; k++) acc[k] = (float)(total[k] * inv_nd);
-        const float inv_n = 1.0f;
         float *dst = out + v * D + col0;
         if constexpr (VEC) {
-            store_stream(reinterpret_cast<float4 *>(dst), make_float4(acc[0] * inv_n, acc[1] * inv_n, acc[2] * inv_n, acc[3] * inv_n));
+            store_stream(reinterpret_cast<float4 *>(dst), make_float4(acc[0], acc[1], acc[2], acc[3]));
         } else {
 #pragma unroll
             for (int k = 0; k < 4; k++)
-                if (col0 + k < D) dst[k] = acc[k] * inv_n;
+                if (col0 + k < D) dst[k] = acc[k];
         }
     }
 }
