@@ -25,8 +25,11 @@
  *     its fit state and, for vector codes, its scratch buffer: the transposed
  *     codes of the rows a call requests, grown with hipMalloc when a larger
  *     request arrives).  Different handles are independent.
- *   - Row indices must satisfy 0 <= idx < N and indptr must be non-decreasing;
- *     this is the caller's contract and is not checked on the GPU.
+ *   - Row indices must satisfy 0 <= idx < N, indptr must be non-decreasing with
+ *     indptr[0] = 0 and indptr[V] = E; this is the caller's contract and is not
+ *     checked on the GPU - unless option "validate" = 1 is set: every gather
+ *     call then first checks it with a small kernel, synchronises `stream`,
+ *     and returns BIFEAT_EINVAL without launching the gather when it is broken.
  *   - Packed layout (the paper fixes none; Appendix C only advises against
  *     elaborate bit packing): row-major; scalar codes: column j's `bits`-bit
  *     code at bit (j*bits) mod 8 of byte floor(j*bits/8), column 0 in the
@@ -217,7 +220,9 @@ const char *bifeat_strerror(int status);
  * "mean_max_degree" = d is the caller's promise that no neighbour list of the
  * following bifeat_gather_mean calls is longer than d (0 = unknown; a sampler
  * knows its fan-out), which lets the library skip the pass that looks for
- * longer lists; "vq_iters" = Lloyd rounds per training chunk.
+ * longer lists (a list that breaks the promise leaves its output row unwritten);
+ * "vq_iters" = Lloyd rounds per training chunk (1..64); "validate" = 1 checks
+ * the index contract of every gather call on the GPU first (see above).
  * Unknown names return BIFEAT_EINVAL. */
 int bifeat_set_option(bifeat_params *p, const char *name, int value);
 

@@ -54,7 +54,7 @@ int ensure_device(bifeat_params *p) {
     nfloat = (nfloat + 3) / 4 * 4;
     nfit = (nfit + 3) / 4 * 4;
     void *blk = nullptr;
-    const size_t bytes = sizeof(float) * nfloat + sizeof(int32_t) * nfit + 64;
+    const size_t bytes = sizeof(float) * nfloat + sizeof(int32_t) * nfit + 128;  // zero row + check flag
     BF_HIP(hipMalloc(&blk, bytes));
     BF_HIP(hipMemset(blk, 0, bytes));
     p->d_block = (float *)blk;
@@ -286,6 +286,7 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     if (!strcmp(name, "mean_slots")) p->opt_mean_slots = value;
     else if (!strcmp(name, "mean_blocks")) p->opt_mean_blocks = value;
     else if (!strcmp(name, "mean_generic")) p->opt_mean_generic = value;
+    else if (!strcmp(name, "validate")) p->opt_validate = value;
     else if (!strcmp(name, "max_blocks")) p->opt_max_blocks = value;
     else if (!strcmp(name, "dequant_flat")) p->opt_dequant_flat = value;
     else if (!strcmp(name, "mean_lean")) p->opt_mean_lean = value;
@@ -504,12 +505,29 @@ int bifeat_quantize(bifeat_params *p, const void *chunk, int32_t dtype, int64_t 
     return BIFEAT_OK;
 }
 
+namespace {
+// option "validate": the caller's index contract checked on the GPU before the gather
+int check_inputs(bifeat_params *p, const int64_t *idx, int64_t M, int64_t N, const int64_t *indptr,
+                 int64_t V, int64_t E, hipStream_t s) {
+    if (!p->opt_validate) return BIFEAT_OK;
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    int32_t *d_bad = reinterpret_cast<int32_t *>(p->d_zero + 64);  // word after the zero row
+    bf::launch_validate(idx, M, N, indptr, V, E, d_bad, s);
+    int32_t bad = 0;
+    BF_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s));
+    BF_HIP(hipStreamSynchronize(s));
+    return bad ? BIFEAT_EINVAL : BIFEAT_OK;
+}
+}  // namespace
+
 int bifeat_gather_codes(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *idx,
                         int64_t M, uint8_t *out, void *stream) {
     if (!p || M < 0 || N < 0) return BIFEAT_EINVAL;
     if (M > 0 && (!codes || !idx || !out || N == 0)) return BIFEAT_EINVAL;
     if ((uintptr_t)codes % 16 || (uintptr_t)out % 16) return BIFEAT_EINVAL;
     if (M == 0) return BIFEAT_OK;
+    if (int rc = check_inputs(p, idx, M, N, nullptr, 0, 0, (hipStream_t)stream)) return rc;
     BF_HIP(bf::launch_gather_codes(p, codes, idx, M, out, (hipStream_t)stream));
     return BIFEAT_OK;
 }
@@ -521,6 +539,7 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
     if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
     if (!p->fitted) return BIFEAT_ENOTFIT;
     if (M == 0) return BIFEAT_OK;
+    if (int rc = check_inputs(p, idx, M, N, nullptr, 0, 0, (hipStream_t)stream)) return rc;
     BF_HIP(bf::launch_gather_dequant(p, codes, idx, M, out, (hipStream_t)stream));
     return BIFEAT_OK;
 }
@@ -532,6 +551,7 @@ int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const 
     if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
     if (!p->fitted) return BIFEAT_ENOTFIT;
     if (V == 0) return BIFEAT_OK;
+    if (int rc = check_inputs(p, indices, E, N, indptr, V, E, (hipStream_t)stream)) return rc;
     BF_HIP(bf::launch_gather_mean(p, codes, indptr, indices, V, E, out, (hipStream_t)stream));
     return BIFEAT_OK;
 }

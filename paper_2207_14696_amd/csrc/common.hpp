@@ -65,6 +65,7 @@ struct bifeat_params {
     int opt_vq_sliced = 1;        // 0: vector codes decode from L2 instead of LDS-resident slices
     int opt_dequant_flat = 0;  // 1: gather_dequant without the LDS-staged tile kernel
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
+    int opt_validate = 0;      // 1: check indices / list bounds on the GPU before every gather (synchronises)
 };
 
 namespace bf {
@@ -106,6 +107,10 @@ void launch_vq_rnorm(bifeat_params *p, hipStream_t s);
 template <typename T>
 void launch_vq_assign(bifeat_params *p, const T *x, int64_t rows, uint8_t *codes_row0, int64_t rb,
                       hipStream_t s);
+// counts violations of 0 <= idx[i] < N (and, with indptr, of indptr[0] == 0, indptr
+// non-decreasing, indptr[V] == E) into *d_bad (zeroed first)
+void launch_validate(const int64_t *idx, int64_t M, int64_t N, const int64_t *indptr, int64_t V,
+                     int64_t E, int32_t *d_bad, hipStream_t s);
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                      int64_t M, float *out, hipStream_t s);
 bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,

@@ -518,3 +518,36 @@ def test_calls_replay_from_a_captured_graph(bf, torch):
         assert torch.equal(out_a, eager_a) and torch.equal(out_b, eager_b), f"replay {rep}"
         # eager work between replays
         assert torch.equal(q.gather_mean(dcodes, dptr, dind), eager_b)
+
+
+def test_validate_option_rejects_broken_index_contracts(bf, torch):
+    # option "validate": indices and list bounds are checked by a small kernel and a broken
+    # contract is refused before any gather kernel is launched
+    q, s, codes, dcodes = _tables(bf, torch, "uniform", 4, 100)
+    N = codes.shape[0]
+    q.set_option("validate", 1)
+    good = torch.tensor([0, N - 1, 5], dtype=torch.int64, device="cuda")
+    assert_close(q.gather_dequant(dcodes, good).cpu().numpy(),
+                 orc.gather_dequant(s, codes, good.cpu().numpy()), s)
+    out = torch.full((3, 100), 7.0, device="cuda")
+    for bad in ([0, N, 5], [0, -1, 5]):
+        with pytest.raises(bf.BifeatError) as e:
+            q.gather_dequant(dcodes, torch.tensor(bad, dtype=torch.int64, device="cuda"), out)
+        assert e.value.status == -1
+        with pytest.raises(bf.BifeatError):
+            q.gather_codes(dcodes, torch.tensor(bad, dtype=torch.int64, device="cuda"))
+    assert bool((out == 7.0).all())                  # nothing was written
+    ptr = torch.tensor([0, 2, 3], dtype=torch.int64, device="cuda")
+    ind = torch.tensor([1, 2, 3], dtype=torch.int64, device="cuda")
+    want = orc.gather_mean(s, codes, ptr.cpu().numpy(), ind.cpu().numpy())
+    assert_close(q.gather_mean(dcodes, ptr, ind).cpu().numpy(), want, s)
+    broken = [(torch.tensor([0, 3, 2], dtype=torch.int64, device="cuda"), ind),      # decreasing
+              (torch.tensor([1, 2, 3], dtype=torch.int64, device="cuda"), ind),      # indptr[0] != 0
+              (torch.tensor([0, 2, 2], dtype=torch.int64, device="cuda"), ind),      # indptr[V] != E
+              (ptr, torch.tensor([1, N + 4, 3], dtype=torch.int64, device="cuda"))]  # index out of range
+    for p_, i_ in broken:
+        with pytest.raises(bf.BifeatError):
+            q.gather_mean(dcodes, p_, i_)
+        with pytest.raises(bf.BifeatError):
+            q.gather_sum(dcodes, p_, i_)
+    q.set_option("validate", 0)
