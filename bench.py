@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--max-blocks", type=int, default=0)
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
                     help="library launch option (bifeat_set_option), repeatable")
+    ap.add_argument("--no-degree-hint", action="store_true",
+                    help="do not tell the library the sampler's fan-out (it then also scans for longer lists)")
     ap.add_argument("--graph", action="store_true",
                     help="replay each launch-set's step from a captured HIP graph (whole-step "
                          "timing; per-kernel figures still come from an eager pass)")
@@ -202,7 +204,7 @@ def main():
             if timed is not None and h == outer:
                 timed[2].record()
             # the sampler's contract: no list of hop h is longer than its fan-out
-            q.set_option("mean_max_degree", w.fanouts[h])
+            q.set_option("mean_max_degree", 0 if args.no_degree_hint else w.fanouts[h])
             aggregate(codes, dp, di, out_h[h][:dp.shape[0] - 1])
         if timed is not None:
             timed[3].record()
