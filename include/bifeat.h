@@ -25,6 +25,11 @@
  *     its fit state and, for vector codes, its scratch buffer: the transposed
  *     codes of the rows a call requests, grown with hipMalloc when a larger
  *     request arrives).  Different handles are independent.
+ *   - The per-iteration calls (gather_codes / gather_dequant / gather_mean /
+ *     gather_sum) only enqueue kernels: no memset, no synchronisation, and no
+ *     allocation except that growth of the vector-code scratch.  They can be
+ *     captured into a HIP graph once a call at least as large has run outside
+ *     the capture (and with option "validate" off).
  *   - Row indices must satisfy 0 <= idx < N, indptr must be non-decreasing with
  *     indptr[0] = 0 and indptr[V] = E; this is the caller's contract and is not
  *     checked on the GPU - unless option "validate" = 1 is set: every gather
