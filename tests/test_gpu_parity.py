@@ -493,11 +493,12 @@ def test_mean_with_self_loops_on_the_gpu(bf, torch):
     assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, ptr, idx), s)
 
 
-def test_calls_replay_from_a_captured_graph(bf, torch):
-    # the per-iteration calls enqueue kernels only (no allocation, no memset, no
-    # synchronisation), so a step can be captured once and replayed; every replay must
-    # reproduce the eager result, with eager work in between
-    q, s, codes, dcodes = _tables(bf, torch, "uniform", 4, 100)
+@pytest.mark.parametrize("kind,bits,D", [("uniform", 4, 100), ("vq", 8, 64), ("log", 2, 100)])
+def test_calls_replay_from_a_captured_graph(bf, torch, kind, bits, D):
+    # the per-iteration calls enqueue kernels only (no memset, no synchronisation, no
+    # allocation once the vector-code scratch has its size), so a step can be captured once
+    # and replayed; every replay must reproduce the eager result, with eager work in between
+    q, s, codes, dcodes = _tables(bf, torch, kind, bits, D)
     rng = np.random.default_rng(12)
     idx = torch.from_numpy(rng.integers(0, codes.shape[0], 1500).astype(np.int64)).cuda()
     indptr, indices = random_csr(400, codes.shape[0], 10, rng, hubs=(120,))
