@@ -426,11 +426,12 @@ bool allow_lds(Kern kern, size_t bytes) {
 
 // workgroups: two fit a CU (LDS, registers); a few per slot so that the last
 // ones to finish leave little of the chip idle, each loading its slice once
-int sliced_grid(const bifeat_params *p, int64_t wave_tiles, int64_t dflt) {
+// (workgroup b serves slice b % NS: never fewer workgroups than slices)
+int sliced_grid(const bifeat_params *p, int64_t wave_tiles, int64_t dflt, int NS) {
     int64_t blocks = (wave_tiles + (kVqThreads / 64) - 1) / (kVqThreads / 64);
     const int64_t cap = p->opt_max_blocks > 0 ? p->opt_max_blocks : dflt;
     if (blocks > cap) blocks = cap;
-    if (blocks < 1) blocks = 1;
+    if (blocks < NS) blocks = NS;
     return (int)blocks;
 }
 
@@ -452,7 +453,7 @@ bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, con
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int rpw = 64 / g.LPS;
     const int64_t tiles = (M + rpw - 1) / rpw;
-    const int grid = sliced_grid(p, (tiles + BF_VQ_U - 1) / BF_VQ_U * g.NS, 2048);
+    const int grid = sliced_grid(p, (tiles + BF_VQ_U - 1) / BF_VQ_U * g.NS, 2048, g.NS);
     gather_dequant_vq_sliced_kernel<<<grid, kVqThreads, g.lds, s>>>(
         (const uint32_t *)p->d_scratch, M, MS, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS),
         p->cbytes, p->d_cb, out);
@@ -480,7 +481,7 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const 
     if (E > 0) launch_planes(p, codes, indices, E, s);
     const int lps = g.LPS * 4 / cpl, rpw = 64 / lps;
     const int64_t tiles = (V + rpw - 1) / rpw;
-    const int grid = sliced_grid(p, tiles * g.NS, 1024);
+    const int grid = sliced_grid(p, tiles * g.NS, 1024, g.NS);
 #define BF_VQL(KERNEL)                                                                       \
     KERNEL<<<grid, kVqThreads, g.lds, s>>>((const uint32_t *)p->d_scratch, MS, indptr, V,     \
                                            (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(lps),   \

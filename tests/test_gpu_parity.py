@@ -552,3 +552,16 @@ def test_validate_option_rejects_broken_index_contracts(bf, torch):
         with pytest.raises(bf.BifeatError):
             q.gather_sum(dcodes, p_, i_)
     q.set_option("validate", 0)
+
+
+@pytest.mark.parametrize("V", [1, 3, 17])
+def test_small_requests_reach_every_codebook_slice(bf, torch, V):
+    # fewer destinations / rows than column slices: every slice still gets a workgroup
+    q, s, codes, dcodes = _tables(bf, torch, "vq", 8, 96, w=4, length=256)   # 24 parts, several slices
+    rng = np.random.default_rng(V)
+    indptr, indices = random_csr(V + 1, codes.shape[0], 6, rng)
+    got = q.gather_mean(dcodes, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda())
+    assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, indptr, indices), s)
+    idx = rng.integers(0, codes.shape[0], V).astype(np.int64)
+    assert_close(q.gather_dequant(dcodes, torch.from_numpy(idx).cuda()).cpu().numpy(),
+                 orc.gather_dequant(s, codes, idx), s)
