@@ -87,3 +87,72 @@ def test_random_configuration(bf, torch, case):
     n = np.maximum(np.diff(indptr), 1)[:, None]
     bound = REL_TOL * np.maximum(np.abs(want), column_magnitude(s).astype(np.float64)[None, :] * n)
     assert not (np.abs(got - want) > bound).any(), f"sum {c}"
+
+
+def _build(bf, torch, c, N, seed):
+    """(quantizer, oracle scheme, oracle codes, device codes) for configuration c."""
+    D = c["D"]
+    spec = FeatureSpec(N, D, seed, c["dtype"])
+    x = feature_chunk(spec, 0, N).astype(np.float32)
+    if c["kind"] == "uniform":
+        mn, mx = orc.fit_minmax(x)
+        scale, inv = orc.uniform_params(mn, mx, c["bits"])
+        s = orc.Scheme.uniform(mn, scale, c["bits"])
+        codes = orc.pack(orc.uniform_encode(x, c["bits"], mn, inv), c["bits"])
+        q = bf.Quantizer(scheme_of("uniform", c["bits"]), D)
+        q.params_set_uniform(mn, mx)
+    elif c["kind"] == "log":
+        e = orc.log_range_clipped(x, 0.02)
+        T, V = orc.log_tables(*e, c["bits"])
+        s = orc.Scheme.log(D, V, c["bits"])
+        codes = orc.pack(orc.log_encode(x, c["bits"], T), c["bits"])
+        q = bf.Quantizer(scheme_of("log", c["bits"]), D)
+        q.params_set_log(*e)
+    else:
+        w, length, metric = c["w"], min(c["length"], 256), c["metric"]
+        cb, _ = orc.vq_train(x[:max(length, 300)], w, length, iters=1, metric=metric)
+        s = orc.Scheme.vq(D, cb)
+        codes = orc.pack(orc.vq_assign(x, w, cb, metric=metric), orc.vq_code_bits(length))
+        q = bf.Quantizer(scheme_of("vq", 8, w, length, metric), D)
+        q.params_set_codebooks(cb)
+    return q, s, codes, torch.from_numpy(codes).cuda()
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_small_requests_and_fanout_bounds(bf, torch, case):
+    # tiny requests (one row, one destination, a few tiles and a ragged tail) and sampled
+    # blocks whose fan-out the caller states, for random configurations
+    rng = np.random.default_rng(5000 + case)
+    c = _draw(rng)
+    if c["D"] > 600:
+        c["D"] = int(rng.choice([8, 96, 128]))
+    N = int(rng.integers(300, 800))
+    q, s, codes, dcodes = _build(bf, torch, c, N, 300 + case)
+    for M in (1, 2, 63, 65, int(rng.integers(3, 300))):
+        idx = rng.integers(0, N, M).astype(np.int64)
+        got = q.gather_dequant(dcodes, torch.from_numpy(idx).cuda()).cpu().numpy()
+        assert_close(got, orc.gather_dequant(s, codes, idx), s, f"dequant M={M} {c}")
+    for V in (1, 2, 64, 65, int(rng.integers(3, 400))):
+        f = int(rng.choice([1, 2, 5, 10, 15, 16, 17, 25, 32, 33, 64]))
+        deg = rng.integers(0, f + 1, V)
+        deg[rng.integers(0, V)] = f                   # the bound is attained
+        indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+        indices = rng.integers(0, N, int(indptr[-1])).astype(np.int64)
+        dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+        q.set_option("mean_max_degree", f)
+        got = q.gather_mean(dcodes, dptr, dind).cpu().numpy()
+        gsum = q.gather_sum(dcodes, dptr, dind).cpu().numpy().astype(np.float64)
+        q.set_option("mean_max_degree", 0)
+        assert_close(got, orc.gather_mean(s, codes, indptr, indices), s, f"mean V={V} f={f} {c}")
+        want = orc.gather_sum(s, codes, indptr, indices).astype(np.float64)
+        n = np.maximum(deg, 1)[:, None]
+        bound = REL_TOL * np.maximum(np.abs(want), column_magnitude(s).astype(np.float64)[None, :] * n)
+        assert not (np.abs(gsum - want) > bound).any(), f"sum V={V} f={f} {c}"
+    # every list empty, with and without the bound
+    V = int(rng.integers(1, 70))
+    zptr = torch.zeros(V + 1, dtype=torch.int64, device="cuda")
+    zind = torch.empty(0, dtype=torch.int64, device="cuda")
+    for hint in (0, 5):
+        q.set_option("mean_max_degree", hint)
+        assert not q.gather_mean(dcodes, zptr, zind).any()
+    q.set_option("mean_max_degree", 0)
