@@ -156,3 +156,58 @@ def test_small_requests_and_fanout_bounds(bf, torch, case):
         q.set_option("mean_max_degree", hint)
         assert not q.gather_mean(dcodes, zptr, zind).any()
     q.set_option("mean_max_degree", 0)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_fits(bf, torch, case):
+    # streaming fits with random chunking, special values in the table
+    rng = np.random.default_rng(9000 + case)
+    D = int(rng.choice([1, 5, 32, 100, 257, 768]))
+    N = int(rng.integers(200, 3000))
+    dtype = str(rng.choice(["f32", "f16"]))
+    spec = FeatureSpec(N, D, 900 + case, dtype)
+    x = feature_chunk(spec, 0, N).astype(np.float32)
+    # sprinkle zeros, NaNs and infinities (NaNs are skipped by the fits; an infinity is a
+    # legitimate extreme of a column for the uniform range and ignored by the log range)
+    flat = x.reshape(-1)
+    k = max(1, flat.size // 200)
+    flat[rng.integers(0, flat.size, k)] = 0.0
+    flat[rng.integers(0, flat.size, max(1, k // 4))] = np.nan
+    with_inf = case % 3 == 0
+    if with_inf:
+        flat[rng.integers(0, flat.size, 2)] = np.inf
+    tx = torch.from_numpy(x).cuda()
+    if dtype == "f16":
+        tx = tx.half()
+        x = tx.float().cpu().numpy()
+    cuts = np.sort(rng.choice(np.arange(1, N), size=min(N - 1, int(rng.integers(0, 6))), replace=False))
+    bounds = [0, *cuts.tolist(), N]
+
+    def stream(q):
+        for a, b in zip(bounds[:-1], bounds[1:]):
+            q.fit_update(tx[a:b])
+
+    bits = int(rng.choice([1, 2, 4, 8]))
+    q = bf.Quantizer(scheme_of("uniform", bits), D)
+    q.fit_reset()
+    stream(q)
+    assert q.fit_finalize() is False
+    mn, mx, scale, inv = q.params_get_uniform()
+    omn, omx = orc.fit_minmax(x)
+    assert np.array_equal(mn, omn) and np.array_equal(mx, omx)
+    if not with_inf:
+        osc, oinv = orc.uniform_params(omn, omx, bits)
+        assert np.array_equal(scale, osc) and np.array_equal(inv, oinv)
+
+    frac = float(rng.choice([0.0, 0.001, 0.01, 0.1, 0.3]))
+    ql = bf.Quantizer(scheme_of("log", bits), D)
+    ql.fit_set_log_clip(frac)
+    ql.fit_reset()
+    again, passes = True, 0
+    while again:
+        stream(ql)
+        again = ql.fit_finalize()
+        passes += 1
+    assert passes == (3 if frac > 0 else 1)
+    want = orc.log_range_clipped(x, frac) if frac > 0 else orc.log_range(orc.log_fit(x))
+    assert ql.params_get_log()[:2] == want
