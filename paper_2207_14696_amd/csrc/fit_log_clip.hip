@@ -18,14 +18,17 @@ namespace bf {
 namespace {
 
 constexpr int kCopies = 4;
+// 16 waves share one 64 KB set of histograms, two such workgroups per CU: enough
+// waves in flight to keep the read stream going
+constexpr int kHistThreads = 1024;
 
 template <typename T, bool VEC>
-__global__ __launch_bounds__(kThreads) void log_hist_kernel(const T *__restrict__ x, int64_t n,
+__global__ __launch_bounds__(kHistThreads) void log_hist_kernel(const T *__restrict__ x, int64_t n,
                                                            int pass, uint32_t prefix_lo,
                                                            uint32_t prefix_hi,
                                                            unsigned long long *__restrict__ hist) {
     __shared__ uint32_t s_h[kCopies][2][kLogHistBins];
-    for (int i = threadIdx.x; i < kCopies * 2 * kLogHistBins; i += kThreads) (&s_h[0][0][0])[i] = 0u;
+    for (int i = threadIdx.x; i < kCopies * 2 * kLogHistBins; i += kHistThreads) (&s_h[0][0][0])[i] = 0u;
     __syncthreads();
     uint32_t(*mine)[kLogHistBins] = s_h[threadIdx.x & (kCopies - 1)];
     auto take = [&](float v) {
@@ -48,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void log_hist_kernel(const T *__restrict_
         const int64_t n4 = n >> 2, per_block = (n4 + gridDim.x - 1) / gridDim.x;
         const int64_t i0 = (int64_t)blockIdx.x * per_block, i1 = min(n4, i0 + per_block);
 #pragma unroll 2
-        for (int64_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
+        for (int64_t i = i0 + threadIdx.x; i < i1; i += kHistThreads) {
             const float4 v = load4(x + 4 * i);
             take(v.x);
             take(v.y);
@@ -57,12 +60,12 @@ __global__ __launch_bounds__(kThreads) void log_hist_kernel(const T *__restrict_
         }
         if (blockIdx.x == 0 && threadIdx.x < (n & 3)) take(load1(x + 4 * n4 + threadIdx.x));
     } else {
-        const int64_t stride = (int64_t)gridDim.x * kThreads;
-        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
+        const int64_t stride = (int64_t)gridDim.x * kHistThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kHistThreads + threadIdx.x; i < n; i += stride)
             take(load1(x + i));
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < 2 * kLogHistBins; i += kThreads) {
+    for (int i = threadIdx.x; i < 2 * kLogHistBins; i += kHistThreads) {
         uint32_t c = 0;
 #pragma unroll
         for (int k = 0; k < kCopies; k++) c += (&s_h[k][0][0])[i];
@@ -85,9 +88,10 @@ hipError_t launch_log_hist_update(bifeat_params *p, const void *chunk, int dtype
     const int64_t n = rows * p->D;
     const size_t esz = dtype == BIFEAT_F32 ? 4 : 2;
     const bool vec = (uintptr_t)chunk % (4 * esz) == 0;
-    const int blocks = blocks_for((n + 31) / 32, 1024);  // 2 workgroups per CU at most (LDS), a few rounds
+    int64_t want = (n / 32 + kHistThreads - 1) / kHistThreads;
+    const int blocks = (int)(want < 1 ? 1 : (want > 1024 ? 1024 : want));  // 2 workgroups per CU (LDS), two rounds
 #define BF_LH(T, V)                                                                          \
-    log_hist_kernel<T, V><<<blocks, kThreads, 0, s>>>((const T *)chunk, n, p->fit_pass,     \
+    log_hist_kernel<T, V><<<blocks, kHistThreads, 0, s>>>((const T *)chunk, n, p->fit_pass,     \
                                                       p->clip_prefix[0], p->clip_prefix[1], p->d_hist)
     if (dtype == BIFEAT_F32) {
         if (vec) BF_LH(float, true); else BF_LH(float, false);
