@@ -43,11 +43,17 @@ __global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restric
         }
         __syncthreads();
     }
+    // A workgroup streams one contiguous piece of the chunk: kThreads/G whole rows per
+    // iteration when a row's G column groups fit a workgroup (a wave's lanes then read
+    // consecutive 16 bytes), else groups of G threads across the grid walk consecutive rows.
+    const bool by_block = G <= kThreads;
+    const int rpi = by_block ? kThreads / G : 0;  // rows per iteration of a workgroup
     const uint32_t total = gridDim.x * kThreads;
     const uint32_t rows_per_pass = total / (uint32_t)G;
     const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
-    if (t < rows_per_pass * (uint32_t)G) {
-        const int g = (int)(t % (uint32_t)G);
+    const bool active = by_block ? (int)threadIdx.x < rpi * G : t < rows_per_pass * (uint32_t)G;
+    if (active) {
+        const int g = by_block ? (int)threadIdx.x % G : (int)(t % (uint32_t)G);
         float mn[VEC], mx[VEC];
 #pragma unroll
         for (int k = 0; k < VEC; k++) {
@@ -55,12 +61,20 @@ __global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restric
             mx[k] = -INFINITY;
         }
         const T *src = x + (int64_t)g * VEC;
-        // each group of G threads walks K consecutive rows: a contiguous stream per group
-        // (rows interleaved across the whole grid measured 13-20 % slower on fp32 tables)
-        const int64_t K = (rows + rows_per_pass - 1) / rows_per_pass;
-        const int64_t rbeg = (int64_t)(t / G) * K, rend = min(rows, rbeg + K);
+        int64_t rbeg, rend, rstep;
+        if (by_block) {
+            const int64_t per_block = (rows + gridDim.x - 1) / gridDim.x;
+            rbeg = (int64_t)blockIdx.x * per_block + (int)threadIdx.x / G;
+            rend = min(rows, (int64_t)(blockIdx.x + 1) * per_block);
+            rstep = rpi;
+        } else {
+            const int64_t K = (rows + rows_per_pass - 1) / rows_per_pass;
+            rbeg = (int64_t)(t / G) * K;
+            rend = min(rows, rbeg + K);
+            rstep = 1;
+        }
 #pragma unroll 4
-        for (int64_t r = rbeg; r < rend; r++) {
+        for (int64_t r = rbeg; r < rend; r += rstep) {
             float v[VEC];
             if constexpr (VEC == 4) {
                 float4 q = load4(src + r * D);
@@ -84,9 +98,13 @@ __global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restric
     }
     if (use_lds) {
         __syncthreads();
+        // thousands of workgroups would hammer the same 2*D words: only those that improve
+        // on the value already there (read without ordering: a stale read merely costs one
+        // atomic that changes nothing) issue the atomic
         for (int i = threadIdx.x; i < D; i += kThreads) {
-            atomicMin(&state[i], lds[i]);
-            atomicMax(&state[D + i], lds[D + i]);
+            const int32_t lo_k = lds[i], hi_k = lds[D + i];
+            if (lo_k < __builtin_nontemporal_load(&state[i])) atomicMin(&state[i], lo_k);
+            if (hi_k > __builtin_nontemporal_load(&state[D + i])) atomicMax(&state[D + i], hi_k);
         }
     }
 }
