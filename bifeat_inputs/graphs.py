@@ -182,3 +182,28 @@ def sample_blocks(graph, seeds: np.ndarray, fanouts: Sequence[int], seed: int,
         blocks.append(Block(dst=dst, indptr=indptr, indices=indices.astype(np.int64)))
         frontier = np.unique(np.concatenate([dst, indices]))
     return blocks, frontier
+
+
+def full_csr(graph, self_loops: bool = True, chunk: int = 1 << 18):
+    """Materialise the whole implicit graph as CSR lists (for graphs small
+    enough to hold): node u lists all ``degree(u)`` neighbour slots in slot
+    order, preceded by u itself when ``self_loops``.  Returns (indptr,
+    indices), int64."""
+    N = graph.N
+    extra = 1 if self_loops else 0
+    deg = graph.degree(np.arange(N, dtype=np.int64)) + extra
+    indptr = np.zeros(N + 1, dtype=np.int64)
+    np.cumsum(deg, out=indptr[1:])
+    indices = np.empty(int(indptr[-1]), dtype=np.int64)
+    for u0 in range(0, N, chunk):
+        u1 = min(N, u0 + chunk)
+        u = np.arange(u0, u1, dtype=np.int64)
+        n = deg[u0:u1]
+        owner = np.repeat(u, n)
+        k = np.arange(int(indptr[u1] - indptr[u0]), dtype=np.int64) - (indptr[owner] - indptr[u0])
+        if self_loops:
+            nb = np.where(k == 0, owner, graph.neighbor(owner, np.maximum(k - 1, 0)))
+        else:
+            nb = graph.neighbor(owner, k)
+        indices[indptr[u0]:indptr[u1]] = nb
+    return indptr, indices

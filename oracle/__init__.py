@@ -328,3 +328,27 @@ def gather_sum(s: Scheme, codes, indptr, indices) -> np.ndarray:
     out = np.empty((V, s.D), dtype=np.float32)
     lib().orc_gather_sum(C.byref(s._c), _p(codes), _p(indptr), _p(indices), C.c_int64(V), _p(out))
     return out
+
+
+# ------------------------------------- later layers, aggregation scale factors
+def aggregate_rows(x, indptr, indices, sum: bool = False) -> np.ndarray:
+    """Appendix A.1 for layers after the first: mean (or sum) of fp32 rows over
+    the listed neighbours."""
+    x, indptr, indices = _f32(x), _i64(indptr), _i64(indices)
+    V = indptr.shape[0] - 1
+    out = np.empty((V, x.shape[1]), dtype=np.float32)
+    lib().orc_aggregate_rows(_p(x), C.c_int64(x.shape[1]), _p(indptr), _p(indices), C.c_int64(V),
+                             C.c_int(1 if sum else 0), _p(out))
+    return out
+
+
+def scale_profile(x, indptr, indices, layers: int) -> np.ndarray:
+    """Appendix A.1 / A.5: mean row length after 0..layers rounds of
+    neighbourhood averaging over the whole graph (fp64)."""
+    x, indptr, indices = _f32(x), _i64(indptr), _i64(indices)
+    n = indptr.shape[0] - 1
+    assert x.shape[0] == n
+    out = np.empty(layers + 1, dtype=np.float64)
+    lib().orc_scale_profile(_p(x), C.c_int64(n), C.c_int64(x.shape[1]), _p(indptr), _p(indices),
+                            C.c_int(layers), _p(out))
+    return out

@@ -14,6 +14,8 @@
  *     `length` entries per part, store the index      Sec. 3.2, Appendix C
  *   - per-iteration load = rows of the sampled nodes, decoded      Sec. 3.3
  *   - neighbourhood mean  g_i = (1/|N(i)|) sum_{j in N(i)} g_j     Appendix A.1
+ *   - the same mean over fp32 rows (layers after the first), and the scale
+ *     factors C^e, C^f, C^_L of the aggregation      Appendix A.1, A.3, A.5
  * Where the paper is silent (bit packing, the uniform scheme's exact rounding,
  * k-means initialisation) the reading taken is stated at the function.
  *
@@ -590,4 +592,80 @@ void orc_gather_mean(const orc_scheme *s, const uint8_t *codes, const int64_t *i
         free(tmp);
         free(acc);
     }
+}
+
+/* ------------------------------- later layers and the aggregation scale factors
+ * Appendix A.1: every layer after the first aggregates the previous layer's
+ * rows in the same way, g_i = (1/|N(i)|) sum_{j in N(i)} g_j, over fp32 rows
+ * instead of packed codes.  out[v] = mean (sum != 0: plain sum) of the listed
+ * rows of x, in list order, fp64, one rounding to fp32; an empty list gives a
+ * zero row; repeats count with multiplicity. */
+void orc_aggregate_rows(const float *x, int64_t D, const int64_t *indptr, const int64_t *indices,
+                        int64_t V, int sum, float *out) {
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(dynamic, 64)
+        for (int64_t v = 0; v < V; v++) {
+            int64_t n = indptr[v + 1] - indptr[v];
+            for (int64_t j = 0; j < D; j++) acc[j] = 0.0;
+            for (int64_t e = indptr[v]; e < indptr[v + 1]; e++) {
+                const float *row = x + indices[e] * D;
+                for (int64_t j = 0; j < D; j++) acc[j] += (double)row[j];
+            }
+            for (int64_t j = 0; j < D; j++) {
+                double r = sum ? acc[j] : (n > 0 ? acc[j] / (double)n : 0.0);
+                out[v * D + j] = (float)r;
+            }
+        }
+        free(acc);
+    }
+}
+
+/* Appendix A.1 defines, per node i and depth l, the factors C^e_{i,l} and
+ * C^f_{i,l}: by how much l rounds of neighbourhood averaging shrink a
+ * quantisation error (independent between nodes) and the features themselves
+ * (correlated between neighbours); the appendix's analysis of depth and graph
+ * structure reports their means over the nodes and the ratio
+ * C^_L = mean_i C^e_{i,L} / mean_i C^f_{i,L}, and says they are obtained by a
+ * profiling run rather than from graph statistics.  That run, as read here:
+ * push a matrix through `layers` rounds of the averaging alone (no weights, no
+ * activation: the factors are defined as the effect of the aggregation) over
+ * the whole graph, lists taken as given (Appendix A.1 uses lists that include
+ * the node itself), and record how long the rows still are:
+ *     h_0 = x,  h_l[i] = (1/|N(i)|) sum_{j in N(i)} h_{l-1}[j]  (empty list: 0),
+ *     scale[l] = (1/n) sum_i ||h_l[i]||_2 ,  l = 0..layers.
+ * With x = an error matrix of independent unit-variance entries,
+ * scale[l]/scale[0] estimates mean_i C^e_{i,l}; with x = the unit-length
+ * feature rows it is mean_i C^f_{i,l}.  Everything in fp64, nothing rounded
+ * between the rounds. */
+void orc_scale_profile(const float *x, int64_t n, int64_t D, const int64_t *indptr,
+                       const int64_t *indices, int layers, double *scale) {
+    size_t total = (size_t)n * (size_t)D;
+    double *h = (double *)malloc(sizeof(double) * (total ? total : 1));
+    double *g = (double *)malloc(sizeof(double) * (total ? total : 1));
+    for (size_t t = 0; t < total; t++) h[t] = (double)x[t];
+    for (int l = 0; l <= layers; l++) {
+        if (l > 0) {
+#pragma omp parallel for schedule(dynamic, 64)
+            for (int64_t i = 0; i < n; i++) {
+                int64_t cnt = indptr[i + 1] - indptr[i];
+                for (int64_t j = 0; j < D; j++) g[i * D + j] = 0.0;
+                for (int64_t e = indptr[i]; e < indptr[i + 1]; e++)
+                    for (int64_t j = 0; j < D; j++) g[i * D + j] += h[indices[e] * D + j];
+                if (cnt > 0)
+                    for (int64_t j = 0; j < D; j++) g[i * D + j] /= (double)cnt;
+            }
+            double *t = h; h = g; g = t;
+        }
+        double s = 0.0;
+        for (int64_t i = 0; i < n; i++) {
+            double q = 0.0;
+            for (int64_t j = 0; j < D; j++) q += h[i * D + j] * h[i * D + j];
+            s += sqrt(q);
+        }
+        scale[l] = n > 0 ? s / (double)n : 0.0;
+    }
+    free(h);
+    free(g);
 }

@@ -87,3 +87,19 @@ def test_uniform_graph_slots_without_replacement():
         got = b.indices[b.indptr[v]:b.indptr[v + 1]]
         pos = [int(np.nonzero(full == x)[0][0]) for x in got]
         assert all(x in full for x in got) and pos == sorted(pos)
+
+
+def test_full_csr_lists_every_slot_after_the_node_itself():
+    from bifeat_inputs import full_csr
+    g = PowerLawGraph(500, 6.0, seed=4)
+    indptr, indices = full_csr(g, chunk=128)
+    u = np.arange(500, dtype=np.int64)
+    assert np.array_equal(np.diff(indptr), g.degree(u) + 1)
+    assert np.array_equal(indices[indptr[:-1]], u)
+    for v in (0, 127, 128, 499):
+        d = int(g.degree(np.array([v]))[0])
+        want = g.neighbor(np.full(d, v, np.int64), np.arange(d, dtype=np.int64))
+        assert np.array_equal(indices[indptr[v] + 1:indptr[v + 1]], want)
+    ip2, ix2 = full_csr(g, self_loops=False)
+    assert np.array_equal(np.diff(ip2), g.degree(u))
+    assert np.array_equal(ix2[ip2[7]:ip2[8]], indices[indptr[7] + 1:indptr[8]])
