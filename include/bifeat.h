@@ -213,6 +213,45 @@ int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const 
 int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream);
 
+/* ---- the layers after the first (Appendix A.1: every layer averages the
+ * previous layer's vectors over the same neighbourhoods): the aggregation over
+ * fp32 rows instead of packed codes.  For v in [0, V): out[v, :] = mean (sum != 0:
+ * plain sum) over e in [indptr[v], indptr[v+1]) of x[indices[e], :], the list
+ * taken as given, an empty list giving a zero row.  With the block's indices
+ * local to the previous hop's output this chains after bifeat_gather_mean into
+ * a multi-hop aggregation.
+ * x: DEVICE [N x D] fp32 row-major; indptr: DEVICE int64 [V+1]; indices: DEVICE
+ * int64 [E], each in [0, N) (the caller's contract, as for the gathers); out:
+ * DEVICE [V x D] fp32, not overlapping x.  Rows are added in list order in fp32
+ * with a compensated sum: within 1e-5 * max(|exact|, mean over the list of
+ * |x[.., j]|) of the exact result whatever the list length (n_v times that for
+ * the sum).
+ * Only enqueues one kernel on `stream`.  V = 0 is a no-op. */
+int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *indptr,
+                          const int64_t *indices, int64_t V, int64_t E, int32_t sum, float *out,
+                          void *stream);
+
+/* ---- the aggregation scale profile (Appendix A.1 defines C^e_{i,l} and
+ * C^f_{i,l}, the factors by which l rounds of averaging shrink independent
+ * errors and correlated features; Appendix A.3 their ratio of means C^_L;
+ * Appendix A.5 measures them by a profiling run to choose a compression
+ * ratio).  The run: h_0 = x, h_l = the neighbourhood mean of h_{l-1} over the
+ * whole graph (V = N, lists as given: include each node in its own list for
+ * the self-loop form of Appendix A.1), and
+ *     scale[l] = (1/N) sum_i ||h_l[i, :]||_2     for l = 0..layers.
+ * Called with a matrix of independent unit-variance errors, scale[l]/scale[0]
+ * estimates the mean of C^e_{i,l}; with unit-length feature rows it is the mean
+ * of C^f_{i,l}; C^_L is the quotient of the two at l = L.
+ * x, indptr, indices as above with V = N; the index contract is checked on
+ * the GPU first (BIFEAT_EINVAL if broken).  work: DEVICE scratch of
+ * min(layers, 2) * N * D floats, not overlapping x (may be NULL for layers = 0).
+ * scale: HOST double[layers + 1].  0 <= layers <= 64.  Row lengths are
+ * accumulated in fp64; h_l is stored in fp32 between rounds.  Allocates a few
+ * bytes of device memory and synchronises `stream`. */
+int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *indptr,
+                         const int64_t *indices, int64_t E, int32_t layers, float *work,
+                         double *scale, void *stream);
+
 const char *bifeat_strerror(int status);
 
 /* Launch tuning for measurements (no effect on results): "mean_slots" = lanes

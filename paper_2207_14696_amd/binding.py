@@ -67,6 +67,10 @@ _SIGNATURES = {
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_gather_sum": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_aggregate_rows": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]),
+    "bifeat_scale_profile": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                       C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "bifeat_strerror": (C.c_char_p, [C.c_int]),
     "bifeat_set_option": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int]),
 }
@@ -264,3 +268,41 @@ class Quantizer:
 
     def gather_sum(self, codes, indptr, indices, out=None):
         return self._aggregate(self._lib.bifeat_gather_sum, codes, indptr, indices, out)
+
+
+def aggregate_rows(x, indptr, indices, out=None, sum: bool = False):
+    """``bifeat_aggregate_rows``: mean (or sum) of fp32 rows of ``x`` over CSR lists."""
+    import torch
+    if x.dim() != 2:
+        raise ValueError("x must be [N, D]")
+    V, D = indptr.shape[0] - 1, x.shape[1]
+    if out is None:
+        out = torch.empty((V, D), dtype=torch.float32, device=x.device)
+    elif out.shape != (V, D):
+        raise ValueError("out must be [V, D]")
+    _check(load_library().bifeat_aggregate_rows(
+        _dev_ptr(x, (torch.float32,)), x.shape[0], D, _dev_ptr(indptr, (torch.int64,)),
+        _dev_ptr(indices, (torch.int64,)), V, indices.shape[0], 1 if sum else 0,
+        _dev_ptr(out, (torch.float32,)), _stream()))
+    return out
+
+
+def scale_profile(x, indptr, indices, layers: int, work=None):
+    """``bifeat_scale_profile``: mean row length of ``x`` after 0..layers rounds of
+    neighbourhood averaging over the whole graph, as a numpy fp64 array."""
+    import numpy as np
+    import torch
+    if x.dim() != 2 or indptr.shape[0] - 1 != x.shape[0]:
+        raise ValueError("x must be [N, D] with one list per row")
+    N, D = x.shape
+    need = min(layers, 2) * N * D
+    if work is None and need > 0:
+        work = torch.empty(need, dtype=torch.float32, device=x.device)
+    elif work is not None and work.numel() < need:
+        raise ValueError("work must hold min(layers, 2) * N * D floats")
+    scale = np.empty(layers + 1, dtype=np.float64)
+    _check(load_library().bifeat_scale_profile(
+        _dev_ptr(x, (torch.float32,)), N, D, _dev_ptr(indptr, (torch.int64,)),
+        _dev_ptr(indices, (torch.int64,)), indices.shape[0], layers,
+        _dev_ptr(work, (torch.float32,)), _np_ptr(scale), _stream()))
+    return scale

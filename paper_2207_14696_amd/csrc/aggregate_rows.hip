@@ -1,0 +1,167 @@
+// Aggregation over fp32 rows: the layers after the first (Appendix A.1), where the
+// neighbourhood mean runs over the previous layer's output instead of packed codes,
+// and the row-length reduction of the scale profile (Appendix A.1, A.5).
+//
+// Both are row gathers bound by HBM: a row of D floats is fetched whole, 16 bytes per
+// lane, several rows in flight per lane; nothing is staged.
+#include "common.hpp"
+
+namespace bf {
+namespace {
+
+constexpr int kAggInFlight = 4;  // rows in flight per lane
+
+// Compensated (Kahan) running sums: the rounding error of a sum stays at a couple of
+// ulps of the mean magnitude whatever the list length; the kernel waits on memory, so
+// the three extra operations per element cost nothing.  (Compiled without contraction
+// or reassociation, which this relies on.)
+__device__ inline void kahan_add(float &s, float &c, const float r) {
+    const float y = r - c;
+    const float t = s + y;
+    c = (t - s) - y;
+    s = t;
+}
+
+template <int VEC>
+struct Acc;
+template <>
+struct Acc<4> {
+    float4 v, c;
+    __device__ void zero() { v = c = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ static float4 load(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    __device__ void add(const float4 r) {
+        kahan_add(v.x, c.x, r.x);
+        kahan_add(v.y, c.y, r.y);
+        kahan_add(v.z, c.z, r.z);
+        kahan_add(v.w, c.w, r.w);
+    }
+    __device__ void store(float *p, int n, bool sum) const {
+        float4 o = v;
+        if (!sum) {
+            const float d = (float)n;
+            o = n > 0 ? make_float4(v.x / d, v.y / d, v.z / d, v.w / d) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        store_stream(reinterpret_cast<float4 *>(p), o);
+    }
+};
+template <>
+struct Acc<1> {
+    float v, c;
+    __device__ void zero() { v = c = 0.f; }
+    __device__ static float load(const float *p) { return *p; }
+    __device__ void add(const float r) { kahan_add(v, c, r); }
+    __device__ void store(float *p, int n, bool sum) const {
+        __builtin_nontemporal_store(sum ? v : (n > 0 ? v / (float)n : 0.f), p);
+    }
+};
+
+// A group of `lpr` lanes (a power of two up to 64) owns one (destination, column
+// tile) item at a time: lane t of the group accumulates columns
+// VEC*(tile*lpr + t) .. +VEC-1 over the destination's list, in list order (fp32, compensated).  Items
+// are numbered tile-fastest so that neighbouring groups write one contiguous row.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(
+    const float *__restrict__ x, int64_t D, const int64_t *__restrict__ indptr,
+    const int64_t *__restrict__ indices, int64_t V, int lpr_log2, int tiles, int sum,
+    float *__restrict__ out) {
+    const int lpr = 1 << lpr_log2;
+    const int t = threadIdx.x & (lpr - 1);
+    const int64_t groups = ((int64_t)gridDim.x * kThreads) >> lpr_log2;
+    const int64_t items = V * tiles;
+    for (int64_t item = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> lpr_log2; item < items;
+         item += groups) {
+        const int64_t v = item / tiles;
+        const int tile = (int)(item - v * tiles);
+        const int64_t col = (int64_t)VEC * (tile * lpr + t);
+        const bool live = col < D;
+        const int64_t beg = indptr[v], end = indptr[v + 1];
+        Acc<VEC> acc;
+        acc.zero();
+        if (live) {
+            const float *base = x + col;
+            int64_t e = beg;
+            for (; e + kAggInFlight <= end; e += kAggInFlight) {
+                decltype(Acc<VEC>::load(base)) r[kAggInFlight];
+#pragma unroll
+                for (int k = 0; k < kAggInFlight; k++) r[k] = Acc<VEC>::load(base + indices[e + k] * D);
+#pragma unroll
+                for (int k = 0; k < kAggInFlight; k++) acc.add(r[k]);
+            }
+            for (; e < end; e++) acc.add(Acc<VEC>::load(base + indices[e] * D));
+            acc.store(out + v * D + col, (int)(end - beg), sum != 0);
+        }
+    }
+}
+
+// acc[0] += sum over rows of sqrt(sum_j h[i][j]^2): one wave per row, squares and
+// their sum in fp64, one atomic per workgroup.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void row_length_sum_kernel(const float *__restrict__ h,
+                                                                  int64_t n, int64_t D,
+                                                                  double *__restrict__ acc) {
+    __shared__ double s_part[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t waves = (int64_t)gridDim.x * (kThreads / 64);
+    double total = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * (kThreads / 64) + wave; i < n; i += waves) {
+        const float *row = h + i * D;
+        double q = 0.0;
+        if constexpr (VEC == 4) {
+            for (int64_t j = 4 * lane; j < D; j += 256) {
+                const float4 r = *reinterpret_cast<const float4 *>(row + j);
+                q += (double)r.x * r.x;
+                q += (double)r.y * r.y;
+                q += (double)r.z * r.z;
+                q += (double)r.w * r.w;
+            }
+        } else {
+            for (int64_t j = lane; j < D; j += 64) q += (double)row[j] * row[j];
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) q += __shfl_xor(q, m, 64);
+        total += sqrt(q);
+    }
+    if (lane == 0) s_part[wave] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double b = 0.0;
+        for (int k = 0; k < kThreads / 64; k++) b += s_part[k];
+        if (b != 0.0) atomicAdd(acc, b);
+    }
+}
+
+bool vec_ok(const void *a, const void *b, int64_t D) {
+    return D % 4 == 0 && (uintptr_t)a % 16 == 0 && (uintptr_t)b % 16 == 0;
+}
+
+}  // namespace
+
+hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indptr,
+                                 const int64_t *indices, int64_t V, int sum, float *out,
+                                 hipStream_t s) {
+    const bool vec = vec_ok(x, out, D);
+    const int64_t granules = vec ? D / 4 : D;
+    int lpr_log2 = 2;  // at least four lanes per row
+    while (lpr_log2 < 6 && ((int64_t)1 << lpr_log2) < granules) lpr_log2++;
+    const int64_t tiles = (granules + ((int64_t)1 << lpr_log2) - 1) >> lpr_log2;
+    const int64_t threads = (V * tiles) << lpr_log2;
+    const int blocks = blocks_for(threads, 8 * 256);
+    if (vec)
+        aggregate_rows_kernel<4><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, lpr_log2,
+                                                            (int)tiles, sum, out);
+    else
+        aggregate_rows_kernel<1><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, lpr_log2,
+                                                            (int)tiles, sum, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_length_sum(const float *h, int64_t n, int64_t D, double *acc, hipStream_t s) {
+    const int blocks = blocks_for(n * 64, 8 * 256);
+    if (vec_ok(h, h, D))
+        row_length_sum_kernel<4><<<blocks, kThreads, 0, s>>>(h, n, D, acc);
+    else
+        row_length_sum_kernel<1><<<blocks, kThreads, 0, s>>>(h, n, D, acc);
+    return hipGetLastError();
+}
+
+}  // namespace bf

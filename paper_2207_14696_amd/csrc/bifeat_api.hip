@@ -565,6 +565,64 @@ int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const i
     return rc;
 }
 
+int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *indptr,
+                          const int64_t *indices, int64_t V, int64_t E, int32_t sum, float *out,
+                          void *stream) {
+    if (V < 0 || N < 0 || E < 0 || D <= 0 || D > (int64_t)1 << 24) return BIFEAT_EINVAL;
+    if (V > 0 && (!indptr || !out || (E > 0 && (!indices || !x || N == 0)))) return BIFEAT_EINVAL;
+    if ((uintptr_t)x % 4 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
+    if (V == 0) return BIFEAT_OK;
+    BF_HIP(bf::launch_aggregate_rows(x, D, indptr, indices, V, sum != 0, out, (hipStream_t)stream));
+    return BIFEAT_OK;
+}
+
+int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *indptr,
+                         const int64_t *indices, int64_t E, int32_t layers, float *work,
+                         double *scale, void *stream) {
+    if (N < 0 || E < 0 || D <= 0 || D > (int64_t)1 << 24 || layers < 0 || layers > 64 || !scale)
+        return BIFEAT_EINVAL;
+    if (N > 0 && (!x || !indptr || (E > 0 && !indices) || (layers > 0 && !work))) return BIFEAT_EINVAL;
+    if ((uintptr_t)x % 4 || (uintptr_t)work % 4) return BIFEAT_EINVAL;
+    if (N == 0) {
+        for (int l = 0; l <= layers; l++) scale[l] = 0.0;
+        return BIFEAT_OK;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    // layers+1 sums, then the flag of the index check
+    double *d_acc = nullptr;
+    const size_t bytes = sizeof(double) * (size_t)(layers + 2);
+    BF_HIP(hipMalloc((void **)&d_acc, bytes));
+    double h_acc[66];
+    int32_t bad = 0;
+    hipError_t e = hipMemsetAsync(d_acc, 0, bytes, s);
+    if (e == hipSuccess) {
+        int32_t *d_bad = reinterpret_cast<int32_t *>(d_acc + layers + 1);
+        bf::launch_validate(indices, E, N, indptr, N, E, d_bad, s);
+        e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess && !bad) {
+        e = bf::launch_row_length_sum(x, N, D, d_acc, s);
+        const float *src = x;
+        for (int l = 1; l <= layers && e == hipSuccess; l++) {
+            float *dst = work + (size_t)((l - 1) & 1) * (size_t)N * (size_t)D;
+            e = bf::launch_aggregate_rows(src, D, indptr, indices, N, 0, dst, s);
+            if (e == hipSuccess) e = bf::launch_row_length_sum(dst, N, D, d_acc + l, s);
+            src = dst;
+        }
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(h_acc, d_acc, sizeof(double) * (size_t)(layers + 1),
+                               hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+    }
+    const hipError_t ef = hipFree(d_acc);
+    if (e != hipSuccess) return hip_fail(e, "bifeat_scale_profile");
+    if (ef != hipSuccess) return hip_fail(ef, "hipFree");
+    if (bad) return BIFEAT_EINVAL;
+    for (int l = 0; l <= layers; l++) scale[l] = h_acc[l] / (double)N;
+    return BIFEAT_OK;
+}
+
 const char *bifeat_strerror(int status) {
     switch (status) {
         case BIFEAT_OK: return "ok";

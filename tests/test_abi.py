@@ -64,6 +64,12 @@ def test_argument_errors_come_before_any_gpu_call(bf):
     assert lib.bifeat_fit_update(h, None, 0, 5, None) == -1
     assert lib.bifeat_gather_dequant(h, 16, 10, 16, 5, 16, None) == -2       # aligned dummies, not fitted
     assert lib.bifeat_gather_dequant(h, 8, 10, 16, 5, 16, None) == -1        # misaligned table
+    assert lib.bifeat_aggregate_rows(16, 10, 0, 16, 16, 1, 0, 0, 16, None) == -1     # D = 0
+    assert lib.bifeat_aggregate_rows(16, 10, 4, None, 16, 1, 0, 0, 16, None) == -1   # no indptr
+    assert lib.bifeat_aggregate_rows(16, 10, 4, 16, 16, 0, 0, 0, 16, None) == 0      # V = 0: no-op
+    assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 65, 16, 16, None) == -1    # too many layers
+    assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 2, None, 16, None) == -1   # no work buffer
+    assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 2, 16, None, None) == -1   # no result array
     assert lib.bifeat_set_option(h, b"no_such_option", 1) == -1
     assert lib.bifeat_set_option(h, b"mean_slots", 4) == 0
     assert lib.bifeat_row_bytes(None) == -1

@@ -1,0 +1,166 @@
+"""GPU parity for the layers after the first and the aggregation scale profile
+(Appendix A.1, A.3, A.5): fp32-row aggregation, two-hop chains that start from
+the packed table, and the profiling run, each against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle as orc
+from bifeat_inputs import (FeatureSpec, PowerLawGraph, UniformGraph, draw_seeds, feature_chunk,
+                           full_csr, sample_blocks)
+from helpers import assert_close, gpu_build_table, oracle_uniform_table, random_csr, scheme_of
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def bf():
+    import paper_2207_14696_amd as m
+    m.load_library()
+    return m
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    return t
+
+
+def _assert_rows_close(got, want, x, indptr, indices, as_sum, what):
+    # |gpu - oracle| <= 1e-5 * max(|oracle|, mean over the list of |x|) (times the list
+    # length for the sum): the scale the rounding of a sum is measured against
+    ref = orc.aggregate_rows(np.abs(x), indptr, indices, sum=as_sum).astype(np.float64)
+    bound = REL_TOL * np.maximum(np.abs(want.astype(np.float64)), ref)
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside 1e-5; worst {(err / np.maximum(bound, 1e-300)).max():.3g}"
+
+
+@pytest.mark.parametrize("as_sum", [False, True])
+@pytest.mark.parametrize("D", [128, 100, 37, 768, 600, 4, 1, 1028])
+def test_aggregate_rows_matches_the_oracle(bf, torch, D, as_sum):
+    rng = np.random.default_rng(D)
+    N, V = 3000, 1501
+    x = (rng.standard_normal((N, D)) * rng.uniform(0.1, 10, D)).astype(np.float32)
+    indptr, indices = random_csr(V, N, 20, rng, hubs=(300, 4500))
+    want = orc.aggregate_rows(x, indptr, indices, sum=as_sum)
+    dx = torch.from_numpy(x).cuda()
+    got = bf.aggregate_rows(dx, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(),
+                            sum=as_sum).cpu().numpy()
+    assert not got[0].any()
+    _assert_rows_close(got, want, x, indptr, indices, as_sum, f"D={D}")
+
+
+def test_aggregate_rows_edge_cases(bf, torch):
+    x = torch.arange(40, dtype=torch.float32, device="cuda").reshape(10, 4)
+    empty = torch.zeros(1, dtype=torch.int64, device="cuda")
+    none = torch.zeros(0, dtype=torch.int64, device="cuda")
+    assert bf.aggregate_rows(x, empty, none).shape == (0, 4)
+    # every list empty: all-zero rows, written (the buffer starts out as ones)
+    out = torch.ones((5, 4), dtype=torch.float32, device="cuda")
+    bf.aggregate_rows(x, torch.zeros(6, dtype=torch.int64, device="cuda"), none, out=out)
+    assert not out.cpu().numpy().any()
+    # a single neighbour is that row, bit for bit; unaligned views take the scalar path
+    idx = torch.tensor([7, 0, 9], dtype=torch.int64, device="cuda")
+    ptr = torch.arange(4, dtype=torch.int64, device="cuda")
+    assert torch.equal(bf.aggregate_rows(x, ptr, idx), x[idx])
+    flat = torch.arange(41, dtype=torch.float32, device="cuda")
+    shifted = flat[1:].reshape(10, 4)                          # 4-byte aligned only
+    assert torch.equal(bf.aggregate_rows(shifted, ptr, idx), shifted[idx])
+
+
+@pytest.mark.parametrize("kind,bits,D", [("uniform", 4, 128), ("uniform", 2, 100), ("log", 1, 64)])
+def test_two_hop_chain_from_the_packed_table(bf, torch, kind, bits, D):
+    # layer 1 aggregates decoded rows of the packed table over the outer block; layer 2
+    # aggregates layer 1's output over the seed block, its lists renumbered to rows of
+    # that output (the frontier is sorted, so a binary search renumbers them)
+    N = 20000
+    spec = FeatureSpec(N, D, 3)
+    x = feature_chunk(spec, 0, N)
+    if kind == "uniform":
+        _, _, s, codes = oracle_uniform_table(spec, bits)
+        q = bf.Quantizer(scheme_of("uniform", bits), D)
+    else:
+        e_min, e_max = orc.log_range(orc.log_fit(x))
+        T, Vt = orc.log_tables(e_min, e_max, bits)
+        codes = orc.pack(orc.log_encode(x, bits, T), bits)
+        s = orc.Scheme.log(D, Vt, bits)
+        q = bf.Quantizer(scheme_of("log", bits), D)
+    from bifeat_inputs.device import DeviceTable
+    dcodes = gpu_build_table(q, DeviceTable(spec), N, 8192)
+    assert np.array_equal(dcodes.cpu().numpy(), codes)
+    g = PowerLawGraph(N, 12.0, seed=5)
+    seeds = draw_seeds(g, 512, 5, 0)
+    blocks, _ = sample_blocks(g, seeds, [10, 15], 5, 0)
+    inner, outer = blocks[0], blocks[1]
+    local = np.searchsorted(outer.dst, inner.indices)
+    assert np.array_equal(outer.dst[local], inner.indices)
+    h1_want = orc.gather_mean(s, codes, outer.indptr, outer.indices)
+    h2_want = orc.aggregate_rows(h1_want, inner.indptr, local)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    h1 = q.gather_mean(dcodes, cu(outer.indptr), cu(outer.indices))
+    h2 = bf.aggregate_rows(h1, cu(inner.indptr), cu(local))
+    assert_close(h1.cpu().numpy(), h1_want, s, "layer 1")
+    # layer 2 inherits layer 1's rounding once more
+    A = np.abs(orc.gather_dequant(s, codes, np.arange(N))).max(axis=0).astype(np.float64)[None, :]
+    err = np.abs(h2.cpu().numpy().astype(np.float64) - h2_want.astype(np.float64))
+    assert (err <= 2 * REL_TOL * np.maximum(np.abs(h2_want), A)).all()
+
+
+def _lists(rows):
+    indptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int64)
+    return indptr, np.array([j for r in rows for j in r], dtype=np.int64)
+
+
+def test_scale_profile_closed_forms_on_the_gpu(bf, torch):
+    n = 64
+    eye = torch.eye(n, dtype=torch.float32, device="cuda")
+    cu = lambda a: torch.from_numpy(a).cuda()
+    ptr, idx = _lists([list(range(n))] * n)                       # complete graph with self loops
+    assert np.allclose(bf.scale_profile(eye, cu(ptr), cu(idx), 3), [1, 0.125, 0.125, 0.125], rtol=1e-6)
+    ptr, idx = _lists([[(i - 1) % n, i, (i + 1) % n] for i in range(n)])
+    assert np.allclose(bf.scale_profile(eye, cu(ptr), cu(idx), 2), [1, 3 ** -0.5, 19 ** 0.5 / 9], rtol=1e-6)
+    ptr, idx = _lists([[] for _ in range(n)])
+    assert np.allclose(bf.scale_profile(eye, cu(ptr), cu(idx), 2), [1, 0, 0])
+    assert np.allclose(bf.scale_profile(eye, cu(ptr), cu(idx), 0), [1])
+
+
+@pytest.mark.parametrize("D,layers", [(64, 3), (37, 2), (256, 5), (600, 1)])
+def test_scale_profile_matches_the_oracle(bf, torch, D, layers):
+    n = 20000
+    rng = np.random.default_rng(D)
+    g = PowerLawGraph(n, 10.0, alpha=2.1, cap=2000, seed=D) if D != 37 else UniformGraph(n, 6, seed=2)
+    indptr, indices = full_csr(g)
+    noise = rng.standard_normal((n, D)).astype(np.float32)
+    base = rng.standard_normal(D)
+    feat = base[None, :] + 0.7 * rng.standard_normal((n, D))
+    feat = (feat / np.linalg.norm(feat, axis=1, keepdims=True)).astype(np.float32)
+    cu = lambda a: torch.from_numpy(a).cuda()
+    dptr, dind = cu(indptr), cu(indices)
+    work = torch.empty(min(layers, 2) * n * D, dtype=torch.float32, device="cuda")
+    ce = bf.scale_profile(cu(noise), dptr, dind, layers, work=work)
+    cf = bf.scale_profile(cu(feat), dptr, dind, layers)
+    ce_want = orc.scale_profile(noise, indptr, indices, layers)
+    cf_want = orc.scale_profile(feat, indptr, indices, layers)
+    assert np.allclose(ce, ce_want, rtol=REL_TOL, atol=0)
+    assert np.allclose(cf, cf_want, rtol=REL_TOL, atol=0)
+    c_hat = (ce / ce[0]) / (cf / cf[0])
+    assert (c_hat[1:] < 1).all() and (np.diff(c_hat) < 0).all()
+
+
+def test_scale_profile_rejects_a_broken_graph(bf, torch):
+    n, D = 100, 8
+    x = torch.ones((n, D), dtype=torch.float32, device="cuda")
+    ptr = torch.arange(n + 1, dtype=torch.int64, device="cuda")
+    idx = torch.arange(n, dtype=torch.int64, device="cuda")
+    assert np.allclose(bf.scale_profile(x, ptr, idx, 2), 8 ** 0.5)
+    bad = idx.clone()
+    bad[17] = n                                                   # out of range
+    with pytest.raises(bf.BifeatError) as e:
+        bf.scale_profile(x, ptr, bad, 2)
+    assert e.value.status == -1
+    with pytest.raises(bf.BifeatError):
+        bf.scale_profile(x, ptr, idx, 65)
+    # the library still works afterwards
+    assert np.allclose(bf.scale_profile(x, ptr, idx, 1), 8 ** 0.5)
