@@ -16,7 +16,9 @@ most time in the step (algorithmic bytes over its HIP-event duration against the
 8 TB/s HBM peak; "traffic" = counter-measured bytes per launch when a profile
 summary for this workload is present), "kernels" (the same for every call of
 the step), "cpu_baseline" (the CPU oracle on the host cores, a bounded sample)
-and "preprocess".  Progress lines go to stderr.
+and "preprocess"; with ``--scale-profile LAYERS`` also "scale_profile" (the
+aggregation scale factors of the workload's codes on a graph of its family).
+Progress lines go to stderr.
 """
 from __future__ import annotations
 
@@ -60,6 +62,12 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="replay each launch-set's step from a captured HIP graph (whole-step "
                          "timing; per-kernel figures still come from an eager pass)")
+    ap.add_argument("--scale-profile", type=int, default=0, metavar="LAYERS",
+                    help="after the timed region, also run the aggregation scale profile (error and "
+                         "feature scale after 1..LAYERS rounds of neighbourhood averaging, and their "
+                         "ratio) of this workload's codes on a materialised graph of the same family")
+    ap.add_argument("--profile-nodes", type=int, default=1 << 20,
+                    help="nodes (= leading rows of the table) of the scale-profile graph")
     ap.add_argument("--aggregator", default="mean", choices=["mean", "sum"],
                     help="which fused aggregation the hops run (the metric's workload is mean)")
     return ap.parse_args()
@@ -298,6 +306,8 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, g, args.cpu_seconds)
 
+    sp = scale_profile_leg(args, w, q, codes, table) if args.scale_profile > 0 else None
+
     value = rows_total / wall
     res = {
         "metric": "sampled rows gathered+dequantized/s", "value": round(value, 1), "unit": "rows/s",
@@ -318,7 +328,73 @@ def main():
         "cpu_baseline": cpu,
         "preprocess": {k: round(v, 3) for k, v in pre.items()},
     }
+    if sp is not None:
+        res["scale_profile"] = sp
     print(json.dumps(res))
+
+
+def scale_profile_leg(args, w, q, codes, table):
+    """The aggregation scale profile for this workload's codes: how much of the
+    actual quantisation error (decoded minus raw rows) and of the unit-length
+    features survives 1..LAYERS rounds of neighbourhood averaging over a whole
+    graph of the workload's family (lists include the node itself), and the
+    ratio of the two, the factor that bounds the tolerable error.  Also times
+    the fp32-row aggregation it is built from."""
+    import torch
+    import paper_2207_14696_amd as bf
+    from bifeat_inputs import PowerLawGraph, UniformGraph, full_csr
+    layers = args.scale_profile
+    n = min(w.N, args.profile_nodes)
+    g = UniformGraph(n, int(w.avg_degree), w.seed) if w.graph == "uniform" \
+        else PowerLawGraph(n, w.avg_degree, 2.1, min(w.cap, n - 1), w.seed)
+    indptr, indices = full_csr(g)
+    E = int(indices.shape[0])
+    say(f"scale profile: graph of {n} nodes, {E} list entries materialised")
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    x = table.chunk(0, n).float()
+    dec = q.gather_dequant(codes, torch.arange(n, dtype=torch.int64, device="cuda"))
+    err = dec - x
+    del dec
+    unit = x / x.norm(dim=1, keepdim=True).clamp_min(1e-30)
+    del x
+    work = torch.empty(min(layers, 2) * n * w.D, dtype=torch.float32, device="cuda")
+    t0 = time.perf_counter()
+    ce = bf.scale_profile(err, dptr, dind, layers, work=work)
+    profile_ms = (time.perf_counter() - t0) * 1e3
+    cf = bf.scale_profile(unit, dptr, dind, layers, work=work)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    err.normal_(generator=gen)
+    ci = bf.scale_profile(err, dptr, dind, layers, work=work)
+    # the fp32-row aggregation on its own: rows are read once each (compulsory) and written once
+    out = work[:n * w.D].view(n, w.D)
+    bf.aggregate_rows(unit, dptr, dind, out=out)
+    reps = 5
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        bf.aggregate_rows(unit, dptr, dind, out=out)
+    b.record()
+    b.synchronize()
+    us = a.elapsed_time(b) / reps * 1e3
+    nbytes = 8 * (n + 1) + 8 * E + 2 * 4 * w.D * n
+    requested = 8 * (n + 1) + 8 * E + 4 * w.D * E + 4 * w.D * n
+    rel = lambda c: [round(float(v / c[0]), 6) if c[0] > 0 else 0.0 for v in c]  # noqa: E731
+    c_e, c_f, c_i = rel(ce), rel(cf), rel(ci)
+    return {"nodes": n, "list_entries": E, "self_loops": True, "layers": layers,
+            "error_row_length": float(ce[0]),
+            "C_e": c_e, "C_f": c_f, "C_hat": [round(e / f, 6) if f > 0 else None for e, f in zip(c_e, c_f)],
+            "C_e_independent_noise": c_i,
+            "profile_ms": round(profile_ms, 3),
+            # algorithmic bytes: every row read once and written once; "requested" counts a row
+            # per list entry, which caches serve in part (it can exceed the HBM peak)
+            "aggregate_rows": {"bound": "hbm", "avg_kernel_us": round(us, 2),
+                               "algorithmic_bytes_per_launch": nbytes,
+                               "achieved": round(nbytes / us / 1e3, 1), "peak": HBM_PEAK_GBPS,
+                               "unit": "GB/s", "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                               "requested_bytes_per_launch": requested,
+                               "requested_GBps": round(requested / us / 1e3, 1),
+                               "list_entries_per_s": round(E / us * 1e6, 1)}}
 
 
 def cpu_baseline(w, g, seconds: float):

@@ -10,6 +10,15 @@ namespace bf {
 namespace {
 
 constexpr int kAggInFlight = 4;  // rows in flight per lane
+// A list longer than kLong is not walked by one lane group (a hub's thousands of rows,
+// one latency after the other, would outlast the rest of the launch): it is cut into
+// pieces of kSub list entries that many groups sum side by side and add into the output
+// row with atomics.  A workgroup of that kernel looks after kRange consecutive list
+// entries, which at most kRange / kLong + 2 long lists can overlap.
+constexpr int kLong = 256;
+constexpr int kRange = 2048;
+constexpr int kSub = 128;
+constexpr int kMaxLong = kRange / kLong + 2;
 
 // Compensated (Kahan) running sums: the rounding error of a sum stays at a couple of
 // ulps of the mean magnitude whatever the list length; the kernel waits on memory, so
@@ -43,6 +52,17 @@ struct Acc<4> {
         }
         store_stream(reinterpret_cast<float4 *>(p), o);
     }
+    __device__ static void store_zero(float *p) {
+        store_stream(reinterpret_cast<float4 *>(p), make_float4(0.f, 0.f, 0.f, 0.f));
+    }
+    // this piece's share of the row: partial sum (divided by the whole list's length)
+    __device__ void add_to(float *p, int n, bool sum) const {
+        const float d = (float)n;
+        unsafeAtomicAdd(p + 0, sum ? v.x : v.x / d);
+        unsafeAtomicAdd(p + 1, sum ? v.y : v.y / d);
+        unsafeAtomicAdd(p + 2, sum ? v.z : v.z / d);
+        unsafeAtomicAdd(p + 3, sum ? v.w : v.w / d);
+    }
 };
 template <>
 struct Acc<1> {
@@ -52,6 +72,10 @@ struct Acc<1> {
     __device__ void add(const float r) { kahan_add(v, c, r); }
     __device__ void store(float *p, int n, bool sum) const {
         __builtin_nontemporal_store(sum ? v : (n > 0 ? v / (float)n : 0.f), p);
+    }
+    __device__ static void store_zero(float *p) { __builtin_nontemporal_store(0.f, p); }
+    __device__ void add_to(float *p, int n, bool sum) const {
+        unsafeAtomicAdd(p, sum ? v : v / (float)n);
     }
 };
 
@@ -77,7 +101,9 @@ __global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(
         const int64_t beg = indptr[v], end = indptr[v + 1];
         Acc<VEC> acc;
         acc.zero();
-        if (live) {
+        if (live && end - beg > kLong) {
+            Acc<VEC>::store_zero(out + v * D + col);  // the pieces are added by the kernel below
+        } else if (live) {
             const float *base = x + col;
             int64_t e = beg;
             for (; e + kAggInFlight <= end; e += kAggInFlight) {
@@ -90,6 +116,97 @@ __global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(
             for (; e < end; e++) acc.add(Acc<VEC>::load(base + indices[e] * D));
             acc.store(out + v * D + col, (int)(end - beg), sum != 0);
         }
+    }
+}
+
+// The long lists: workgroup b looks after list entries [b*kRange, (b+1)*kRange).  It
+// finds the first destination whose list reaches into that range (a 64-way search in
+// indptr by one wave), walks on from there, notes the long lists with the part that
+// falls inside the range, and
+// its lane groups sum pieces of kSub entries of those parts, each piece added to the
+// (zeroed) output row.  Launched after the kernel above, on the same stream.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void aggregate_long_kernel(
+    const float *__restrict__ x, int64_t D, const int64_t *__restrict__ indptr,
+    const int64_t *__restrict__ indices, int64_t V, int64_t E, int lpr_log2, int tiles, int sum,
+    float *__restrict__ out) {
+    __shared__ int64_t s_v[kMaxLong], s_beg[kMaxLong], s_end[kMaxLong], s_first;
+    __shared__ int s_deg[kMaxLong], s_n;
+    const int lpr = 1 << lpr_log2;
+    const int t = threadIdx.x & (lpr - 1);
+    const int group = threadIdx.x >> lpr_log2, groups = kThreads >> lpr_log2;
+    constexpr int kPieces = kRange / kSub;
+    for (int64_t r0 = (int64_t)blockIdx.x * kRange; r0 < E; r0 += (int64_t)gridDim.x * kRange) {
+        const int64_t r1 = r0 + kRange < E ? r0 + kRange : E;
+        if (threadIdx.x < 64) {
+            // first v with indptr[v + 1] > r0: 64 probes a round, evenly spaced over [lo, hi)
+            int64_t lo = 0, hi = V;
+            while (lo < hi) {
+                const int64_t step = (hi - lo + 63) >> 6;
+                const int64_t probe = lo + (int64_t)threadIdx.x * step;
+                const uint64_t valid = __ballot(probe < hi);
+                const uint64_t hit = __ballot(probe < hi && indptr[probe + 1] > r0);
+                if (hit == 0) {
+                    lo += (int64_t)(__popcll(valid) - 1) * step + 1;  // past the last probe
+                } else {
+                    const int j = __ffsll((unsigned long long)hit) - 1;
+                    hi = lo + j * step;
+                    if (j > 0) lo += (int64_t)(j - 1) * step + 1;
+                }
+            }
+            if (threadIdx.x == 0) {
+                s_first = lo;
+                s_n = 0;
+            }
+        }
+        __syncthreads();
+        // walk the destinations from there until one starts at or after r1
+        for (int64_t v0 = s_first;; v0 += kThreads) {
+            const int64_t v = v0 + threadIdx.x;
+            bool past = v >= V;
+            if (!past) {
+                const int64_t beg = indptr[v];
+                past = beg >= r1;
+                if (!past) {
+                    const int64_t end = indptr[v + 1];
+                    if (end - beg > kLong) {
+                        const int k = atomicAdd(&s_n, 1);
+                        if (k < kMaxLong) {
+                            s_v[k] = v;
+                            s_beg[k] = beg > r0 ? beg : r0;
+                            s_end[k] = end < r1 ? end : r1;
+                            s_deg[k] = (int)(end - beg);
+                        }
+                    }
+                }
+            }
+            if (__syncthreads_or(past)) break;
+        }
+        const int n_long = s_n < kMaxLong ? s_n : kMaxLong;
+        const int work = n_long * kPieces * tiles;
+        for (int it = group; it < work; it += groups) {
+            const int tile = it % tiles;
+            const int piece = (it / tiles) % kPieces;
+            const int k = it / (tiles * kPieces);
+            const int64_t b = s_beg[k] + (int64_t)piece * kSub;
+            const int64_t col = (int64_t)VEC * (tile * lpr + t);
+            if (b >= s_end[k] || col >= D) continue;
+            const int64_t end = b + kSub < s_end[k] ? b + kSub : s_end[k];
+            const float *base = x + col;
+            Acc<VEC> acc;
+            acc.zero();
+            int64_t e = b;
+            for (; e + kAggInFlight <= end; e += kAggInFlight) {
+                decltype(Acc<VEC>::load(base)) r[kAggInFlight];
+#pragma unroll
+                for (int i = 0; i < kAggInFlight; i++) r[i] = Acc<VEC>::load(base + indices[e + i] * D);
+#pragma unroll
+                for (int i = 0; i < kAggInFlight; i++) acc.add(r[i]);
+            }
+            for (; e < end; e++) acc.add(Acc<VEC>::load(base + indices[e] * D));
+            acc.add_to(out + s_v[k] * D + col, s_deg[k], sum != 0);
+        }
+        __syncthreads();
     }
 }
 
@@ -137,7 +254,7 @@ bool vec_ok(const void *a, const void *b, int64_t D) {
 }  // namespace
 
 hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indptr,
-                                 const int64_t *indices, int64_t V, int sum, float *out,
+                                 const int64_t *indices, int64_t V, int64_t E, int sum, float *out,
                                  hipStream_t s) {
     const bool vec = vec_ok(x, out, D);
     const int64_t granules = vec ? D / 4 : D;
@@ -152,6 +269,16 @@ hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indpt
     else
         aggregate_rows_kernel<1><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, lpr_log2,
                                                             (int)tiles, sum, out);
+    if (E > kLong) {  // otherwise no list is long
+        int64_t lb = (E + kRange - 1) / kRange;
+        if (lb > 8 * 256) lb = 8 * 256;
+        if (vec)
+            aggregate_long_kernel<4><<<(int)lb, kThreads, 0, s>>>(x, D, indptr, indices, V, E, lpr_log2,
+                                                                 (int)tiles, sum, out);
+        else
+            aggregate_long_kernel<1><<<(int)lb, kThreads, 0, s>>>(x, D, indptr, indices, V, E, lpr_log2,
+                                                                 (int)tiles, sum, out);
+    }
     return hipGetLastError();
 }
 

@@ -572,7 +572,7 @@ int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *i
     if (V > 0 && (!indptr || !out || (E > 0 && (!indices || !x || N == 0)))) return BIFEAT_EINVAL;
     if ((uintptr_t)x % 4 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
     if (V == 0) return BIFEAT_OK;
-    BF_HIP(bf::launch_aggregate_rows(x, D, indptr, indices, V, sum != 0, out, (hipStream_t)stream));
+    BF_HIP(bf::launch_aggregate_rows(x, D, indptr, indices, V, E, sum != 0, out, (hipStream_t)stream));
     return BIFEAT_OK;
 }
 
@@ -606,7 +606,7 @@ int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *in
         const float *src = x;
         for (int l = 1; l <= layers && e == hipSuccess; l++) {
             float *dst = work + (size_t)((l - 1) & 1) * (size_t)N * (size_t)D;
-            e = bf::launch_aggregate_rows(src, D, indptr, indices, N, 0, dst, s);
+            e = bf::launch_aggregate_rows(src, D, indptr, indices, N, E, 0, dst, s);
             if (e == hipSuccess) e = bf::launch_row_length_sum(dst, N, D, d_acc + l, s);
             src = dst;
         }

@@ -113,7 +113,7 @@ void launch_validate(const int64_t *idx, int64_t M, int64_t N, const int64_t *in
                      int64_t E, int32_t *d_bad, hipStream_t s);
 // fp32-row neighbourhood mean / sum (layers after the first) and the sum of row lengths
 hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indptr,
-                                 const int64_t *indices, int64_t V, int sum, float *out,
+                                 const int64_t *indices, int64_t V, int64_t E, int sum, float *out,
                                  hipStream_t s);
 hipError_t launch_row_length_sum(const float *h, int64_t n, int64_t D, double *acc, hipStream_t s);
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
