@@ -10,6 +10,7 @@ namespace bf {
 namespace {
 
 constexpr int kAggInFlight = 4;  // rows in flight per lane
+constexpr int kItemsPerGroup = 4;  // (destination, tile) items a lane group works through
 // A list longer than kLong is not walked by one lane group (a hub's thousands of rows,
 // one latency after the other, would outlast the rest of the launch): it is cut into
 // pieces of kSub list entries that many groups sum side by side and add into the output
@@ -17,7 +18,7 @@ constexpr int kAggInFlight = 4;  // rows in flight per lane
 // entries, which at most kRange / kLong + 2 long lists can overlap.
 constexpr int kLong = 256;
 constexpr int kRange = 2048;
-constexpr int kSub = 128;
+constexpr int kSub = 64;
 constexpr int kMaxLong = kRange / kLong + 2;
 
 // Compensated (Kahan) running sums: the rounding error of a sum stays at a couple of
@@ -52,9 +53,6 @@ struct Acc<4> {
         }
         store_stream(reinterpret_cast<float4 *>(p), o);
     }
-    __device__ static void store_zero(float *p) {
-        store_stream(reinterpret_cast<float4 *>(p), make_float4(0.f, 0.f, 0.f, 0.f));
-    }
     // this piece's share of the row: partial sum (divided by the whole list's length)
     __device__ void add_to(float *p, int n, bool sum) const {
         const float d = (float)n;
@@ -73,70 +71,71 @@ struct Acc<1> {
     __device__ void store(float *p, int n, bool sum) const {
         __builtin_nontemporal_store(sum ? v : (n > 0 ? v / (float)n : 0.f), p);
     }
-    __device__ static void store_zero(float *p) { __builtin_nontemporal_store(0.f, p); }
     __device__ void add_to(float *p, int n, bool sum) const {
         unsafeAtomicAdd(p, sum ? v : v / (float)n);
     }
 };
 
-// A group of `lpr` lanes (a power of two up to 64) owns one (destination, column
-// tile) item at a time: lane t of the group accumulates columns
-// VEC*(tile*lpr + t) .. +VEC-1 over the destination's list, in list order (fp32, compensated).  Items
-// are numbered tile-fastest so that neighbouring groups write one contiguous row.
+// rows of `pieces` consecutive list entries [e, end) added into acc, U loads in flight
+template <int VEC, int U>
+__device__ inline void add_rows(Acc<VEC> &acc, const float *__restrict__ base, int64_t D,
+                                const int64_t *__restrict__ indices, int64_t e, int64_t end) {
+    for (; e + U <= end; e += U) {
+        decltype(Acc<VEC>::load(base)) r[U];
+#pragma unroll
+        for (int k = 0; k < U; k++) r[k] = Acc<VEC>::load(base + indices[e + k] * D);
+#pragma unroll
+        for (int k = 0; k < U; k++) acc.add(r[k]);
+    }
+    for (; e < end; e++) acc.add(Acc<VEC>::load(base + indices[e] * D));
+}
+
+// The lists of up to kLong entries.  A group of `lpr` lanes (a power of two up to 64)
+// owns one (destination, column tile) item at a time: lane t of the group accumulates
+// columns VEC*(tile*lpr + t) .. +VEC-1 over the destination's list, in list order
+// (fp32, compensated).  Items are numbered tile-fastest so that neighbouring groups
+// write one contiguous row.  Long lists are left to long_lists().
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(
-    const float *__restrict__ x, int64_t D, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int lpr_log2, int tiles, int sum,
-    float *__restrict__ out) {
+__device__ inline void short_lists(const float *__restrict__ x, int64_t D,
+                                   const int64_t *__restrict__ indptr,
+                                   const int64_t *__restrict__ indices, int64_t V, int lpr_log2,
+                                   int tiles, int sum, float *__restrict__ out, int64_t block,
+                                   int64_t nblocks) {
     const int lpr = 1 << lpr_log2;
     const int t = threadIdx.x & (lpr - 1);
-    const int64_t groups = ((int64_t)gridDim.x * kThreads) >> lpr_log2;
+    const int64_t groups = (nblocks * kThreads) >> lpr_log2;
     const int64_t items = V * tiles;
-    for (int64_t item = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> lpr_log2; item < items;
-         item += groups) {
+    for (int64_t item = (block * kThreads + threadIdx.x) >> lpr_log2; item < items; item += groups) {
         const int64_t v = item / tiles;
         const int tile = (int)(item - v * tiles);
         const int64_t col = (int64_t)VEC * (tile * lpr + t);
-        const bool live = col < D;
         const int64_t beg = indptr[v], end = indptr[v + 1];
+        if (col >= D || end - beg > kLong) continue;
         Acc<VEC> acc;
         acc.zero();
-        if (live && end - beg > kLong) {
-            Acc<VEC>::store_zero(out + v * D + col);  // the pieces are added by the kernel below
-        } else if (live) {
-            const float *base = x + col;
-            int64_t e = beg;
-            for (; e + kAggInFlight <= end; e += kAggInFlight) {
-                decltype(Acc<VEC>::load(base)) r[kAggInFlight];
-#pragma unroll
-                for (int k = 0; k < kAggInFlight; k++) r[k] = Acc<VEC>::load(base + indices[e + k] * D);
-#pragma unroll
-                for (int k = 0; k < kAggInFlight; k++) acc.add(r[k]);
-            }
-            for (; e < end; e++) acc.add(Acc<VEC>::load(base + indices[e] * D));
-            acc.store(out + v * D + col, (int)(end - beg), sum != 0);
-        }
+        add_rows<VEC, kAggInFlight>(acc, x + col, D, indices, beg, end);
+        acc.store(out + v * D + col, (int)(end - beg), sum != 0);
     }
 }
 
-// The long lists: workgroup b looks after list entries [b*kRange, (b+1)*kRange).  It
+// The long lists: a workgroup looks after kRange consecutive list entries at a time.  It
 // finds the first destination whose list reaches into that range (a 64-way search in
 // indptr by one wave), walks on from there, notes the long lists with the part that
-// falls inside the range, and
-// its lane groups sum pieces of kSub entries of those parts, each piece added to the
-// (zeroed) output row.  Launched after the kernel above, on the same stream.
+// falls inside the range, and its lane groups sum pieces of kSub entries of those parts,
+// each piece added to the output row, which aggregate_zero_long_kernel has zeroed.
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void aggregate_long_kernel(
-    const float *__restrict__ x, int64_t D, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int64_t E, int lpr_log2, int tiles, int sum,
-    float *__restrict__ out) {
+__device__ inline void long_lists(const float *__restrict__ x, int64_t D,
+                                  const int64_t *__restrict__ indptr,
+                                  const int64_t *__restrict__ indices, int64_t V, int64_t E,
+                                  int lpr_log2, int tiles, int sum, float *__restrict__ out,
+                                  int64_t block, int64_t nblocks) {
     __shared__ int64_t s_v[kMaxLong], s_beg[kMaxLong], s_end[kMaxLong], s_first;
     __shared__ int s_deg[kMaxLong], s_n;
     const int lpr = 1 << lpr_log2;
     const int t = threadIdx.x & (lpr - 1);
     const int group = threadIdx.x >> lpr_log2, groups = kThreads >> lpr_log2;
     constexpr int kPieces = kRange / kSub;
-    for (int64_t r0 = (int64_t)blockIdx.x * kRange; r0 < E; r0 += (int64_t)gridDim.x * kRange) {
+    for (int64_t r0 = block * kRange; r0 < E; r0 += nblocks * kRange) {
         const int64_t r1 = r0 + kRange < E ? r0 + kRange : E;
         if (threadIdx.x < 64) {
             // first v with indptr[v + 1] > r0: 64 probes a round, evenly spaced over [lo, hi)
@@ -192,21 +191,48 @@ __global__ __launch_bounds__(kThreads) void aggregate_long_kernel(
             const int64_t col = (int64_t)VEC * (tile * lpr + t);
             if (b >= s_end[k] || col >= D) continue;
             const int64_t end = b + kSub < s_end[k] ? b + kSub : s_end[k];
-            const float *base = x + col;
             Acc<VEC> acc;
             acc.zero();
-            int64_t e = b;
-            for (; e + kAggInFlight <= end; e += kAggInFlight) {
-                decltype(Acc<VEC>::load(base)) r[kAggInFlight];
-#pragma unroll
-                for (int i = 0; i < kAggInFlight; i++) r[i] = Acc<VEC>::load(base + indices[e + i] * D);
-#pragma unroll
-                for (int i = 0; i < kAggInFlight; i++) acc.add(r[i]);
-            }
-            for (; e < end; e++) acc.add(Acc<VEC>::load(base + indices[e] * D));
+            add_rows<VEC, 2 * kAggInFlight>(acc, x + col, D, indices, b, end);
             acc.add_to(out + s_v[k] * D + col, s_deg[k], sum != 0);
         }
         __syncthreads();
+    }
+}
+
+// One launch for both: the first `long_blocks` workgroups (dispatched first; their
+// pieces are the longest single chains of the launch) take the long lists, the rest
+// the short ones.  The two write disjoint rows.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(
+    const float *__restrict__ x, int64_t D, const int64_t *__restrict__ indptr,
+    const int64_t *__restrict__ indices, int64_t V, int64_t E, int lpr_log2, int tiles, int sum,
+    int long_blocks, float *__restrict__ out) {
+    if ((int)blockIdx.x < long_blocks)
+        long_lists<VEC>(x, D, indptr, indices, V, E, lpr_log2, tiles, sum, out, blockIdx.x,
+                        long_blocks);
+    else
+        short_lists<VEC>(x, D, indptr, indices, V, lpr_log2, tiles, sum, out,
+                         (int64_t)blockIdx.x - long_blocks, (int64_t)gridDim.x - long_blocks);
+}
+
+// Output rows of the long lists set to zero ahead of the launch above: a lane per
+// destination looks at its list length, the wave then clears each long one's row.
+__global__ __launch_bounds__(kThreads) void aggregate_zero_long_kernel(
+    const int64_t *__restrict__ indptr, int64_t V, int64_t D, float *__restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    // whole waves stay in the loop together: the bound is rounded up to the wave
+    for (int64_t v0 = (int64_t)blockIdx.x * kThreads + (threadIdx.x & ~63); v0 < V; v0 += stride) {
+        const int64_t v = v0 + lane;
+        const bool is_long = v < V && indptr[v + 1] - indptr[v] > kLong;
+        uint64_t m = __ballot(is_long);
+        while (m) {
+            const int j = __ffsll((unsigned long long)m) - 1;
+            m &= m - 1;
+            float *row = out + (v0 + j) * D;
+            for (int64_t c = lane; c < D; c += 64) row[c] = 0.f;
+        }
     }
 }
 
@@ -262,23 +288,22 @@ hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indpt
     while (lpr_log2 < 6 && ((int64_t)1 << lpr_log2) < granules) lpr_log2++;
     const int64_t tiles = (granules + ((int64_t)1 << lpr_log2) - 1) >> lpr_log2;
     const int64_t threads = (V * tiles) << lpr_log2;
-    const int blocks = blocks_for(threads, 8 * 256);
-    if (vec)
-        aggregate_rows_kernel<4><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, lpr_log2,
-                                                            (int)tiles, sum, out);
-    else
-        aggregate_rows_kernel<1><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, lpr_log2,
-                                                            (int)tiles, sum, out);
+    // many small workgroups rather than one resident set: the two kinds of work take turns
+    // on the CUs as slots free up, and no workgroup's share is large enough to form a tail
+    const int short_blocks = blocks_for((threads + kItemsPerGroup - 1) / kItemsPerGroup, 1 << 20);
+    int long_blocks = 0;
     if (E > kLong) {  // otherwise no list is long
-        int64_t lb = (E + kRange - 1) / kRange;
-        if (lb > 8 * 256) lb = 8 * 256;
-        if (vec)
-            aggregate_long_kernel<4><<<(int)lb, kThreads, 0, s>>>(x, D, indptr, indices, V, E, lpr_log2,
-                                                                 (int)tiles, sum, out);
-        else
-            aggregate_long_kernel<1><<<(int)lb, kThreads, 0, s>>>(x, D, indptr, indices, V, E, lpr_log2,
-                                                                 (int)tiles, sum, out);
+        const int64_t ranges = (E + kRange - 1) / kRange;
+        long_blocks = (int)(ranges < (1 << 20) ? ranges : (1 << 20));
+        aggregate_zero_long_kernel<<<blocks_for(V, 8 * 256), kThreads, 0, s>>>(indptr, V, D, out);
     }
+    const int blocks = short_blocks + long_blocks;
+    if (vec)
+        aggregate_rows_kernel<4><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, E, lpr_log2,
+                                                            (int)tiles, sum, long_blocks, out);
+    else
+        aggregate_rows_kernel<1><<<blocks, kThreads, 0, s>>>(x, D, indptr, indices, V, E, lpr_log2,
+                                                            (int)tiles, sum, long_blocks, out);
     return hipGetLastError();
 }
 
