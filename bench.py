@@ -392,6 +392,8 @@ def scale_profile_leg(args, w, q, codes, table):
                                "algorithmic_bytes_per_launch": nbytes,
                                "achieved": round(nbytes / us / 1e3, 1), "peak": HBM_PEAK_GBPS,
                                "unit": "GB/s", "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                               "traffic": traffic_from_profile(args.workload, "aggregate_rows")
+                               if (not args.rows and args.profile_nodes == 1 << 20) else None,
                                "requested_bytes_per_launch": requested,
                                "requested_GBps": round(requested / us / 1e3, 1),
                                "list_entries_per_s": round(E / us * 1e6, 1)}}
