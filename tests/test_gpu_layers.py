@@ -164,3 +164,40 @@ def test_scale_profile_rejects_a_broken_graph(bf, torch):
         bf.scale_profile(x, ptr, idx, 65)
     # the library still works afterwards
     assert np.allclose(bf.scale_profile(x, ptr, idx, 1), 8 ** 0.5)
+
+
+def test_two_layer_chain_replays_from_a_captured_graph(bf, torch):
+    # gather_mean + aggregate_rows enqueue kernels only, so the chain can be captured and
+    # replayed; rows of lists of up to 256 entries are reproduced bit for bit, rows of longer
+    # lists (summed in pieces combined by atomics) to the documented bound
+    N, D = 6000, 128
+    spec = FeatureSpec(N, D, 9)
+    _, _, s, codes = oracle_uniform_table(spec, 4)
+    q = bf.Quantizer(scheme_of("uniform", 4), D)
+    from bifeat_inputs.device import DeviceTable
+    dcodes = gpu_build_table(q, DeviceTable(spec), N, 4096)
+    rng = np.random.default_rng(3)
+    ptr1, idx1 = random_csr(2000, N, 12, rng)
+    ptr2, idx2 = random_csr(700, 2000, 15, rng, hubs=(900,))
+    cu = lambda a: torch.from_numpy(a).cuda()
+    dp1, di1, dp2, di2 = cu(ptr1), cu(idx1), cu(ptr2), cu(idx2)
+    h1 = torch.empty((2000, D), dtype=torch.float32, device="cuda")
+    h2 = torch.empty((700, D), dtype=torch.float32, device="cuda")
+    q.gather_mean(dcodes, dp1, di1, h1)
+    eager = bf.aggregate_rows(h1, dp2, di2).clone()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        q.gather_mean(dcodes, dp1, di1, h1)
+        bf.aggregate_rows(h1, dp2, di2, out=h2)
+    short = torch.from_numpy(np.diff(ptr2) <= 256).cuda()
+    want = orc.aggregate_rows(orc.gather_mean(s, codes, ptr1, idx1), ptr2, idx2)
+    for rep in range(3):
+        h1.fill_(-1.0)
+        h2.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(h2[short], eager[short]), f"replay {rep}"
+        assert torch.allclose(h2[~short], eager[~short], rtol=1e-5, atol=1e-6), f"replay {rep}"
+        assert_close(h2.cpu().numpy(), want, s, f"replay {rep} against the oracle")
+        assert torch.equal(bf.aggregate_rows(h1, dp2, di2)[short], eager[short])
