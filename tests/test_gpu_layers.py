@@ -201,3 +201,43 @@ def test_two_layer_chain_replays_from_a_captured_graph(bf, torch):
         assert torch.allclose(h2[~short], eager[~short], rtol=1e-5, atol=1e-6), f"replay {rep}"
         assert_close(h2.cpu().numpy(), want, s, f"replay {rep} against the oracle")
         assert torch.equal(bf.aggregate_rows(h1, dp2, di2)[short], eager[short])
+
+
+def _csr_from_degrees(deg, N, rng):
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    return indptr, rng.integers(0, N, int(indptr[-1])).astype(np.int64)
+
+
+@pytest.mark.parametrize("case", ["threshold", "packed_longs", "long_first_and_last", "mostly_empty",
+                                  "one_giant", "random_mix"])
+@pytest.mark.parametrize("D", [64, 100, 7])
+def test_aggregate_rows_long_list_layouts(bf, torch, case, D):
+    # lists longer than 256 entries are summed in pieces by workgroups that each look after
+    # 2048 consecutive entries: lengths at the threshold, long lists packed back to back
+    # (as many as fit one range, with both range ends cutting a list), long lists at either
+    # end of the block, long runs of empty lists, one list spanning many ranges
+    rng = np.random.default_rng(len(case) * 1000 + D)
+    N = 5000
+    if case == "threshold":
+        deg = np.array([255, 256, 257, 258, 0, 256, 257, 1, 512, 513, 2048, 2049, 2047, 3], np.int64)
+    elif case == "packed_longs":
+        deg = np.concatenate([[1000], np.full(40, 257), [5], np.full(17, 300), [0, 0, 2], np.full(9, 257)])
+    elif case == "long_first_and_last":
+        deg = np.concatenate([[3000], rng.integers(0, 12, 500), [2600]])
+    elif case == "mostly_empty":
+        deg = np.zeros(6000, np.int64)
+        deg[[0, 1500, 1501, 5999]] = [700, 257, 4000, 300]
+        deg[rng.integers(0, 6000, 200)] = 3
+    elif case == "one_giant":
+        deg = np.concatenate([rng.integers(0, 5, 300), [70001], rng.integers(0, 5, 300)])
+    else:
+        deg = np.where(rng.random(1200) < 0.05, rng.integers(257, 3000, 1200), rng.integers(0, 30, 1200))
+    deg = deg.astype(np.int64)
+    indptr, indices = _csr_from_degrees(deg, N, rng)
+    x = (rng.standard_normal((N, D)) + 0.5).astype(np.float32)
+    dx, dp, di = torch.from_numpy(x).cuda(), torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    for as_sum in (False, True):
+        out = torch.full((deg.shape[0], D), 7.0, dtype=torch.float32, device="cuda")
+        bf.aggregate_rows(dx, dp, di, out=out, sum=as_sum)
+        _assert_rows_close(out.cpu().numpy(), orc.aggregate_rows(x, indptr, indices, sum=as_sum),
+                           x, indptr, indices, as_sum, f"{case} D={D} sum={as_sum}")
