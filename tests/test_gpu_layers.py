@@ -241,3 +241,28 @@ def test_aggregate_rows_long_list_layouts(bf, torch, case, D):
         bf.aggregate_rows(dx, dp, di, out=out, sum=as_sum)
         _assert_rows_close(out.cpu().numpy(), orc.aggregate_rows(x, indptr, indices, sum=as_sum),
                            x, indptr, indices, as_sum, f"{case} D={D} sum={as_sum}")
+
+
+@pytest.mark.timeout(600)
+def test_scale_profile_at_bench_size(bf, torch):
+    # the configuration `bench.py --workload mid --scale-profile 2` runs: the mid workload's
+    # graph family over 2^20 nodes with self-loops, D = 100
+    from bifeat_inputs import WORKLOADS
+    w = WORKLOADS["mid"]
+    n = 1 << 20
+    g = PowerLawGraph(n, w.avg_degree, 2.1, w.cap, w.seed)
+    indptr, indices = full_csr(g)
+    x = feature_chunk(FeatureSpec(n, w.D, w.seed), 0, n)
+    x = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32)
+    dx, dp, di = torch.from_numpy(x).cuda(), torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    got = bf.scale_profile(dx, dp, di, 2)
+    want = orc.scale_profile(x, indptr, indices, 2)
+    assert np.allclose(got, want, rtol=REL_TOL, atol=0), (got, want)
+    # one round, element by element, on a sample of destinations that includes the longest lists
+    h1 = bf.aggregate_rows(dx, dp, di)
+    deg = np.diff(indptr)
+    sample = np.unique(np.concatenate([np.argsort(deg)[-8:], np.random.default_rng(1).integers(0, n, 300)]))
+    sub_ptr = np.concatenate([[0], np.cumsum(deg[sample])]).astype(np.int64)
+    sub_idx = np.concatenate([indices[indptr[v]:indptr[v + 1]] for v in sample])
+    _assert_rows_close(h1[torch.from_numpy(sample).cuda()].cpu().numpy(),
+                       orc.aggregate_rows(x, sub_ptr, sub_idx), x, sub_ptr, sub_idx, False, "bench size")
