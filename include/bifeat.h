@@ -231,6 +231,14 @@ int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *i
                           const int64_t *indices, int64_t V, int64_t E, int32_t sum, float *out,
                           void *stream);
 
+/* The index contract of the calls above, checked on its own (bifeat_aggregate_rows has
+ * no parameter object to carry the "validate" option): 0 <= indices[e] < N for all
+ * e < E and, when indptr is not NULL, indptr[0] == 0, indptr non-decreasing,
+ * indptr[V] == E.  DEVICE pointers.  Returns BIFEAT_OK or BIFEAT_EINVAL; allocates a few
+ * bytes of device memory and synchronises `stream`. */
+int bifeat_check_lists(const int64_t *indptr, const int64_t *indices, int64_t V, int64_t E,
+                       int64_t N, void *stream);
+
 /* ---- the aggregation scale profile (Appendix A.1 defines C^e_{i,l} and
  * C^f_{i,l}, the factors by which l rounds of averaging shrink independent
  * errors and correlated features; Appendix A.3 their ratio of means C^_L;

@@ -6,9 +6,9 @@ streams only; every step of the path runs in the library's kernels.  There is
 no CPU fallback: if the library is missing, loading fails.
 """
 from .binding import (Quantizer, Scheme, BifeatError, load_library, library_path,
-                      aggregate_rows, scale_profile,
+                      aggregate_rows, scale_profile, check_lists,
                       UNIFORM, LOG, VQ, VQ_L2, VQ_COSINE, F32, F16)
 
 __all__ = ["Quantizer", "Scheme", "BifeatError", "load_library", "library_path",
-           "aggregate_rows", "scale_profile",
+           "aggregate_rows", "scale_profile", "check_lists",
            "UNIFORM", "LOG", "VQ", "VQ_L2", "VQ_COSINE", "F32", "F16"]

@@ -69,6 +69,7 @@ _SIGNATURES = {
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_aggregate_rows": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]),
+    "bifeat_check_lists": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p]),
     "bifeat_scale_profile": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "bifeat_strerror": (C.c_char_p, [C.c_int]),
@@ -306,3 +307,16 @@ def scale_profile(x, indptr, indices, layers: int, work=None):
         _dev_ptr(indices, (torch.int64,)), indices.shape[0], layers,
         _dev_ptr(work, (torch.float32,)), _np_ptr(scale), _stream()))
     return scale
+
+
+def check_lists(indptr, indices, N: int) -> bool:
+    """``bifeat_check_lists``: True if the CSR lists (``indptr`` may be None for a plain
+    index array) satisfy the index contract of the gather calls for a table of N rows."""
+    import torch
+    V = 0 if indptr is None else indptr.shape[0] - 1
+    rc = load_library().bifeat_check_lists(_dev_ptr(indptr, (torch.int64,)), _dev_ptr(indices, (torch.int64,)),
+                                           V, indices.shape[0], N, _stream())
+    if rc == EINVAL:
+        return False
+    _check(rc)
+    return True

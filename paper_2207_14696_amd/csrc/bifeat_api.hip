@@ -576,6 +576,21 @@ int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *i
     return BIFEAT_OK;
 }
 
+int bifeat_check_lists(const int64_t *indptr, const int64_t *indices, int64_t V, int64_t E,
+                       int64_t N, void *stream) {
+    if (V < 0 || E < 0 || N < 0 || (E > 0 && !indices) || (V > 0 && !indptr)) return BIFEAT_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *d_bad = nullptr, bad = 0;
+    BF_HIP(hipMalloc((void **)&d_bad, sizeof(int32_t)));
+    bf::launch_validate(indices, E, N, indptr, indptr ? V : 0, E, d_bad, s);
+    hipError_t e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    const hipError_t ef = hipFree(d_bad);
+    if (e != hipSuccess) return hip_fail(e, "bifeat_check_lists");
+    if (ef != hipSuccess) return hip_fail(ef, "hipFree");
+    return bad ? BIFEAT_EINVAL : BIFEAT_OK;
+}
+
 int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *indptr,
                          const int64_t *indices, int64_t E, int32_t layers, float *work,
                          double *scale, void *stream) {

@@ -70,6 +70,8 @@ def test_argument_errors_come_before_any_gpu_call(bf):
     assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 65, 16, 16, None) == -1    # too many layers
     assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 2, None, 16, None) == -1   # no work buffer
     assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 2, 16, None, None) == -1   # no result array
+    assert lib.bifeat_check_lists(None, None, 3, 5, 10, None) == -1                  # no arrays
+    assert lib.bifeat_check_lists(16, 16, -1, 5, 10, None) == -1
     assert lib.bifeat_set_option(h, b"no_such_option", 1) == -1
     assert lib.bifeat_set_option(h, b"mean_slots", 4) == 0
     assert lib.bifeat_row_bytes(None) == -1

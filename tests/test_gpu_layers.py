@@ -266,3 +266,17 @@ def test_scale_profile_at_bench_size(bf, torch):
     sub_idx = np.concatenate([indices[indptr[v]:indptr[v + 1]] for v in sample])
     _assert_rows_close(h1[torch.from_numpy(sample).cuda()].cpu().numpy(),
                        orc.aggregate_rows(x, sub_ptr, sub_idx), x, sub_ptr, sub_idx, False, "bench size")
+
+
+def test_check_lists(bf, torch):
+    ptr = torch.tensor([0, 2, 2, 5], dtype=torch.int64, device="cuda")
+    idx = torch.tensor([4, 0, 9, 9, 3], dtype=torch.int64, device="cuda")
+    assert bf.check_lists(ptr, idx, 10)
+    assert bf.check_lists(None, idx, 10)
+    assert not bf.check_lists(ptr, idx, 9)                        # 9 is out of range for 9 rows
+    assert not bf.check_lists(None, torch.tensor([0, -1], dtype=torch.int64, device="cuda"), 10)
+    assert not bf.check_lists(torch.tensor([0, 3, 2, 5], dtype=torch.int64, device="cuda"), idx, 10)
+    assert not bf.check_lists(torch.tensor([1, 2, 2, 5], dtype=torch.int64, device="cuda"), idx, 10)
+    assert not bf.check_lists(torch.tensor([0, 2, 2, 4], dtype=torch.int64, device="cuda"), idx, 10)
+    assert bf.check_lists(torch.zeros(1, dtype=torch.int64, device="cuda"),
+                          torch.zeros(0, dtype=torch.int64, device="cuda"), 10)
