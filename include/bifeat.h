@@ -33,8 +33,10 @@
  *   - Row indices must satisfy 0 <= idx < N, indptr must be non-decreasing with
  *     indptr[0] = 0 and indptr[V] = E; this is the caller's contract and is not
  *     checked on the GPU - unless option "validate" = 1 is set: every gather
- *     call then first checks it with a small kernel, synchronises `stream`,
- *     and returns BIFEAT_EINVAL without launching the gather when it is broken.
+ *     call then first checks it (and, for gather_mean / gather_sum, a bound
+ *     promised through option "mean_max_degree") with a small kernel,
+ *     synchronises `stream`, and returns BIFEAT_EINVAL without launching the
+ *     gather when it is broken.
  *   - Packed layout (the paper fixes none; Appendix C only advises against
  *     elaborate bit packing): row-major; scalar codes: column j's `bits`-bit
  *     code at bit (j*bits) mod 8 of byte floor(j*bits/8), column 0 in the
@@ -272,7 +274,8 @@ const char *bifeat_strerror(int status);
  * "mean_max_degree" = d is the caller's promise that no neighbour list of the
  * following bifeat_gather_mean calls is longer than d (0 = unknown; a sampler
  * knows its fan-out), which lets the library skip the pass that looks for
- * longer lists (a list that breaks the promise leaves its output row unwritten);
+ * longer lists (a list that breaks the promise leaves its output row unwritten;
+ * "validate" checks the promise too);
  * "vq_iters" = Lloyd rounds per training chunk (1..64); "validate" = 1 checks
  * the index contract of every gather call on the GPU first (see above).
  * Unknown names return BIFEAT_EINVAL. */

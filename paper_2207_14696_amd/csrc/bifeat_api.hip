@@ -513,7 +513,8 @@ int check_inputs(bifeat_params *p, const int64_t *idx, int64_t M, int64_t N, con
     int rc = ensure_device(p);
     if (rc) return rc;
     int32_t *d_bad = reinterpret_cast<int32_t *>(p->d_zero + 64);  // word after the zero row
-    bf::launch_validate(idx, M, N, indptr, V, E, d_bad, s);
+    // a promised bound on the list lengths (option mean_max_degree) is part of the contract
+    bf::launch_validate(idx, M, N, indptr, V, E, indptr ? p->opt_mean_max_degree : 0, d_bad, s);
     int32_t bad = 0;
     BF_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s));
     BF_HIP(hipStreamSynchronize(s));
@@ -582,7 +583,7 @@ int bifeat_check_lists(const int64_t *indptr, const int64_t *indices, int64_t V,
     hipStream_t s = (hipStream_t)stream;
     int32_t *d_bad = nullptr, bad = 0;
     BF_HIP(hipMalloc((void **)&d_bad, sizeof(int32_t)));
-    bf::launch_validate(indices, E, N, indptr, indptr ? V : 0, E, d_bad, s);
+    bf::launch_validate(indices, E, N, indptr, indptr ? V : 0, E, 0, d_bad, s);
     hipError_t e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     const hipError_t ef = hipFree(d_bad);
@@ -612,7 +613,7 @@ int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *in
     hipError_t e = hipMemsetAsync(d_acc, 0, bytes, s);
     if (e == hipSuccess) {
         int32_t *d_bad = reinterpret_cast<int32_t *>(d_acc + layers + 1);
-        bf::launch_validate(indices, E, N, indptr, N, E, d_bad, s);
+        bf::launch_validate(indices, E, N, indptr, N, E, 0, d_bad, s);
         e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(s);

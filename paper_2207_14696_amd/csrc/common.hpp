@@ -108,9 +108,10 @@ template <typename T>
 void launch_vq_assign(bifeat_params *p, const T *x, int64_t rows, uint8_t *codes_row0, int64_t rb,
                       hipStream_t s);
 // counts violations of 0 <= idx[i] < N (and, with indptr, of indptr[0] == 0, indptr
-// non-decreasing, indptr[V] == E) into *d_bad (zeroed first)
+// non-decreasing, indptr[V] == E, no list longer than max_len if that is positive) into
+// *d_bad (zeroed first)
 void launch_validate(const int64_t *idx, int64_t M, int64_t N, const int64_t *indptr, int64_t V,
-                     int64_t E, int32_t *d_bad, hipStream_t s);
+                     int64_t E, int64_t max_len, int32_t *d_bad, hipStream_t s);
 // fp32-row neighbourhood mean / sum (layers after the first) and the sum of row lengths
 hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indptr,
                                  const int64_t *indices, int64_t V, int64_t E, int sum, float *out,

@@ -182,24 +182,26 @@ __global__ void validate_zero_kernel(int32_t *bad) { *bad = 0; }
 __global__ __launch_bounds__(kThreads) void validate_kernel(const int64_t *__restrict__ idx, int64_t M,
                                                            int64_t N,
                                                            const int64_t *__restrict__ indptr,
-                                                           int64_t V, int64_t E, int32_t *bad) {
+                                                           int64_t V, int64_t E, int64_t max_len,
+                                                           int32_t *bad) {
     int wrong = 0;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < M; i += stride)
         wrong |= idx[i] < 0 || idx[i] >= N;
     if (indptr) {
         for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < V; v += stride)
-            wrong |= indptr[v] > indptr[v + 1] || indptr[v] < 0;
+            wrong |= indptr[v] > indptr[v + 1] || indptr[v] < 0 ||
+                     (max_len > 0 && indptr[v + 1] - indptr[v] > max_len);
         if (blockIdx.x == 0 && threadIdx.x == 0) wrong |= indptr[0] != 0 || indptr[V] != E;
     }
     if (wrong) atomicOr(bad, 1);
 }
 
 void launch_validate(const int64_t *idx, int64_t M, int64_t N, const int64_t *indptr, int64_t V,
-                     int64_t E, int32_t *d_bad, hipStream_t s) {
+                     int64_t E, int64_t max_len, int32_t *d_bad, hipStream_t s) {
     validate_zero_kernel<<<1, 1, 0, s>>>(d_bad);
     const int64_t n = M > V ? M : V;
-    validate_kernel<<<blocks_for(n > 0 ? n : 1), kThreads, 0, s>>>(idx, M, N, indptr, V, E, d_bad);
+    validate_kernel<<<blocks_for(n > 0 ? n : 1), kThreads, 0, s>>>(idx, M, N, indptr, V, E, max_len, d_bad);
 }
 
 // vector codes: columns 4g..4g+3 of part p = col / w come from entry q = index p of

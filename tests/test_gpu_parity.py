@@ -551,6 +551,13 @@ def test_validate_option_rejects_broken_index_contracts(bf, torch):
             q.gather_mean(dcodes, p_, i_)
         with pytest.raises(bf.BifeatError):
             q.gather_sum(dcodes, p_, i_)
+    # a promised bound on the list lengths is checked as part of the contract
+    q.set_option("mean_max_degree", 2)
+    assert_close(q.gather_mean(dcodes, ptr, ind).cpu().numpy(), want, s)     # lists of 2 and 1
+    q.set_option("mean_max_degree", 1)
+    with pytest.raises(bf.BifeatError):
+        q.gather_mean(dcodes, ptr, ind)
+    q.set_option("mean_max_degree", 0)
     q.set_option("validate", 0)
 
 
