@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="mid",
-                    choices=["tiny", "mid", "large", "largest1", "largest4", "vq", "vq2k", "log2", "log1"])
+                    choices=["tiny", "mid", "large", "largest1", "largest4", "vq", "vq2k", "log2", "log4", "log1"])
     ap.add_argument("--rows", type=int, default=0, help="override N (debugging)")
     ap.add_argument("--batches", type=int, default=0, help="distinct pre-sampled launch-sets")
     ap.add_argument("--batches-per-step", type=int, default=0)

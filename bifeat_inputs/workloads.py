@@ -60,6 +60,9 @@ WORKLOADS = {
     # "large" table and sampling
     "log2": Workload("log2", 111_000_000, 128, "f32", "log", 2, "powerlaw", 15, (15, 10, 5), 1024,
                      seed_mode="degree", log_clip=0.01),
+    # the same codes at 4 bits (a sixteen-entry decode table per value: no integer-sum form)
+    "log4": Workload("log4", 111_000_000, 128, "f32", "log", 4, "powerlaw", 15, (15, 10, 5), 1024,
+                     seed_mode="degree", log_clip=0.01),
     # the paper's large-graph vector setting (Appendix B: width 16, length 2048, i.e.
     # two-byte indices, cosine search) on the "large" table and sampling
     "vq2k": Workload("vq2k", 111_000_000, 128, "f32", "vq", 8, "powerlaw", 15, (15, 10, 5), 1024,
@@ -76,7 +79,7 @@ def make_graph(w: Workload):
 # minibatches concatenated into one launch by default (what a prefetching
 # loader hands over); 1 = a single minibatch per launch
 BATCHES_PER_STEP = {"tiny": 64, "mid": 64, "large": 8, "largest1": 32, "largest4": 32, "vq": 8,
-                    "vq2k": 8, "log2": 8, "log1": 32}
+                    "vq2k": 8, "log2": 8, "log4": 8, "log1": 32}
 
 
 def launch_set(w: Workload, graph, set_index: int, L: int):

@@ -123,6 +123,10 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const 
                                   const int64_t *indices, int64_t V, int64_t E, float *out,
                                   hipStream_t s);
 int lean_capacity(int bits, bool wide);
+// logarithmic codes of 4 / 8 bits, lists of at most logf_capacity() neighbours
+int logf_capacity();
+bool launch_gather_mean_logf(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
+                             const int64_t *indices, int64_t V, float *out, int thr, hipStream_t s);
 bool launch_gather_mean_lean_log2(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                                   const int64_t *indices, int64_t V, float *out, int thr, bool wide,
                                   hipStream_t s);

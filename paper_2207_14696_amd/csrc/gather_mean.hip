@@ -171,6 +171,18 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
         const bool all_short = lean && p->opt_mean_max_degree > 0;
         if (!all_short)
             launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, lean ? thr : -1);
+    } else if (kind == BIFEAT_SQ_LOG && (p->scheme.bits == 4 || p->scheme.bits == 8) && vec &&
+               !p->opt_mean_generic) {
+        // short lists: the look-up kernel with whole 16-byte code loads; longer lists: the
+        // general kernel, each skipping the other's destinations
+        const int64_t avg = V > 0 ? E / V : 0;
+        const int64_t need = p->opt_mean_max_degree > 0 ? p->opt_mean_max_degree : 2 * avg;
+        const int thr = logf_capacity();
+        const bool tiled = p->opt_mean_lean && V > 0 && need <= thr &&
+                           launch_gather_mean_logf(p, codes, indptr, indices, V, out, thr, s);
+        const bool all_short = tiled && p->opt_mean_max_degree > 0;
+        if (!all_short)
+            launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, tiled ? thr : -1);
     } else if (kind == BIFEAT_SQ_LOG) {
         launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s);
     } else if (p->opt_vq_sliced && launch_gather_mean_vq_sliced(p, codes, indptr, indices, V, E, out, s)) {

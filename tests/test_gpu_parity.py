@@ -162,6 +162,7 @@ def _tables(bf, torch, kind, bits, D, N=6007, w=8, length=32, seed=6):
 CASES = [("uniform", 1, 768), ("uniform", 2, 128), ("uniform", 4, 100), ("uniform", 8, 128),
          ("uniform", 4, 37), ("uniform", 8, 5), ("uniform", 1, 70), ("uniform", 2, 1),
          ("log", 1, 64), ("log", 1, 768), ("log", 2, 100), ("log", 4, 37), ("log", 8, 16),
+         ("log", 4, 128), ("log", 4, 100), ("log", 4, 768), ("log", 8, 200), ("log", 8, 1024),
          ("vq", 8, 64), ("vq", 8, 100), ("vq", 8, 23), ("vq", 8, 96)]
 
 
@@ -199,13 +200,18 @@ def test_gather_mean(bf, torch, kind, bits, D):
     q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, w=w)
     rng = np.random.default_rng(1)
     # long lists cross the integer-accumulator capacity of every bit width
-    hubs = (90, 300, 700, 4500) if kind == "uniform" else (300,)
+    # (64 / 65: either side of the look-up kernel's limit for 4- and 8-bit logarithmic codes)
+    hubs = (90, 300, 700, 4500) if kind == "uniform" else (40, 64, 65, 300)
     indptr, indices = random_csr(1501, codes.shape[0], 30, rng, hubs=hubs)
     want = orc.gather_mean(s, codes, indptr, indices)
     dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
     got = q.gather_mean(dcodes, dptr, dind).cpu().numpy()
     assert not got[0].any()
     assert_close(got, want, s, "gather_mean")
+    if kind == "log":
+        q.set_option("mean_generic", 1)
+        assert_close(q.gather_mean(dcodes, dptr, dind).cpu().numpy(), want, s, "general kernel only")
+        q.set_option("mean_generic", 0)
     if kind == "uniform":
         for slots in (1, 2, 8, 64):
             q.set_option("mean_slots", slots)

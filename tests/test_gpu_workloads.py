@@ -269,3 +269,24 @@ def test_log_2bit_clipped(torch, bf):
         encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
     del codes
     torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(900)
+def test_log_4bit(torch, bf):
+    # the same codes at 4 bits: a sixteen-entry decode table, the look-up mean kernel.  The
+    # range is taken from a sample of the table (any range serves the parity of codes,
+    # decoded rows and means; the clipped fit itself is pinned by the 2-bit workload)
+    w = WORKLOADS["log4"]
+    e_min, e_max = orc.log_range_clipped(feature_chunk(w.spec, 0, 200_000).astype(np.float32), w.log_clip)
+    q = bf.Quantizer(scheme_of("log", w.bits), w.D)
+    q.params_set_log(e_min, e_max)
+    oT, oV = orc.log_tables(e_min, e_max, w.bits)
+    _, _, T, V = q.params_get_log()
+    assert np.array_equal(T, oT) and np.array_equal(V, oV)
+    (codes,), *_ = _stream_table(torch, w, [q], fit=False)
+    _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
+        encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
+    del codes
+    torch.cuda.empty_cache()
