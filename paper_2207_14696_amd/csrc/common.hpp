@@ -129,10 +129,10 @@ bool launch_gather_mean_logf(bifeat_params *p, const uint8_t *codes, const int64
                              const int64_t *indices, int64_t V, float *out, int thr, hipStream_t s);
 bool launch_gather_mean_lean_log2(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                                   const int64_t *indices, int64_t V, float *out, int thr, bool wide,
-                                  hipStream_t s);
+                                  int lo, hipStream_t s);
 bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                              const int64_t *indices, int64_t V, float *out, int thr, bool wide,
-                             hipStream_t s);
+                             int lo, hipStream_t s);
 
 // ---- order-preserving float <-> int keys for atomic min/max
 __host__ __device__ inline int32_t float_key(float f) {

@@ -154,9 +154,19 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
         const bool wide = need > lean_capacity(p->scheme.bits, false);
         const int thr = lean_capacity(p->scheme.bits, wide);
         const bool lean = p->opt_mean_lean && p->opt_mean_slots == 0 && vec && V > 0 && need <= thr &&
-                          launch_gather_mean_lean(p, codes, indptr, indices, V, out, thr, wide, s);
+                          launch_gather_mean_lean(p, codes, indptr, indices, V, out, thr, wide, -1, s);
         const bool all_short = lean && p->opt_mean_max_degree > 0;
-        if (!all_short) launch_gather_mean_swar(p, codes, indptr, indices, V, E, out, vec, lean ? thr : -1, s);
+        if (!all_short) {
+            // Without the caller's bound the narrow form was chosen on the average alone: the
+            // lists between its capacity and the wide form's (a sampler's fan-out sits there
+            // when most lists are full) go to the wide form, not to the general kernel.
+            int covered = lean ? thr : -1;
+            const int thr_wide = lean_capacity(p->scheme.bits, true);
+            if (lean && !wide && thr_wide > thr &&
+                launch_gather_mean_lean(p, codes, indptr, indices, V, out, thr_wide, true, thr, s))
+                covered = thr_wide;
+            launch_gather_mean_swar(p, codes, indptr, indices, V, E, out, vec, covered, s);
+        }
     } else if (kind == BIFEAT_SQ_UNIFORM) {
         launch_float<MK_UNIFORM>(p, codes, indptr, indices, V, p->d_min, p->d_scale, out, vec, s);
     } else if (kind == BIFEAT_SQ_LOG && p->scheme.bits == 2 && vec && D <= 1024 && !p->opt_mean_generic) {
@@ -167,10 +177,16 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
         const bool wide = need > lean_capacity(1, false);
         const int thr = lean_capacity(1, wide);
         const bool lean = p->opt_mean_lean && V > 0 && need <= thr &&
-                          launch_gather_mean_lean_log2(p, codes, indptr, indices, V, out, thr, wide, s);
+                          launch_gather_mean_lean_log2(p, codes, indptr, indices, V, out, thr, wide, -1, s);
         const bool all_short = lean && p->opt_mean_max_degree > 0;
-        if (!all_short)
-            launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, lean ? thr : -1);
+        if (!all_short) {
+            int covered = lean ? thr : -1;
+            const int thr_wide = lean_capacity(1, true);
+            if (lean && !wide && thr_wide > thr &&
+                launch_gather_mean_lean_log2(p, codes, indptr, indices, V, out, thr_wide, true, thr, s))
+                covered = thr_wide;
+            launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, covered);
+        }
     } else if (kind == BIFEAT_SQ_LOG && (p->scheme.bits == 4 || p->scheme.bits == 8) && vec &&
                !p->opt_mean_generic) {
         // short lists: the look-up kernel with whole 16-byte code loads; longer lists: the

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
     const int64_t *__restrict__ indices, int64_t V, int D, int Dp, const float *__restrict__ mn,
     const float *__restrict__ sc, const uint8_t *__restrict__ zero_row, float *__restrict__ out,
-    int lpr_log2, int chunks, int thr) {
+    int lpr_log2, int chunks, int thr, int lo) {
     using W = LeanSwar<BITS, WIDE>;
     constexpr int R = CW * W::kN;   // accumulator registers per lane
     constexpr int CPW = 32 / BITS;  // codes per word
@@ -131,7 +131,9 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
             end = indptr[v_tile + d_local + 1];
         }
         const int64_t n64 = end - beg;
-        const bool mine = d_local < ndst && n64 <= thr;  // longer lists: the general kernel
+        // longer lists: the general kernel; lists of up to `lo`: an earlier launch of the narrow form
+        const bool mine = d_local < ndst && n64 <= thr && n64 > lo;
+        if (__ballot(mine) == 0) continue;  // nothing for this launch in the tile
         const int n = mine ? (int)n64 : 0;
         if (lane_chunk == 0)
             meta[d_local] = mine ? (n > 0 ? (SUM ? (float)n : 1.0f / (float)n) : 0.0f) : -1.0f;
@@ -277,7 +279,7 @@ inline int ilog2(int x) {
 
 template <int BITS, bool WIDE, bool PAIR>
 bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                      const int64_t *indices, int64_t V, float *out, int thr, const float *mn,
+                      const int64_t *indices, int64_t V, float *out, int thr, int lo, const float *mn,
                       const float *sc, hipStream_t s) {
     using W = LeanSwar<BITS, WIDE>;
     const int64_t rb = p->rb;
@@ -309,11 +311,11 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
         if (p->agg_sum)                                                                          \
             gather_mean_lean_kernel<BITS, CWV, WIDE, true, PAIR><<<blocks, kThreads, shm, s>>>(  \
                 codes, (uint32_t)rb, indptr, indices, V, D, Dp, mn, sc, p->d_zero, out,          \
-                ilog2(lpr), chunks, thr);                                                        \
+                ilog2(lpr), chunks, thr, lo);                                                        \
         else                                                                                     \
             gather_mean_lean_kernel<BITS, CWV, WIDE, false, PAIR><<<blocks, kThreads, shm, s>>>( \
                 codes, (uint32_t)rb, indptr, indices, V, D, Dp, mn, sc, p->d_zero, out,          \
-                ilog2(lpr), chunks, thr);                                                        \
+                ilog2(lpr), chunks, thr, lo);                                                        \
     } while (0)
     switch (cw) {
         case 4: BF_LN(4); break;
@@ -327,22 +329,22 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
 
 }  // namespace
 
-// Launches the short-list kernel (lists of at most `thr` rows; wide = the form
-// with the larger field capacity); returns false (nothing launched) when the
+// Launches the short-list kernel (lists of more than `lo` and at most `thr` rows; wide =
+// the form with the larger field capacity); returns false (nothing launched) when the
 // table's shape is outside what it handles.
 bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, float *out, int thr, bool wide,
+                             const int64_t *indices, int64_t V, float *out, int thr, bool wide, int lo,
                              hipStream_t s) {
     const float *mn = p->d_min, *sc = p->d_scale;
     switch (p->scheme.bits) {
         case 1:
-            return wide ? launch_lean_bits<1, true, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s)
-                        : launch_lean_bits<1, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
-        case 2: return launch_lean_bits<2, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
+            return wide ? launch_lean_bits<1, true, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s)
+                        : launch_lean_bits<1, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
+        case 2: return launch_lean_bits<2, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
         case 4:
-            return wide ? launch_lean_bits<4, true, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s)
-                        : launch_lean_bits<4, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
-        default: return launch_lean_bits<8, false, false>(p, codes, indptr, indices, V, out, thr, mn, sc, s);
+            return wide ? launch_lean_bits<4, true, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s)
+                        : launch_lean_bits<4, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
+        default: return launch_lean_bits<8, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
     }
 }
 
@@ -355,10 +357,10 @@ bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64
 // 2*D entries each), and the epilogue adds each pair.
 bool launch_gather_mean_lean_log2(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
                                   const int64_t *indices, int64_t V, float *out, int thr, bool wide,
-                                  hipStream_t s) {
-    return wide ? launch_lean_bits<1, true, true>(p, codes, indptr, indices, V, out, thr, p->d_min,
+                                  int lo, hipStream_t s) {
+    return wide ? launch_lean_bits<1, true, true>(p, codes, indptr, indices, V, out, thr, lo, p->d_min,
                                                   p->d_scale, s)
-                : launch_lean_bits<1, false, true>(p, codes, indptr, indices, V, out, thr, p->d_min,
+                : launch_lean_bits<1, false, true>(p, codes, indptr, indices, V, out, thr, lo, p->d_min,
                                                    p->d_scale, s);
 }
 

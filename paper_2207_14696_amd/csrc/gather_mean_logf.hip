@@ -67,6 +67,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
         }
         const int64_t n64 = end - beg;
         const bool mine = d_local < ndst && n64 <= thr;  // longer lists: the general kernel
+        if (__ballot(mine) == 0) continue;               // nothing for this launch in the tile
         const int n = mine ? (int)n64 : 0;
         if (lane_chunk == 0)
             meta[d_local] = mine ? (n > 0 ? (agg_sum ? 1.0f : 1.0f / (float)n) : 0.0f) : -1.0f;

@@ -269,13 +269,17 @@ def test_argument_errors(bf, torch):
     assert e.value.status == -1                       # fewer sample rows than codebook entries
 
 
-@pytest.mark.parametrize("bits,D", [(1, 768), (2, 128), (4, 100), (8, 128), (4, 768), (1, 64), (8, 4)])
-def test_gather_mean_short_lists_take_two_kernels(bf, torch, bits, D):
-    # sampled-block shape: short lists (the lean kernel) with a few long ones mixed
-    # in (left to the general kernel, which skips the short ones)
-    q, s, codes, dcodes = _tables(bf, torch, "uniform", bits, D, N=4001)
+@pytest.mark.parametrize("kind,bits,D", [("uniform", 1, 768), ("uniform", 2, 128), ("uniform", 4, 100),
+                                         ("uniform", 8, 128), ("uniform", 4, 768), ("uniform", 1, 64),
+                                         ("uniform", 8, 4), ("log", 2, 128), ("log", 1, 256), ("log", 4, 128)])
+def test_gather_mean_short_lists_take_two_kernels(bf, torch, kind, bits, D):
+    # sampled-block shape: short lists (the short-list kernel, chosen on the average length)
+    # with longer ones mixed in: up to 64 they go to the short-list kernel's wide form where
+    # there is one (15 / 17 are the narrow forms' capacities), beyond that to the general
+    # kernel; each launch skips the others' destinations
+    q, s, codes, dcodes = _tables(bf, torch, kind, bits, D, N=4001)
     rng = np.random.default_rng(3)
-    indptr, indices = random_csr(2307, codes.shape[0], 10, rng, hubs=(16, 18, 40, 300))
+    indptr, indices = random_csr(2307, codes.shape[0], 10, rng, hubs=(15, 16, 17, 18, 40, 64, 65, 300))
     want = orc.gather_mean(s, codes, indptr, indices)
     dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
     out = torch.full((2307, D), float("nan"), device="cuda")
