@@ -1,5 +1,7 @@
 """Seeded random configurations (shape, scheme, bit width, list lengths) through the whole
 path against the oracle: the shape classes the hand-picked cases do not name."""
+import os
+
 import numpy as np
 import pytest
 
@@ -9,6 +11,9 @@ from bifeat_inputs.device import DeviceTable
 from helpers import scheme_of, assert_close, column_magnitude, REL_TOL, random_csr, gpu_build_table
 
 pytestmark = pytest.mark.gpu
+
+# BIFEAT_TEST_SEED=k shifts every seed below: further draws of the same distributions
+SEED = 100_000 * int(os.environ.get("BIFEAT_TEST_SEED", "0"))
 
 
 @pytest.fixture(scope="module")
@@ -39,11 +44,11 @@ def _draw(rng):
 
 @pytest.mark.parametrize("case", range(72))
 def test_random_configuration(bf, torch, case):
-    rng = np.random.default_rng(1000 + case)
+    rng = np.random.default_rng(SEED + 1000 + case)
     c = _draw(rng)
     N = int(rng.integers(700, 2500))
     D = c["D"]
-    spec = FeatureSpec(N, D, 100 + case, c["dtype"])
+    spec = FeatureSpec(N, D, SEED + 100 + case, c["dtype"])
     x = feature_chunk(spec, 0, N).astype(np.float32)
     if c["kind"] == "uniform":
         mn, mx = orc.fit_minmax(x)
@@ -122,7 +127,7 @@ def _build(bf, torch, c, N, seed):
 def test_small_requests_and_fanout_bounds(bf, torch, case):
     # tiny requests (one row, one destination, a few tiles and a ragged tail) and sampled
     # blocks whose fan-out the caller states, for random configurations
-    rng = np.random.default_rng(5000 + case)
+    rng = np.random.default_rng(SEED + 5000 + case)
     c = _draw(rng)
     if c["D"] > 600:
         c["D"] = int(rng.choice([8, 96, 128]))
@@ -161,11 +166,11 @@ def test_small_requests_and_fanout_bounds(bf, torch, case):
 @pytest.mark.parametrize("case", range(24))
 def test_random_fits(bf, torch, case):
     # streaming fits with random chunking, special values in the table
-    rng = np.random.default_rng(9000 + case)
+    rng = np.random.default_rng(SEED + 9000 + case)
     D = int(rng.choice([1, 5, 32, 100, 257, 768]))
     N = int(rng.integers(200, 3000))
     dtype = str(rng.choice(["f32", "f16"]))
-    spec = FeatureSpec(N, D, 900 + case, dtype)
+    spec = FeatureSpec(N, D, SEED + 900 + case, dtype)
     x = feature_chunk(spec, 0, N).astype(np.float32)
     # sprinkle zeros, NaNs and infinities (NaNs are skipped by the fits; an infinity is a
     # legitimate extreme of a column for the uniform range and ignored by the log range)
