@@ -280,3 +280,25 @@ def test_check_lists(bf, torch):
     assert not bf.check_lists(torch.tensor([0, 2, 2, 4], dtype=torch.int64, device="cuda"), idx, 10)
     assert bf.check_lists(torch.zeros(1, dtype=torch.int64, device="cuda"),
                           torch.zeros(0, dtype=torch.int64, device="cuda"), 10)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_aggregate_rows_random(bf, torch, case):
+    # seeded random shapes: width, number of rows and lists, list-length mix (empty, short,
+    # a few long ones on either side of the 256-entry threshold), mean or sum
+    import os
+    rng = np.random.default_rng(100_000 * int(os.environ.get("BIFEAT_TEST_SEED", "0")) + 7000 + case)
+    D = int(rng.choice([1, 2, 4, 5, 12, 32, 100, 128, 260, 516, 1024, 1500]))
+    N = int(rng.integers(1, 3000))
+    V = int(rng.integers(1, 1500))
+    deg = rng.integers(0, int(rng.choice([2, 8, 40])) + 1, V)
+    for _ in range(int(rng.integers(0, 6))):
+        deg[rng.integers(0, V)] = int(rng.choice([255, 256, 257, 300, 1000, 2047, 2049, 5000]))
+    indptr, indices = _csr_from_degrees(deg.astype(np.int64), N, rng)
+    x = (rng.standard_normal((N, D)) * rng.uniform(0.01, 100) + rng.uniform(-1, 1)).astype(np.float32)
+    as_sum = bool(rng.integers(0, 2))
+    out = torch.full((V, D), -3.0, dtype=torch.float32, device="cuda")
+    bf.aggregate_rows(torch.from_numpy(x).cuda(), torch.from_numpy(indptr).cuda(),
+                      torch.from_numpy(indices).cuda(), out=out, sum=as_sum)
+    _assert_rows_close(out.cpu().numpy(), orc.aggregate_rows(x, indptr, indices, sum=as_sum), x, indptr,
+                       indices, as_sum, f"case {case}: D={D} N={N} V={V} sum={as_sum}")
