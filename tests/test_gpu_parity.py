@@ -503,7 +503,7 @@ def test_mean_with_self_loops_on_the_gpu(bf, torch):
     assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, ptr, idx), s)
 
 
-@pytest.mark.parametrize("kind,bits,D", [("uniform", 4, 100), ("vq", 8, 64), ("log", 2, 100)])
+@pytest.mark.parametrize("kind,bits,D", [("uniform", 4, 100), ("vq", 8, 64), ("log", 2, 100), ("log", 4, 128)])
 def test_calls_replay_from_a_captured_graph(bf, torch, kind, bits, D):
     # the per-iteration calls enqueue kernels only (no memset, no synchronisation, no
     # allocation once the vector-code scratch has its size), so a step can be captured once
