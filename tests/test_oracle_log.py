@@ -119,3 +119,75 @@ def test_error_shrinks_with_bits():
                                  np.arange(x.shape[0]))
         errs.append(np.sqrt(((dec - x) ** 2).mean()))
     assert all(a > b for a, b in zip(errs, errs[1:]))
+
+
+# ---- the clipped range (Sec. 3.1: the range is taken after outliers are clipped; Appendix C
+# leaves the fraction open).  The reading: with n finite nonzero magnitudes and fraction p, the
+# order statistics at ranks floor(p(n-1)) and ceil((1-p)(n-1)).  Pinned by what an order
+# statistic is (a counting property that no sort is needed to state), by numpy's selection
+# routine, and by hand-countable cases.
+def _count_pin(m, p, e_min, e_max):
+    """#{m < v} <= rank < #{m <= v} for both ends, v recovered from the log2 the oracle returns."""
+    n = m.size
+    lo, hi = np.float32(2.0 ** e_min), np.float32(2.0 ** e_max)
+    # the ends are table magnitudes, reproduced exactly by exp2 of their fp64 log2
+    assert np.any(m == lo) and np.any(m == hi)
+    k_lo = int(np.floor(p * (n - 1)))
+    k_hi = int(np.ceil((1.0 - p) * (n - 1)))
+    assert (m < lo).sum() <= k_lo < (m <= lo).sum()
+    assert (m < hi).sum() <= k_hi < (m <= hi).sum()
+    return k_lo, k_hi
+
+
+@pytest.mark.parametrize("p", [0.0, 0.001, 0.01, 0.05, 0.25, 0.499])
+@pytest.mark.parametrize("n", [1, 2, 3, 10, 101, 1000, 4097])
+def test_clipped_range_is_the_order_statistic_by_counting(n, p):
+    rng = np.random.default_rng(1000 * n + int(1e4 * p))
+    x = (rng.standard_normal(n) * np.exp(rng.standard_normal(n))).astype(np.float32)
+    x[x == 0] = 1.0
+    e_min, e_max = orc.log_range_clipped(x, p)
+    m = np.abs(x)
+    k_lo, k_hi = _count_pin(m, p, e_min, e_max)
+    # a library selection routine on the same ranks
+    assert np.float32(2.0 ** e_min) == np.partition(m, k_lo)[k_lo]
+    assert np.float32(2.0 ** e_max) == np.partition(m, k_hi)[k_hi]
+    assert e_min <= e_max
+
+
+def test_clipped_range_hand_counted_cases():
+    # magnitudes 1, 2, 4, ..., 1024 (n = 11, log2 = 0..10), signs mixed, order shuffled
+    x = np.array([-(2.0 ** i) if i % 2 else 2.0 ** i for i in range(11)], dtype=np.float32)[
+        [5, 0, 9, 3, 10, 1, 7, 2, 8, 4, 6]]
+    # p(n-1) integral: p = 0.1 -> ranks 1 and 9; p = 0.2 -> 2 and 8; p = 0.3 -> 3 and 7
+    assert orc.log_range_clipped(x, 0.1) == (1.0, 9.0)
+    assert orc.log_range_clipped(x, 0.2) == (2.0, 8.0)
+    assert orc.log_range_clipped(x, 0.3) == (3.0, 7.0)
+    # fractional ranks: the low end rounds down, the high end up (never clips more than asked)
+    assert orc.log_range_clipped(x, 0.15) == (1.0, 9.0)        # 1.5 -> 1,  8.5 -> 9
+    assert orc.log_range_clipped(x, 0.25) == (2.0, 8.0)        # 2.5 -> 2,  7.5 -> 8
+    assert orc.log_range_clipped(x, 0.05) == (0.0, 10.0)       # 0.5 -> 0,  9.5 -> 10
+    assert orc.log_range_clipped(x, 0.0) == (0.0, 10.0)        # no clipping: the extremes
+    # both tails are clipped, and symmetrically in rank
+    for p in [0.1, 0.2, 0.3, 0.4]:
+        e_min, e_max = orc.log_range_clipped(x, p)
+        assert e_min == 10.0 - e_max
+    # a single value, and all values equal
+    assert orc.log_range_clipped(np.array([-8.0], np.float32), 0.3) == (3.0, 3.0)
+    assert orc.log_range_clipped(np.full(7, 0.25, np.float32), 0.2) == (-2.0, -2.0)
+
+
+def test_clipped_range_ignores_zeros_and_non_finite_and_handles_ties():
+    # ties: magnitudes 1 x5, 2 x5, 4 x5 -> n = 15; p = 0.2 -> ranks floor(2.8) = 2, ceil(11.2) = 12
+    x = np.array([1, -1, 1, -1, 1, 2, -2, 2, -2, 2, 4, -4, 4, -4, 4], dtype=np.float32)
+    assert orc.log_range_clipped(x, 0.2) == (0.0, 2.0)
+    # p = 0.4 -> ranks floor(5.6) = 5, ceil(8.4) = 9: both inside the run of 2s
+    assert orc.log_range_clipped(x, 0.4) == (1.0, 1.0)
+    # zeros, NaN and infinities do not count towards n
+    y = np.concatenate([x, np.array([0, 0, -0.0, np.nan, np.inf, -np.inf], np.float32)])
+    for p in [0.0, 0.2, 0.4]:
+        assert orc.log_range_clipped(y, p) == orc.log_range_clipped(x, p)
+    assert orc.log_range_clipped(np.array([0, np.nan, np.inf], np.float32), 0.1) == (0.0, 0.0)
+    # p = 0 equals the plain fit of the extremes
+    t = _table()
+    assert orc.log_range_clipped(t, 0.0) == orc.log_range(orc.log_fit(t))
+    _count_pin(np.abs(t.reshape(-1))[np.abs(t.reshape(-1)) > 0], 0.01, *orc.log_range_clipped(t, 0.01))
