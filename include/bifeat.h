@@ -22,14 +22,18 @@
  *     gives a description (for BIFEAT_EHIP: the HIP error text of the last
  *     failure on the calling thread).
  *   - Calls on one bifeat_params handle must not overlap in time (they share
- *     its fit state and, for vector codes, its scratch buffer: the transposed
- *     codes of the rows a call requests, grown with hipMalloc when a larger
- *     request arrives).  Different handles are independent.
+ *     its fit state and, for vector codes, its workspace: the transposed
+ *     codes of the rows a call requests).  Different handles are independent.
  *   - The per-iteration calls (gather_codes / gather_dequant / gather_mean /
  *     gather_sum) only enqueue kernels: no memset, no synchronisation, and no
- *     allocation except that growth of the vector-code scratch.  They can be
- *     captured into a HIP graph once a call at least as large has run outside
- *     the capture (and with option "validate" off).
+ *     allocation except growth of the vector-code workspace when a request is
+ *     larger than any before (bifeat_reserve sizes it ahead of time).  An
+ *     outgrown workspace stays allocated until the handle is destroyed, so
+ *     work in flight and HIP graphs captured from earlier calls keep valid
+ *     addresses.  The calls can be captured into a HIP graph (with option
+ *     "validate" off); nothing is allocated while the stream is capturing: a
+ *     vector-code request larger than the workspace is then decoded by the
+ *     slower kernels that need none.
  *   - Row indices must satisfy 0 <= idx < N, indptr must be non-decreasing with
  *     indptr[0] = 0 and indptr[V] = E; this is the caller's contract and is not
  *     checked on the GPU - unless option "validate" = 1 is set: every gather
@@ -206,6 +210,12 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
 int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                        const int64_t *indices, int64_t V, int64_t E, float *out, void *stream);
 
+/* The same with 32-bit list entries (tables of at most 2^31 - 1 rows; otherwise
+ * BIFEAT_EINVAL): half the index bytes per list entry.  indices: DEVICE int32
+ * [E].  Not available together with option "validate" (BIFEAT_ENOTSUP). */
+int bifeat_gather_mean_i32(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                           const int32_t *indices, int64_t V, int64_t E, float *out, void *stream);
+
 /* ---- the same without the division: the sum aggregator.  out[v, :] = sum over
  * the list of decode(codes[indices[e]]) (Appendix A.1 analyses the mean; the
  * sum is its unnormalised form, and with v listed among its own neighbours
@@ -214,6 +224,25 @@ int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const 
  * 1e-5 * max(|exact|, n_v * A_j), n_v the list length. */
 int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream);
+int bifeat_gather_sum_i32(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                          const int32_t *indices, int64_t V, int64_t E, float *out, void *stream);
+
+/* A promise the caller made through option "mean_max_degree" and a list broke
+ * (Appendix A.1's mean needs every neighbour of the list): the kernel that
+ * meets such a list writes NaN into its whole output row and raises the
+ * handle's status word, without any synchronisation.  The word is looked at
+ * (and cleared) by the next bifeat_gather_mean / bifeat_gather_sum call on the
+ * handle, which then returns BIFEAT_EINVAL without launching, and by this call:
+ * BIFEAT_EINVAL if a kernel that has finished raised it since the last look,
+ * else BIFEAT_OK.  wait != 0 synchronises `stream` first, so that the answer
+ * covers everything enqueued on it. */
+int bifeat_poll_status(bifeat_params *p, void *stream, int32_t wait);
+
+/* Sizes the handle's workspace for gather calls of up to max_requests rows
+ * (gather_dequant: M; gather_mean / gather_sum: E), so that no later call
+ * allocates.  Only vector codes use a workspace; for the other kinds this is a
+ * no-op.  Not during a stream capture (BIFEAT_EHIP). */
+int bifeat_reserve(bifeat_params *p, int64_t max_requests, void *stream);
 
 /* ---- the layers after the first (Appendix A.1: every layer averages the
  * previous layer's vectors over the same neighbourhoods): the aggregation over
@@ -236,8 +265,9 @@ int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *i
 /* The index contract of the calls above, checked on its own (bifeat_aggregate_rows has
  * no parameter object to carry the "validate" option): 0 <= indices[e] < N for all
  * e < E and, when indptr is not NULL, indptr[0] == 0, indptr non-decreasing,
- * indptr[V] == E.  DEVICE pointers.  Returns BIFEAT_OK or BIFEAT_EINVAL; allocates a few
- * bytes of device memory and synchronises `stream`. */
+ * indptr[V] == E.  DEVICE pointers.  Returns BIFEAT_OK or BIFEAT_EINVAL; synchronises
+ * `stream` (its flag lives in a small device block taken from a per-device pool that
+ * the library keeps: an allocation only when every block is in use). */
 int bifeat_check_lists(const int64_t *indptr, const int64_t *indices, int64_t V, int64_t E,
                        int64_t N, void *stream);
 
@@ -256,8 +286,8 @@ int bifeat_check_lists(const int64_t *indptr, const int64_t *indices, int64_t V,
  * the GPU first (BIFEAT_EINVAL if broken).  work: DEVICE scratch of
  * min(layers, 2) * N * D floats, not overlapping x (may be NULL for layers = 0).
  * scale: HOST double[layers + 1].  0 <= layers <= 64.  Row lengths are
- * accumulated in fp64; h_l is stored in fp32 between rounds.  Allocates a few
- * bytes of device memory and synchronises `stream`. */
+ * accumulated in fp64; h_l is stored in fp32 between rounds.  Synchronises `stream`
+ * (sums and flag in a pooled device block, as for bifeat_check_lists). */
 int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *indptr,
                          const int64_t *indices, int64_t E, int32_t layers, float *work,
                          double *scale, void *stream);
@@ -274,8 +304,8 @@ const char *bifeat_strerror(int status);
  * "mean_max_degree" = d is the caller's promise that no neighbour list of the
  * following bifeat_gather_mean calls is longer than d (0 = unknown; a sampler
  * knows its fan-out), which lets the library skip the pass that looks for
- * longer lists (a list that breaks the promise leaves its output row unwritten;
- * "validate" checks the promise too);
+ * longer lists (a list that breaks the promise gets a row of NaNs and raises the
+ * status word, see bifeat_poll_status; "validate" checks the promise up front);
  * "vq_iters" = Lloyd rounds per training chunk (1..64); "validate" = 1 checks
  * the index contract of every gather call on the GPU first (see above).
  * Unknown names return BIFEAT_EINVAL. */

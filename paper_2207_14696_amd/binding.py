@@ -67,6 +67,12 @@ _SIGNATURES = {
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_gather_sum": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_gather_mean_i32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                         C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_gather_sum_i32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_poll_status": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32]),
+    "bifeat_reserve": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p]),
     "bifeat_aggregate_rows": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]),
     "bifeat_check_lists": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p]),
@@ -252,23 +258,39 @@ class Quantizer:
                                                _dev_ptr(out, (torch.float32,)), _stream()))
         return out
 
-    def _aggregate(self, fn, codes, indptr, indices, out):
+    def _aggregate(self, fn64, fn32, codes, indptr, indices, out):
         import torch
         V = indptr.shape[0] - 1
         if out is None:
             out = torch.empty((V, self.D), dtype=torch.float32, device=codes.device)
         elif out.shape != (V, self.D):
             raise ValueError("out must be [V, D]")
+        # int32 list entries go to the _i32 entry point, int64 ones to the plain one
+        fn = fn32 if indices.dtype == torch.int32 else fn64
         _check(fn(self._h, _dev_ptr(codes, (torch.uint8,)), codes.shape[0],
-                  _dev_ptr(indptr, (torch.int64,)), _dev_ptr(indices, (torch.int64,)), V,
+                  _dev_ptr(indptr, (torch.int64,)), _dev_ptr(indices, (torch.int64, torch.int32)), V,
                   indices.shape[0], _dev_ptr(out, (torch.float32,)), _stream()))
         return out
 
     def gather_mean(self, codes, indptr, indices, out=None):
-        return self._aggregate(self._lib.bifeat_gather_mean, codes, indptr, indices, out)
+        return self._aggregate(self._lib.bifeat_gather_mean, self._lib.bifeat_gather_mean_i32,
+                               codes, indptr, indices, out)
 
     def gather_sum(self, codes, indptr, indices, out=None):
-        return self._aggregate(self._lib.bifeat_gather_sum, codes, indptr, indices, out)
+        return self._aggregate(self._lib.bifeat_gather_sum, self._lib.bifeat_gather_sum_i32,
+                               codes, indptr, indices, out)
+
+    def poll_status(self, wait: bool = True) -> bool:
+        """``bifeat_poll_status``: False if a kernel of an earlier call met a list longer
+        than the promised ``mean_max_degree`` (the word is cleared), True otherwise."""
+        rc = self._lib.bifeat_poll_status(self._h, _stream(), 1 if wait else 0)
+        if rc == EINVAL:
+            return False
+        _check(rc)
+        return True
+
+    def reserve(self, max_requests: int) -> None:
+        _check(self._lib.bifeat_reserve(self._h, int(max_requests), _stream()))
 
 
 def aggregate_rows(x, indptr, indices, out=None, sum: bool = False):

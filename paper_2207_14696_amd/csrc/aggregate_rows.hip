@@ -307,6 +307,16 @@ hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indpt
     return hipGetLastError();
 }
 
+// a small fill kernel instead of a memset node: callers may capture the stream into a graph
+__global__ void zero_doubles_kernel(double *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0;
+}
+
+void launch_zero_doubles(double *p, int n, hipStream_t s) {
+    zero_doubles_kernel<<<(n + 127) / 128, 128, 0, s>>>(p, n);
+}
+
 hipError_t launch_row_length_sum(const float *h, int64_t n, int64_t D, double *acc, hipStream_t s) {
     const int blocks = blocks_for(n * 64, 8 * 256);
     if (vec_ok(h, h, D))

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <map>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -84,7 +86,50 @@ int ensure_device(bifeat_params *p) {
     p->d_fit = reinterpret_cast<int32_t *>(p->d_block + nfloat);
     if (p->scheme.kind == BIFEAT_SQ_LOG) p->d_hist = reinterpret_cast<unsigned long long *>(p->d_fit + 4);
     p->d_zero = reinterpret_cast<uint8_t *>(p->d_fit + nfit);
+    // the status word: pinned host memory that the kernels write through its device mapping
+    void *hs = nullptr, *ds = nullptr;
+    BF_HIP(hipHostMalloc(&hs, 64, hipHostMallocMapped));
+    memset(hs, 0, 64);
+    BF_HIP(hipHostGetDevicePointer(&ds, hs, 0));
+    p->h_status = (int32_t *)hs;
+    p->d_status = (int32_t *)ds;
     return BIFEAT_OK;
+}
+
+// Small zeroed device blocks for the calls that have no handle to keep one in
+// (bifeat_check_lists, bifeat_scale_profile): taken from a per-device pool and given back,
+// so that a call allocates only when every block of its device is in use.
+constexpr size_t kPoolBlockBytes = 1024;
+std::mutex g_pool_mutex;
+std::map<int, std::vector<void *>> g_pool;
+
+int pool_take(void **out) {
+    int dev = 0;
+    BF_HIP(hipGetDevice(&dev));
+    {
+        std::lock_guard<std::mutex> lock(g_pool_mutex);
+        std::vector<void *> &free_blocks = g_pool[dev];
+        if (!free_blocks.empty()) {
+            *out = free_blocks.back();
+            free_blocks.pop_back();
+            return BIFEAT_OK;
+        }
+    }
+    BF_HIP(hipMalloc(out, kPoolBlockBytes));
+    return BIFEAT_OK;
+}
+
+void pool_give(void *blk) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return;
+    std::lock_guard<std::mutex> lock(g_pool_mutex);
+    g_pool[dev].push_back(blk);
+}
+
+// the status word raised by a kernel of an earlier call on this handle, cleared
+int take_status(bifeat_params *p) {
+    if (!p->h_status) return 0;
+    return __atomic_exchange_n(p->h_status, 0, __ATOMIC_ACQ_REL);
 }
 
 // log scheme: bin edges and decode table from (e_min, e_max), fp64 -> fp32
@@ -275,6 +320,8 @@ void bifeat_params_destroy(bifeat_params *p) {
     if (!p) return;
     if (p->d_block) (void)hipFree(p->d_block);
     if (p->d_scratch) (void)hipFree(p->d_scratch);
+    for (void *q : p->retired) (void)hipFree(q);
+    if (p->h_status) (void)hipHostFree(p->h_status);
     delete p;
 }
 
@@ -545,25 +592,66 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
     return BIFEAT_OK;
 }
 
-int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
-                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+namespace {
+int gather_aggregate(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                     const void *indices, bool idx32, int64_t V, int64_t E, int agg_sum, float *out,
+                     void *stream) {
     if (!p || V < 0 || N < 0 || E < 0) return BIFEAT_EINVAL;
     if (V > 0 && (!codes || !indptr || !out || (E > 0 && !indices))) return BIFEAT_EINVAL;
     if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
+    if (idx32 && N > (int64_t)INT32_MAX) return BIFEAT_EINVAL;  // row ids would not fit
     if (!p->fitted) return BIFEAT_ENOTFIT;
+    // a promise broken in an earlier call (its kernel has finished since) is reported now
+    if (take_status(p)) return BIFEAT_EINVAL;
     if (V == 0) return BIFEAT_OK;
-    if (int rc = check_inputs(p, indices, E, N, indptr, V, E, (hipStream_t)stream)) return rc;
-    BF_HIP(bf::launch_gather_mean(p, codes, indptr, indices, V, E, out, (hipStream_t)stream));
+    if (p->opt_validate) {
+        if (idx32) return BIFEAT_ENOTSUP;  // the checker reads 64-bit entries
+        if (int rc = check_inputs(p, (const int64_t *)indices, E, N, indptr, V, E, (hipStream_t)stream))
+            return rc;
+    }
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    const bf::MeanCall c{codes, indptr, indices, idx32, V, E, out, agg_sum, p->opt_mean_max_degree,
+                         p->d_status, (hipStream_t)stream};
+    BF_HIP(bf::launch_gather_mean(p, c));
     return BIFEAT_OK;
+}
+}  // namespace
+
+int bifeat_gather_mean(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+    return gather_aggregate(p, codes, N, indptr, indices, false, V, E, 0, out, stream);
 }
 
 int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                       const int64_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+    return gather_aggregate(p, codes, N, indptr, indices, false, V, E, 1, out, stream);
+}
+
+int bifeat_gather_mean_i32(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                           const int32_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+    return gather_aggregate(p, codes, N, indptr, indices, true, V, E, 0, out, stream);
+}
+
+int bifeat_gather_sum_i32(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
+                          const int32_t *indices, int64_t V, int64_t E, float *out, void *stream) {
+    return gather_aggregate(p, codes, N, indptr, indices, true, V, E, 1, out, stream);
+}
+
+int bifeat_poll_status(bifeat_params *p, void *stream, int32_t wait) {
     if (!p) return BIFEAT_EINVAL;
-    p->agg_sum = 1;
-    const int rc = bifeat_gather_mean(p, codes, N, indptr, indices, V, E, out, stream);
-    p->agg_sum = 0;
-    return rc;
+    if (wait) BF_HIP(hipStreamSynchronize((hipStream_t)stream));
+    return take_status(p) ? BIFEAT_EINVAL : BIFEAT_OK;
+}
+
+int bifeat_reserve(bifeat_params *p, int64_t max_requests, void *stream) {
+    if (!p || max_requests < 0) return BIFEAT_EINVAL;
+    if (p->scheme.kind != BIFEAT_VQ || max_requests == 0) return BIFEAT_OK;  // no workspace needed
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    if (!bf::ensure_scratch(p, bf::vq_gather_scratch_bytes(p, max_requests), (hipStream_t)stream))
+        return hip_fail(hipErrorOutOfMemory, "bifeat_reserve");
+    return BIFEAT_OK;
 }
 
 int bifeat_aggregate_rows(const float *x, int64_t N, int64_t D, const int64_t *indptr,
@@ -581,14 +669,14 @@ int bifeat_check_lists(const int64_t *indptr, const int64_t *indices, int64_t V,
                        int64_t N, void *stream) {
     if (V < 0 || E < 0 || N < 0 || (E > 0 && !indices) || (V > 0 && !indptr)) return BIFEAT_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    int32_t *d_bad = nullptr, bad = 0;
-    BF_HIP(hipMalloc((void **)&d_bad, sizeof(int32_t)));
+    void *blk = nullptr;
+    if (int rc = pool_take(&blk)) return rc;
+    int32_t *d_bad = (int32_t *)blk, bad = 0;
     bf::launch_validate(indices, E, N, indptr, indptr ? V : 0, E, 0, d_bad, s);
     hipError_t e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    const hipError_t ef = hipFree(d_bad);
+    pool_give(blk);
     if (e != hipSuccess) return hip_fail(e, "bifeat_check_lists");
-    if (ef != hipSuccess) return hip_fail(ef, "hipFree");
     return bad ? BIFEAT_EINVAL : BIFEAT_OK;
 }
 
@@ -604,18 +692,16 @@ int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *in
         return BIFEAT_OK;
     }
     hipStream_t s = (hipStream_t)stream;
-    // layers+1 sums, then the flag of the index check
-    double *d_acc = nullptr;
-    const size_t bytes = sizeof(double) * (size_t)(layers + 2);
-    BF_HIP(hipMalloc((void **)&d_acc, bytes));
+    // layers+1 sums, then the flag of the index check (a pooled block holds 128 doubles)
+    void *blk = nullptr;
+    if (int rc = pool_take(&blk)) return rc;
+    double *d_acc = (double *)blk;
     double h_acc[66];
     int32_t bad = 0;
-    hipError_t e = hipMemsetAsync(d_acc, 0, bytes, s);
-    if (e == hipSuccess) {
-        int32_t *d_bad = reinterpret_cast<int32_t *>(d_acc + layers + 1);
-        bf::launch_validate(indices, E, N, indptr, N, E, 0, d_bad, s);
-        e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
-    }
+    int32_t *d_bad = reinterpret_cast<int32_t *>(d_acc + layers + 1);
+    bf::launch_zero_doubles(d_acc, layers + 2, s);
+    bf::launch_validate(indices, E, N, indptr, N, E, 0, d_bad, s);
+    hipError_t e = hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e == hipSuccess && !bad) {
         e = bf::launch_row_length_sum(x, N, D, d_acc, s);
@@ -631,9 +717,9 @@ int bifeat_scale_profile(const float *x, int64_t N, int64_t D, const int64_t *in
                                hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
     }
-    const hipError_t ef = hipFree(d_acc);
+    // the block goes back only when no work that uses it can still be running
+    if (e == hipSuccess) pool_give(blk);
     if (e != hipSuccess) return hip_fail(e, "bifeat_scale_profile");
-    if (ef != hipSuccess) return hip_fail(ef, "hipFree");
     if (bad) return BIFEAT_EINVAL;
     for (int l = 0; l <= layers; l++) scale[l] = h_acc[l] / (double)N;
     return BIFEAT_OK;

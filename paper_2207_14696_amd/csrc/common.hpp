@@ -36,6 +36,7 @@ struct bifeat_params {
     float *d_dist = nullptr;    // vq training: summed squared distance per Lloyd round (64 slots)
     uint8_t *d_scratch = nullptr;  // grow-only workspace (vector codes: slice-major code strips)
     size_t scratch_bytes = 0;
+    std::vector<void *> retired;   // outgrown workspaces, kept allocated until the handle dies
     uint8_t *d_zero = nullptr;  // 64 zero bytes (stand-in row for masked loads)
     int32_t *d_fit = nullptr;  // uniform: ordered-int keys [min D | max D]; log: bits of [mmin, mmax]
     unsigned long long *d_hist = nullptr;  // log, clipped fit: digit histograms [2][kLogHistBins]
@@ -53,7 +54,10 @@ struct bifeat_params {
     int64_t vq_last_rows = 0;   // rows of the last training chunk
     int vq_last_rounds = 0;
 
-    int agg_sum = 0;  // 1 while a gather_sum call is being launched: no division by the list length
+    // status word the kernels can raise without the host waiting for them: pinned host memory
+    // mapped into the device's address space (h_status / d_status name the same word)
+    int32_t *h_status = nullptr;
+    int32_t *d_status = nullptr;
 
     // launch tuning (0 = automatic)
     int opt_mean_slots = 0;
@@ -88,18 +92,36 @@ hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64
                            uint8_t *codes_row0, hipStream_t s);
 hipError_t launch_gather_codes(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                int64_t M, uint8_t *out, hipStream_t s);
+// planes: workspace for the vector-code kernels (nullptr = the handle's own, grown as needed)
 hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
-                                 int64_t M, float *out, hipStream_t s);
-hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                              const int64_t *indices, int64_t V, int64_t E, float *out,
-                              hipStream_t s);
+                                 int64_t M, float *out, hipStream_t s, uint32_t *planes = nullptr);
+// One fused gather + aggregate request as the launchers of the mean kernels see it.
+struct MeanCall {
+    const uint8_t *codes;   // packed table
+    const int64_t *indptr;  // [V + 1]
+    const void *indices;    // [E] row ids, int64 or (idx32) int32
+    bool idx32;
+    int64_t V, E;
+    float *out;             // [V x D]
+    int agg_sum;            // 1: sum aggregator (no division by the list length)
+    // the caller's promise that no list is longer (0 = none given).  A kernel that relies on
+    // it (no complementary pass for longer lists is launched) writes a row of NaNs for a list
+    // that breaks it and raises kStatusListTooLong in *status
+    int max_degree;
+    int32_t *status;
+    hipStream_t s;
+};
+constexpr int32_t kStatusListTooLong = 1;
+
+hipError_t launch_gather_mean(bifeat_params *p, const MeanCall &c);
 // min_len: lists with at most this many neighbours are skipped (left to the
 // short-list kernel); -1 = none
-void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
-                             int min_len, hipStream_t s);
-// grow-only library workspace (p->d_scratch); false if the allocation fails
-bool ensure_scratch(bifeat_params *p, size_t bytes);
+void launch_gather_mean_swar(bifeat_params *p, const MeanCall &c, int vec, int min_len);
+// grow-only library workspace (p->d_scratch); false if the allocation fails or `s` is being
+// captured into a graph (nothing is allocated during a capture)
+bool ensure_scratch(bifeat_params *p, size_t bytes, hipStream_t s);
+// bytes of workspace a vector-code gather of M requested rows needs
+size_t vq_gather_scratch_bytes(const bifeat_params *p, int64_t M);
 // 1/|entry| for every codebook entry, fp64 inside (cosine metric)
 void launch_vq_rnorm(bifeat_params *p, hipStream_t s);
 // nearest-entry search of `rows` rows into codes_row0 (row stride rb bytes, indices of
@@ -117,22 +139,21 @@ hipError_t launch_aggregate_rows(const float *x, int64_t D, const int64_t *indpt
                                  const int64_t *indices, int64_t V, int64_t E, int sum, float *out,
                                  hipStream_t s);
 hipError_t launch_row_length_sum(const float *h, int64_t n, int64_t D, double *acc, hipStream_t s);
+void launch_zero_doubles(double *p, int n, hipStream_t s);
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
-                                     int64_t M, float *out, hipStream_t s);
-bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                                  const int64_t *indices, int64_t V, int64_t E, float *out,
-                                  hipStream_t s);
+                                     int64_t M, float *out, hipStream_t s, uint32_t *planes);
+bool launch_gather_mean_vq_sliced(bifeat_params *p, const MeanCall &c);
 int lean_capacity(int bits, bool wide);
 // logarithmic codes of 4 / 8 bits, lists of at most logf_capacity() neighbours
 int logf_capacity();
-bool launch_gather_mean_logf(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, float *out, int thr, hipStream_t s);
-bool launch_gather_mean_lean_log2(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                                  const int64_t *indices, int64_t V, float *out, int thr, bool wide,
-                                  int lo, hipStream_t s);
-bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, float *out, int thr, bool wide,
-                             int lo, hipStream_t s);
+// The short-list kernels: lists of more than `lo` and at most `thr` rows; alone = no other
+// kernel is launched for the longer lists (they then get NaN rows and raise the status word).
+// Each returns false (nothing launched) when the table's shape is outside what it handles.
+bool launch_gather_mean_logf(bifeat_params *p, const MeanCall &c, int thr, bool alone);
+bool launch_gather_mean_lean_log2(bifeat_params *p, const MeanCall &c, int thr, bool wide, int lo,
+                                  bool alone);
+bool launch_gather_mean_lean(bifeat_params *p, const MeanCall &c, int thr, bool wide, int lo,
+                             bool alone);
 
 // ---- order-preserving float <-> int keys for atomic min/max
 __host__ __device__ inline int32_t float_key(float f) {
@@ -178,6 +199,51 @@ __device__ inline T load_stream(const T *p) { return __builtin_nontemporal_load(
 
 __device__ inline float load1(const float *p) { return *p; }
 __device__ inline float load1(const __half *p) { return __half2float(*p); }
+
+// ---- helpers shared by the tile kernels
+// orders a wave's LDS writes before its later LDS reads (all lanes of a wave execute each DS
+// instruction together, in program order): no workgroup barrier needed inside a wave's tile
+__device__ inline void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+struct __attribute__((aligned(4))) U3 { uint32_t x, y, z; };
+
+// CW consecutive 32-bit words of a packed row with one load instruction
+template <int CW>
+__device__ inline void load_words(const uint8_t *p, uint32_t *w) {
+    if constexpr (CW == 4) {
+        uint4 q = *reinterpret_cast<const uint4 *>(p);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else if constexpr (CW == 3) {
+        U3 q = *reinterpret_cast<const U3 *>(p);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z;
+    } else if constexpr (CW == 2) {
+        uint2 q = *reinterpret_cast<const uint2 *>(p);
+        w[0] = q.x; w[1] = q.y;
+    } else {
+        w[0] = *reinterpret_cast<const uint32_t *>(p);
+    }
+}
+
+// a kernel reports a broken caller promise: a plain system-scope store of the code into the
+// mapped status word (no read-modify-write across the bus; the word holds the last code raised)
+__device__ inline void raise_status(int32_t *status, int32_t code) {
+    __hip_atomic_store(status, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+inline int pow2ceil(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+inline int ilog2(int x) {
+    int l = 0;
+    while ((1 << l) < x) l++;
+    return l;
+}
 
 inline int blocks_for(int64_t threads_needed, int64_t cap = kMaxBlocks) {
     int64_t b = (threads_needed + kThreads - 1) / kThreads;

@@ -99,14 +99,6 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
     }
 }
 
-// orders this wave's LDS writes before its later LDS reads (all lanes of a wave
-// execute each DS instruction together, in program order)
-__device__ inline void wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Tile form of the scalar-code kernel (output rows 16-byte aligned, packed row
 // of at most 64 16-byte chunks).  A wavefront takes RT = 64/c16 consecutive
 // output rows: one 16-byte load per lane fetches their packed rows in whole
@@ -306,7 +298,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_vq_tile_kernel(
 }
 
 hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
-                                 int64_t M, float *out, hipStream_t s) {
+                                 int64_t M, float *out, hipStream_t s, uint32_t *planes) {
     const int D = (int)p->D;
     const int G = (D + 3) / 4;
     const int vec = (D % 4 == 0) && ((uintptr_t)out % 16 == 0);
@@ -314,7 +306,7 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
     if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
     const int kind = p->scheme.kind, bits = p->scheme.bits;
     if (kind == BIFEAT_VQ) {
-        if (p->opt_vq_sliced && launch_gather_dequant_vq_sliced(p, codes, idx, M, out, s))
+        if (p->opt_vq_sliced && launch_gather_dequant_vq_sliced(p, codes, idx, M, out, s, planes))
             return hipGetLastError();
         const int w = p->scheme.vq_width;
         const int c16v = (int)(p->rb / 16);
@@ -343,7 +335,12 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
         return hipGetLastError();
     }
     const int c16 = (int)(p->rb / 16);
-    if (vec && c16 <= 64 && !p->opt_dequant_flat) {
+    // LDS of the tile kernel: the parameters (2*D floats for uniform codes) plus one 16-byte
+    // slot per lane; tables too wide for the 64 KB a workgroup gets by default take the
+    // flat kernel below
+    const size_t tile_lds = sizeof(uint32_t) * (size_t)(((kind == BIFEAT_SQ_UNIFORM ? 2 * D : (1 << bits)) + 3) & ~3) +
+                            (size_t)(kThreads / 64) * 64 * 16;
+    if (vec && c16 <= 64 && !p->opt_dequant_flat && tile_lds <= 65536) {
         const int RT = 64 / c16;
         const int64_t tiles = (M + RT - 1) / RT;
         // about one tile per wave: the hardware's wave scheduling hides the index -> row ->
@@ -352,8 +349,7 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
         const int64_t cap = p->opt_max_blocks > 0 ? p->opt_max_blocks : (1 << 16);
         int64_t want = (tiles + 3) / 4;
         const int tb = (int)(want < cap ? want : cap);
-        const int npar = kind == BIFEAT_SQ_UNIFORM ? 2 * D : (1 << bits);
-        const size_t shm = sizeof(uint32_t) * (size_t)((npar + 3) & ~3) + (size_t)(kThreads / 64) * 64 * 16;
+        const size_t shm = tile_lds;
 #define BF_GT(B, DEC, A, Bp) \
     gather_dequant_tile_kernel<B, DEC><<<tb, kThreads, shm, s>>>((const uint4 *)codes, c16, idx, M, D, A, Bp, out)
         if (kind == BIFEAT_SQ_UNIFORM) {

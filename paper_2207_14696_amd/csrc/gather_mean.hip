@@ -27,10 +27,10 @@ __device__ inline int mean_vq_index(const uint8_t *row, int part) {
     else return row[part];
 }
 
-template <int KIND, int BITS, bool VEC>
+template <int KIND, int BITS, bool VEC, typename IT>
 __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ pa,
+    const IT *__restrict__ indices, int64_t V, int D, const float *__restrict__ pa,
     const float *__restrict__ pb, int w, int len, int agg_sum, int min_len,
     float *__restrict__ out) {
     __shared__ float s_lut[KIND == MK_LOG ? (1 << (BITS & 15)) : 1];
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
             float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
             for (int64_t e = c0; e < c1; e++) {
-                const uint8_t *row = codes + indices[e] * rb;
+                const uint8_t *row = codes + (int64_t)indices[e] * rb;
                 if constexpr (KIND == MK_UNIFORM || KIND == MK_LOG) {
                     const uint32_t bits = mean_code_bits4<BITS>(row, g);
 #pragma unroll
@@ -109,17 +109,25 @@ __global__ __launch_bounds__(kThreads) void gather_mean_float_kernel(
 }
 
 template <int KIND>
-static void launch_float(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                         const int64_t *indices, int64_t V, const float *pa, const float *pb,
-                         float *out, int vec, hipStream_t s, int min_len = -1) {
+static void launch_float(bifeat_params *p, const MeanCall &c, const float *pa, const float *pb,
+                         int vec, int min_len = -1) {
     const int D = (int)p->D, G = (D + 3) / 4;
-    int blocks = blocks_for(V * G);
+    int blocks = blocks_for(c.V * G);
     if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
-#define BF_FL(B)                                                                                         \
-    do {                                                                                                 \
-        if (vec) gather_mean_float_kernel<KIND, B, true><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, min_len, out); \
-        else gather_mean_float_kernel<KIND, B, false><<<blocks, kThreads, 0, s>>>(codes, p->rb, indptr, indices, V, D, pa, pb, w, len, p->agg_sum, min_len, out);    \
+#define BF_FK(B, VECV, IT)                                                                        \
+    gather_mean_float_kernel<KIND, B, VECV, IT><<<blocks, kThreads, 0, c.s>>>(                    \
+        c.codes, p->rb, c.indptr, (const IT *)c.indices, c.V, D, pa, pb, w, len, c.agg_sum,       \
+        min_len, c.out)
+#define BF_FL(B)                                                                                  \
+    do {                                                                                          \
+        if (vec) {                                                                                \
+            if (c.idx32) BF_FK(B, true, int32_t);                                                 \
+            else BF_FK(B, true, int64_t);                                                         \
+        } else {                                                                                  \
+            if (c.idx32) BF_FK(B, false, int32_t);                                                \
+            else BF_FK(B, false, int64_t);                                                        \
+        }                                                                                         \
     } while (0)
     if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
         if (p->cbytes == 2) BF_FL(16);
@@ -133,14 +141,20 @@ static void launch_float(bifeat_params *p, const uint8_t *codes, const int64_t *
         }
     }
 #undef BF_FL
+#undef BF_FK
 }
 
-hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                              const int64_t *indices, int64_t V, int64_t E, float *out,
-                              hipStream_t s) {
+hipError_t launch_gather_mean(bifeat_params *p, const MeanCall &c) {
     const int D = (int)p->D;
-    const int vec = (D % 4 == 0) && ((uintptr_t)out % 16 == 0);
+    const int64_t V = c.V, E = c.E;
+    const int vec = (D % 4 == 0) && ((uintptr_t)c.out % 16 == 0);
     const int kind = p->scheme.kind;
+    // With the caller's bound on the list lengths a short-list kernel that covers the bound
+    // runs alone: the pass that looks for longer lists is not launched, and a list that breaks
+    // the promise gets a row of NaNs and raises the handle's status word.
+    const bool promised = c.max_degree > 0;
+    const int64_t avg = V > 0 ? E / V : 0;
+    const int64_t need = promised ? c.max_degree : 2 * avg;
     // 1-bit logarithmic codes (Sec. 3.1: sign only) decode affinely, V[0] + q*(V[1]-V[0]),
     // so they take the integer-sum kernels of the uniform codes with that map per column
     const bool affine = kind == BIFEAT_SQ_UNIFORM || (kind == BIFEAT_SQ_LOG && p->scheme.bits == 1);
@@ -149,13 +163,11 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
         // general one; each skips the other's destinations.  The caller's bound on
         // the list length (or, without one, twice the average) picks the lean
         // kernel's field width.
-        const int64_t avg = V > 0 ? E / V : 0;
-        const int64_t need = p->opt_mean_max_degree > 0 ? p->opt_mean_max_degree : 2 * avg;
         const bool wide = need > lean_capacity(p->scheme.bits, false);
         const int thr = lean_capacity(p->scheme.bits, wide);
         const bool lean = p->opt_mean_lean && p->opt_mean_slots == 0 && vec && V > 0 && need <= thr &&
-                          launch_gather_mean_lean(p, codes, indptr, indices, V, out, thr, wide, -1, s);
-        const bool all_short = lean && p->opt_mean_max_degree > 0;
+                          launch_gather_mean_lean(p, c, thr, wide, -1, promised);
+        const bool all_short = lean && promised;
         if (!all_short) {
             // Without the caller's bound the narrow form was chosen on the average alone: the
             // lists between its capacity and the wide form's (a sampler's fan-out sits there
@@ -163,50 +175,45 @@ hipError_t launch_gather_mean(bifeat_params *p, const uint8_t *codes, const int6
             int covered = lean ? thr : -1;
             const int thr_wide = lean_capacity(p->scheme.bits, true);
             if (lean && !wide && thr_wide > thr &&
-                launch_gather_mean_lean(p, codes, indptr, indices, V, out, thr_wide, true, thr, s))
+                launch_gather_mean_lean(p, c, thr_wide, true, thr, false))
                 covered = thr_wide;
-            launch_gather_mean_swar(p, codes, indptr, indices, V, E, out, vec, covered, s);
+            launch_gather_mean_swar(p, c, vec, covered);
         }
     } else if (kind == BIFEAT_SQ_UNIFORM) {
-        launch_float<MK_UNIFORM>(p, codes, indptr, indices, V, p->d_min, p->d_scale, out, vec, s);
+        launch_float<MK_UNIFORM>(p, c, p->d_min, p->d_scale, vec);
     } else if (kind == BIFEAT_SQ_LOG && p->scheme.bits == 2 && vec && D <= 1024 && !p->opt_mean_generic) {
         // short lists: the two bit planes summed as integers by the 1-bit short-list kernel;
         // longer lists: the table look-up kernel, each skipping the other's destinations
-        const int64_t avg = V > 0 ? E / V : 0;
-        const int64_t need = p->opt_mean_max_degree > 0 ? p->opt_mean_max_degree : 2 * avg;
         const bool wide = need > lean_capacity(1, false);
         const int thr = lean_capacity(1, wide);
         const bool lean = p->opt_mean_lean && V > 0 && need <= thr &&
-                          launch_gather_mean_lean_log2(p, codes, indptr, indices, V, out, thr, wide, -1, s);
-        const bool all_short = lean && p->opt_mean_max_degree > 0;
+                          launch_gather_mean_lean_log2(p, c, thr, wide, -1, promised);
+        const bool all_short = lean && promised;
         if (!all_short) {
             int covered = lean ? thr : -1;
             const int thr_wide = lean_capacity(1, true);
             if (lean && !wide && thr_wide > thr &&
-                launch_gather_mean_lean_log2(p, codes, indptr, indices, V, out, thr_wide, true, thr, s))
+                launch_gather_mean_lean_log2(p, c, thr_wide, true, thr, false))
                 covered = thr_wide;
-            launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, covered);
+            launch_float<MK_LOG>(p, c, p->d_V, nullptr, vec, covered);
         }
     } else if (kind == BIFEAT_SQ_LOG && (p->scheme.bits == 4 || p->scheme.bits == 8) && vec &&
                !p->opt_mean_generic) {
         // short lists: the look-up kernel with whole 16-byte code loads; longer lists: the
         // general kernel, each skipping the other's destinations
-        const int64_t avg = V > 0 ? E / V : 0;
-        const int64_t need = p->opt_mean_max_degree > 0 ? p->opt_mean_max_degree : 2 * avg;
         const int thr = logf_capacity();
         const bool tiled = p->opt_mean_lean && V > 0 && need <= thr &&
-                           launch_gather_mean_logf(p, codes, indptr, indices, V, out, thr, s);
-        const bool all_short = tiled && p->opt_mean_max_degree > 0;
-        if (!all_short)
-            launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s, tiled ? thr : -1);
+                           launch_gather_mean_logf(p, c, thr, promised);
+        const bool all_short = tiled && promised;
+        if (!all_short) launch_float<MK_LOG>(p, c, p->d_V, nullptr, vec, tiled ? thr : -1);
     } else if (kind == BIFEAT_SQ_LOG) {
-        launch_float<MK_LOG>(p, codes, indptr, indices, V, p->d_V, nullptr, out, vec, s);
-    } else if (p->opt_vq_sliced && launch_gather_mean_vq_sliced(p, codes, indptr, indices, V, E, out, s)) {
+        launch_float<MK_LOG>(p, c, p->d_V, nullptr, vec);
+    } else if (p->opt_vq_sliced && launch_gather_mean_vq_sliced(p, c)) {
         // vector codes, codebook slices in LDS
     } else if (p->scheme.vq_width % 4 == 0 && vec) {
-        launch_float<MK_VQ4>(p, codes, indptr, indices, V, p->d_cb, nullptr, out, vec, s);
+        launch_float<MK_VQ4>(p, c, p->d_cb, nullptr, vec);
     } else {
-        launch_float<MK_VQ>(p, codes, indptr, indices, V, p->d_cb, nullptr, out, vec, s);
+        launch_float<MK_VQ>(p, c, p->d_cb, nullptr, vec);
     }
     return hipGetLastError();
 }

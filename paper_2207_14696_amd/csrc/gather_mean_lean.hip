@@ -45,30 +45,6 @@ int lean_capacity(int bits, bool wide) {
 
 namespace {
 
-struct __attribute__((aligned(4))) U3 { uint32_t x, y, z; };
-
-template <int CW>
-__device__ inline void load_words(const uint8_t *p, uint32_t *w) {
-    if constexpr (CW == 4) {
-        uint4 q = *reinterpret_cast<const uint4 *>(p);
-        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
-    } else if constexpr (CW == 3) {
-        U3 q = *reinterpret_cast<const U3 *>(p);
-        w[0] = q.x; w[1] = q.y; w[2] = q.z;
-    } else if constexpr (CW == 2) {
-        uint2 q = *reinterpret_cast<const uint2 *>(p);
-        w[0] = q.x; w[1] = q.y;
-    } else {
-        w[0] = *reinterpret_cast<const uint32_t *>(p);
-    }
-}
-
-__device__ inline void wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 constexpr int kWaves = kThreads / 64;
 #ifndef BF_LEAN_U
 #define BF_LEAN_U 4
@@ -84,12 +60,15 @@ constexpr int kWaves = kThreads / 64;
 // 2-bit logarithmic codes, whose decoded sum is linear in the two bit-plane
 // sums (see launch_gather_mean_lean_log2).  Dp = number of parameter columns
 // (D, or 2*D with PAIR).
-template <int BITS, int CW, bool WIDE, bool SUM, bool PAIR>
+// IT: the type of a list entry (int64_t or int32_t).  alone: no other kernel takes the lists
+// longer than thr (the caller promised there are none): such a list gets a row of NaNs and
+// raises the status word.
+template <int BITS, int CW, bool WIDE, bool SUM, bool PAIR, typename IT>
 __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel(
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int D, int Dp, const float *__restrict__ mn,
+    const IT *__restrict__ indices, int64_t V, int D, int Dp, const float *__restrict__ mn,
     const float *__restrict__ sc, const uint8_t *__restrict__ zero_row, float *__restrict__ out,
-    int lpr_log2, int chunks, int thr, int lo) {
+    int lpr_log2, int chunks, int thr, int lo, int alone, int32_t *__restrict__ status) {
     using W = LeanSwar<BITS, WIDE>;
     constexpr int R = CW * W::kN;   // accumulator registers per lane
     constexpr int CPW = 32 / BITS;  // codes per word
@@ -133,18 +112,23 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
         const int64_t n64 = end - beg;
         // longer lists: the general kernel; lists of up to `lo`: an earlier launch of the narrow form
         const bool mine = d_local < ndst && n64 <= thr && n64 > lo;
-        if (__ballot(mine) == 0) continue;  // nothing for this launch in the tile
+        const bool over = alone && d_local < ndst && n64 > thr;  // a broken promise
+        if (__ballot(mine || over) == 0) continue;  // nothing for this launch in the tile
         const int n = mine ? (int)n64 : 0;
-        if (lane_chunk == 0)
-            meta[d_local] = mine ? (n > 0 ? (SUM ? (float)n : 1.0f / (float)n) : 0.0f) : -1.0f;
+        if (lane_chunk == 0) {
+            // > 0: scale of the sum; 0: empty list; < 0: another kernel's destination; NaN: over
+            meta[d_local] = mine ? (n > 0 ? (SUM ? (float)n : 1.0f / (float)n) : 0.0f)
+                                 : (over ? __builtin_nanf("") : -1.0f);
+            if (over) raise_status(status, kStatusListTooLong);
+        }
 
         uint32_t acc[R];
 #pragma unroll
         for (int r = 0; r < R; r++) acc[r] = 0u;
-        const int64_t *ip = indices + beg;
+        const IT *ip = indices + beg;
         const int cnt = chunk_ok ? n : 0;
         for (int k = 0; k < cnt; k += U) {
-            int64_t row[U];
+            IT row[U];
             uint32_t w[U][CW];
 #pragma unroll
             for (int u = 0; u < U; u++) row[u] = ip[min(k + u, cnt - 1)];
@@ -254,7 +238,8 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
                 val.w = some ? fmaf(a.w, (float)sum[3] * md, b.w) : 0.0f;
             }
             }
-            if (md >= 0.0f) store_stream(&span[m], val);  // md < 0: not this kernel's destination
+            if (md != md) val.x = val.y = val.z = val.w = md;  // list beyond the promised bound
+            if (!(md < 0.0f)) store_stream(&span[m], val);  // md < 0: not this kernel's destination
             d += step_d;
             f += step_f;
             if (f >= nf4) {
@@ -266,33 +251,22 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
     }
 }
 
-inline int pow2ceil(int x) {
-    int p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
-inline int ilog2(int x) {
-    int l = 0;
-    while ((1 << l) < x) l++;
-    return l;
-}
-
 template <int BITS, bool WIDE, bool PAIR>
-bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                      const int64_t *indices, int64_t V, float *out, int thr, int lo, const float *mn,
-                      const float *sc, hipStream_t s) {
+bool launch_lean_bits(bifeat_params *p, const MeanCall &c, int thr, int lo, bool alone,
+                      const float *mn, const float *sc) {
     using W = LeanSwar<BITS, WIDE>;
+    const int64_t V = c.V;
     const int64_t rb = p->rb;
     int cw = 0;
     double best_eff = -1.0;
-    for (int c = 4; c >= 1; c--) {
-        if (rb % (4 * c)) continue;
-        const int chunks = (int)(rb / (4 * c));
+    for (int cand = 4; cand >= 1; cand--) {
+        if (rb % (4 * cand)) continue;
+        const int chunks = (int)(rb / (4 * cand));
         if (chunks > 64) continue;
         const double eff = (double)chunks / pow2ceil(chunks);
         if (eff > best_eff + 1e-9) {
             best_eff = eff;
-            cw = c;
+            cw = cand;
         }
     }
     if (!cw) return false;  // packed row longer than 64 lane loads
@@ -306,16 +280,19 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
     const int D = (int)p->D, Dp = PAIR ? 2 * D : D;
     const int R = cw * W::kN;
     const size_t shm = sizeof(uint32_t) * ((size_t)2 * Dp + 64 * kWaves + (size_t)kWaves * 64 * R);
-#define BF_LN(CWV)                                                                               \
-    do {                                                                                         \
-        if (p->agg_sum)                                                                          \
-            gather_mean_lean_kernel<BITS, CWV, WIDE, true, PAIR><<<blocks, kThreads, shm, s>>>(  \
-                codes, (uint32_t)rb, indptr, indices, V, D, Dp, mn, sc, p->d_zero, out,          \
-                ilog2(lpr), chunks, thr, lo);                                                        \
-        else                                                                                     \
-            gather_mean_lean_kernel<BITS, CWV, WIDE, false, PAIR><<<blocks, kThreads, shm, s>>>( \
-                codes, (uint32_t)rb, indptr, indices, V, D, Dp, mn, sc, p->d_zero, out,          \
-                ilog2(lpr), chunks, thr, lo);                                                        \
+#define BF_LK(CWV, SUMV, IT)                                                                   \
+    gather_mean_lean_kernel<BITS, CWV, WIDE, SUMV, PAIR, IT><<<blocks, kThreads, shm, c.s>>>(      \
+        c.codes, (uint32_t)rb, c.indptr, (const IT *)c.indices, V, D, Dp, mn, sc, p->d_zero,       \
+        c.out, ilog2(lpr), chunks, thr, lo, alone ? 1 : 0, c.status)
+#define BF_LN(CWV)                                                                                 \
+    do {                                                                                           \
+        if (c.agg_sum) {                                                                           \
+            if (c.idx32) BF_LK(CWV, true, int32_t);                                                \
+            else BF_LK(CWV, true, int64_t);                                                        \
+        } else {                                                                                   \
+            if (c.idx32) BF_LK(CWV, false, int32_t);                                               \
+            else BF_LK(CWV, false, int64_t);                                                       \
+        }                                                                                          \
     } while (0)
     switch (cw) {
         case 4: BF_LN(4); break;
@@ -324,6 +301,7 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
         default: BF_LN(1); break;
     }
 #undef BF_LN
+#undef BF_LK
     return true;
 }
 
@@ -332,19 +310,18 @@ bool launch_lean_bits(bifeat_params *p, const uint8_t *codes, const int64_t *ind
 // Launches the short-list kernel (lists of more than `lo` and at most `thr` rows; wide =
 // the form with the larger field capacity); returns false (nothing launched) when the
 // table's shape is outside what it handles.
-bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, float *out, int thr, bool wide, int lo,
-                             hipStream_t s) {
+bool launch_gather_mean_lean(bifeat_params *p, const MeanCall &c, int thr, bool wide, int lo,
+                             bool alone) {
     const float *mn = p->d_min, *sc = p->d_scale;
     switch (p->scheme.bits) {
         case 1:
-            return wide ? launch_lean_bits<1, true, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s)
-                        : launch_lean_bits<1, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
-        case 2: return launch_lean_bits<2, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
+            return wide ? launch_lean_bits<1, true, false>(p, c, thr, lo, alone, mn, sc)
+                        : launch_lean_bits<1, false, false>(p, c, thr, lo, alone, mn, sc);
+        case 2: return launch_lean_bits<2, false, false>(p, c, thr, lo, alone, mn, sc);
         case 4:
-            return wide ? launch_lean_bits<4, true, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s)
-                        : launch_lean_bits<4, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
-        default: return launch_lean_bits<8, false, false>(p, codes, indptr, indices, V, out, thr, lo, mn, sc, s);
+            return wide ? launch_lean_bits<4, true, false>(p, c, thr, lo, alone, mn, sc)
+                        : launch_lean_bits<4, false, false>(p, c, thr, lo, alone, mn, sc);
+        default: return launch_lean_bits<8, false, false>(p, c, thr, lo, alone, mn, sc);
     }
 }
 
@@ -355,13 +332,10 @@ bool launch_gather_mean_lean(bifeat_params *p, const uint8_t *codes, const int64
 // is therefore read as 2*D one-bit columns (bit 2t = b0, bit 2t+1 = b1 of column t) by the
 // 1-bit kernel, with those two affine maps as per-bit-column parameters (p->d_min / d_scale,
 // 2*D entries each), and the epilogue adds each pair.
-bool launch_gather_mean_lean_log2(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                                  const int64_t *indices, int64_t V, float *out, int thr, bool wide,
-                                  int lo, hipStream_t s) {
-    return wide ? launch_lean_bits<1, true, true>(p, codes, indptr, indices, V, out, thr, lo, p->d_min,
-                                                  p->d_scale, s)
-                : launch_lean_bits<1, false, true>(p, codes, indptr, indices, V, out, thr, lo, p->d_min,
-                                                   p->d_scale, s);
+bool launch_gather_mean_lean_log2(bifeat_params *p, const MeanCall &c, int thr, bool wide, int lo,
+                                  bool alone) {
+    return wide ? launch_lean_bits<1, true, true>(p, c, thr, lo, alone, p->d_min, p->d_scale)
+                : launch_lean_bits<1, false, true>(p, c, thr, lo, alone, p->d_min, p->d_scale);
 }
 
 }  // namespace bf

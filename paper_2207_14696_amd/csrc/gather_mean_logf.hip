@@ -17,17 +17,14 @@ namespace {
 constexpr int kLogfWaves = kThreads / 64;
 constexpr int kLogfU = 3;  // neighbour rows in flight per lane (2: 7 % slower, 4: no faster)
 
-__device__ inline void logf_wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <int BITS>
+// IT: the type of a list entry (int64_t or int32_t).  alone: no other kernel takes the lists
+// longer than thr: such a list gets a row of NaNs and raises the status word.
+template <int BITS, typename IT>
 __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ table,
-    float *__restrict__ out, int lpr_log2, int chunks, int thr, int agg_sum) {
+    const IT *__restrict__ indices, int64_t V, int D, const float *__restrict__ table,
+    float *__restrict__ out, int lpr_log2, int chunks, int thr, int agg_sum, int alone,
+    int32_t *__restrict__ status) {
     constexpr int CPW = 32 / BITS;    // codes per 32-bit word
     constexpr int CPL = 4 * CPW;      // columns per lane (16 bytes of codes)
     constexpr int NS = CPL / 4;       // 16-byte slots of decoded values per lane
@@ -67,18 +64,22 @@ __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
         }
         const int64_t n64 = end - beg;
         const bool mine = d_local < ndst && n64 <= thr;  // longer lists: the general kernel
-        if (__ballot(mine) == 0) continue;               // nothing for this launch in the tile
+        const bool over = alone && d_local < ndst && n64 > thr;  // a broken promise
+        if (__ballot(mine || over) == 0) continue;       // nothing for this launch in the tile
         const int n = mine ? (int)n64 : 0;
-        if (lane_chunk == 0)
-            meta[d_local] = mine ? (n > 0 ? (agg_sum ? 1.0f : 1.0f / (float)n) : 0.0f) : -1.0f;
+        if (lane_chunk == 0) {
+            meta[d_local] = mine ? (n > 0 ? (agg_sum ? 1.0f : 1.0f / (float)n) : 0.0f)
+                                 : (over ? __builtin_nanf("") : -1.0f);
+            if (over) raise_status(status, kStatusListTooLong);
+        }
 
         float acc[CPL];
 #pragma unroll
         for (int j = 0; j < CPL; j++) acc[j] = 0.0f;
-        const int64_t *ip = indices + beg;
+        const IT *ip = indices + beg;
         const int cnt = chunk_ok ? n : 0;
         for (int k = 0; k < cnt; k += kLogfU) {
-            int64_t row[kLogfU];
+            IT row[kLogfU];
             uint4 w[kLogfU];
 #pragma unroll
             for (int u = 0; u < kLogfU; u++) row[u] = ip[min(k + u, cnt - 1)];
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
             for (int s = 0; s < NS; s++)
                 sp[s ^ swz] = make_float4(acc[4 * s], acc[4 * s + 1], acc[4 * s + 2], acc[4 * s + 3]);
         }
-        logf_wave_sync();
+        wave_sync();
 
         // ---- the tile's output rows, one contiguous span of ndst * nf4 float4 granules
         float4 *span = reinterpret_cast<float4 *>(out + v_tile * D);
@@ -119,9 +120,10 @@ __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
             const float4 q = *reinterpret_cast<const float4 *>(
                 stage + ((d << lpr_log2) + owner) * CPL + 4 * (slot ^ (owner & (NS - 1))));
             const bool some = md > 0.0f;  // md == 0: empty list, zero row
-            const float4 val = make_float4(some ? q.x * md : 0.0f, some ? q.y * md : 0.0f,
-                                           some ? q.z * md : 0.0f, some ? q.w * md : 0.0f);
-            if (md >= 0.0f) store_stream(&span[m], val);  // md < 0: not this kernel's destination
+            float4 val = make_float4(some ? q.x * md : 0.0f, some ? q.y * md : 0.0f,
+                                     some ? q.z * md : 0.0f, some ? q.w * md : 0.0f);
+            if (md != md) val.x = val.y = val.z = val.w = md;  // list beyond the promised bound
+            if (!(md < 0.0f)) store_stream(&span[m], val);  // md < 0: not this kernel's destination
             d += step_d;
             f += step_f;
             if (f >= nf4) {
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
                 d++;
             }
         }
-        logf_wave_sync();  // the stage is rewritten by the next tile
+        wave_sync();  // the stage is rewritten by the next tile
     }
 }
 
@@ -140,28 +142,31 @@ __global__ __launch_bounds__(kThreads) void gather_mean_logf_kernel(
 int logf_capacity() { return 64; }
 
 // False (nothing launched) when the shape is outside what the kernel handles.
-bool launch_gather_mean_logf(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, float *out, int thr, hipStream_t s) {
+bool launch_gather_mean_logf(bifeat_params *p, const MeanCall &c, int thr, bool alone) {
     const int bits = p->scheme.bits;
     const int64_t c16 = p->rb / 16;
-    if ((bits != 4 && bits != 8) || p->D % 4 || (uintptr_t)out % 16 || (uintptr_t)codes % 16 ||
-        c16 > 64 || V <= 0)
+    if ((bits != 4 && bits != 8) || p->D % 4 || (uintptr_t)c.out % 16 || (uintptr_t)c.codes % 16 ||
+        c16 > 64 || c.V <= 0)
         return false;
     int lpr_log2 = 0;
     while ((1 << lpr_log2) < c16) lpr_log2++;
     const int dpw = 64 >> lpr_log2;
-    const int64_t tiles = (V + dpw - 1) / dpw;
+    const int64_t tiles = (c.V + dpw - 1) / dpw;
     const int64_t want = (tiles + kLogfWaves - 1) / kLogfWaves;
     const int64_t cap = p->opt_mean_blocks > 0 ? p->opt_mean_blocks : (1 << 16);
     const int blocks = (int)(want < cap ? want : cap);
-    if (bits == 4)
-        gather_mean_logf_kernel<4><<<blocks, kThreads, 0, s>>>(codes, (uint32_t)p->rb, indptr, indices, V,
-                                                              (int)p->D, p->d_V, out, lpr_log2,
-                                                              (int)c16, thr, p->agg_sum);
-    else
-        gather_mean_logf_kernel<8><<<blocks, kThreads, 0, s>>>(codes, (uint32_t)p->rb, indptr, indices, V,
-                                                              (int)p->D, p->d_V, out, lpr_log2,
-                                                              (int)c16, thr, p->agg_sum);
+#define BF_LF(B, IT)                                                                              \
+    gather_mean_logf_kernel<B, IT><<<blocks, kThreads, 0, c.s>>>(                                 \
+        c.codes, (uint32_t)p->rb, c.indptr, (const IT *)c.indices, c.V, (int)p->D, p->d_V, c.out, \
+        lpr_log2, (int)c16, thr, c.agg_sum, alone ? 1 : 0, c.status)
+    if (bits == 4) {
+        if (c.idx32) BF_LF(4, int32_t);
+        else BF_LF(4, int64_t);
+    } else {
+        if (c.idx32) BF_LF(8, int32_t);
+        else BF_LF(8, int64_t);
+    }
+#undef BF_LF
     return true;
 }
 

@@ -50,32 +50,6 @@ template <> struct Swar<1> {
     static constexpr int kCap0 = 15, kCap1 = 255;
 };
 
-struct __attribute__((aligned(4))) U3 { uint32_t x, y, z; };
-
-template <int CW>
-__device__ inline void load_words(const uint8_t *p, uint32_t *w) {
-    if constexpr (CW == 4) {
-        uint4 q = *reinterpret_cast<const uint4 *>(p);
-        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
-    } else if constexpr (CW == 3) {
-        U3 q = *reinterpret_cast<const U3 *>(p);
-        w[0] = q.x; w[1] = q.y; w[2] = q.z;
-    } else if constexpr (CW == 2) {
-        uint2 q = *reinterpret_cast<const uint2 *>(p);
-        w[0] = q.x; w[1] = q.y;
-    } else {
-        w[0] = *reinterpret_cast<const uint32_t *>(p);
-    }
-}
-
-// orders this wave's LDS writes before its later LDS reads (all lanes of a wave
-// execute each DS instruction together, in program order)
-__device__ inline void wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 enum : uint32_t { F_SKIP = 1u, F_MORE = 2u, F_PREV = 4u, F_EMPTY = 8u };
 
 constexpr int kWaves = kThreads / 64;
@@ -86,10 +60,10 @@ constexpr int kWaves = kThreads / 64;
 #define BF_SWAR_U 4
 #endif
 
-template <int BITS, int CW, bool VEC>
+template <int BITS, int CW, bool VEC, typename IT>
 __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr,
-    const int64_t *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
+    const IT *__restrict__ indices, int64_t V, int D, const float *__restrict__ mn,
     const float *__restrict__ sc, float *__restrict__ out, int lpr_log2, int s_log2, int chunks,
     int long_thr, int min_len, int agg_sum) {
     using W = Swar<BITS>;
@@ -198,12 +172,12 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
                             // and are masked, so all U index loads, then all U row loads,
                             // are in flight together
                             uint32_t w[U][CW];
-                            int64_t row[U];
+                            IT row[U];
 #pragma unroll
                             for (int u = 0; u < U; u++)
                                 row[u] = indices[min(e + (int64_t)u * S, rend - 1)];
 #pragma unroll
-                            for (int u = 0; u < U; u++) load_words<CW>(cptr + row[u] * rb, w[u]);
+                            for (int u = 0; u < U; u++) load_words<CW>(cptr + (int64_t)row[u] * rb, w[u]);
 #pragma unroll
                             for (int u = 0; u < U; u++) {
                                 const uint32_t keep = (chunk_ok && e + (int64_t)u * S < rend) ? ~0u : 0u;
@@ -413,36 +387,23 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
     }
 }
 
-static inline int pow2ceil(int x) {
-    int p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
-static inline int ilog2(int x) {
-    int l = 0;
-    while ((1 << l) < x) l++;
-    return l;
-}
-
 template <int BITS>
-static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                        const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
-                        int min_len, hipStream_t s) {
+static void launch_swar(bifeat_params *p, const MeanCall &c, int vec, int min_len) {
     using W = Swar<BITS>;
-    const int64_t rb = p->rb;
+    const int64_t rb = p->rb, V = c.V, E = c.E;
     // words per lane: every row chunk must be whole; prefer the choice that
     // leaves the fewest idle lanes, then the widest load
     int cw = 4;
     double best_eff = -1.0;
-    for (int c = 4; c >= 1; c--) {
-        if (rb % (4 * c)) continue;
-        int chunks = (int)(rb / (4 * c));
+    for (int cand = 4; cand >= 1; cand--) {
+        if (rb % (4 * cand)) continue;
+        int chunks = (int)(rb / (4 * cand));
         int lpr = pow2ceil(chunks > 64 ? 64 : chunks);
         int passes = (chunks + lpr - 1) / lpr;
         double eff = (double)chunks / ((double)lpr * passes);
         if (eff > best_eff + 1e-9) {
             best_eff = eff;
-            cw = c;
+            cw = cand;
         }
     }
     const int chunks = (int)(rb / (4 * cw));
@@ -467,16 +428,19 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
     const int Dp = ((int)p->D + 3) & ~3;
     const int R1 = cw * W::kN1;
     const size_t shm = sizeof(uint32_t) * ((size_t)2 * Dp + 2 * 64 * kWaves + (size_t)kWaves * (64 / S) * R1);
+#define BF_SK(CWV, VECV, IT)                                                                       \
+    gather_mean_swar_kernel<BITS, CWV, VECV, IT><<<blocks, kThreads, shm, c.s>>>(                  \
+        c.codes, rb, c.indptr, (const IT *)c.indices, V, (int)p->D, p->d_min, p->d_scale, c.out,   \
+        ilog2(lpr), ilog2(S), chunks, long_thr, min_len, c.agg_sum)
 #define BF_SW(CWV)                                                                                 \
     do {                                                                                           \
-        if (vec)                                                                                   \
-            gather_mean_swar_kernel<BITS, CWV, true><<<blocks, kThreads, shm, s>>>(                \
-                codes, rb, indptr, indices, V, (int)p->D, p->d_min, p->d_scale, out, ilog2(lpr),   \
-                ilog2(S), chunks, long_thr, min_len, p->agg_sum);                                                       \
-        else                                                                                       \
-            gather_mean_swar_kernel<BITS, CWV, false><<<blocks, kThreads, shm, s>>>(               \
-                codes, rb, indptr, indices, V, (int)p->D, p->d_min, p->d_scale, out, ilog2(lpr),   \
-                ilog2(S), chunks, long_thr, min_len, p->agg_sum);                                                       \
+        if (vec) {                                                                                 \
+            if (c.idx32) BF_SK(CWV, true, int32_t);                                                \
+            else BF_SK(CWV, true, int64_t);                                                        \
+        } else {                                                                                   \
+            if (c.idx32) BF_SK(CWV, false, int32_t);                                               \
+            else BF_SK(CWV, false, int64_t);                                                       \
+        }                                                                                          \
     } while (0)
     switch (cw) {
         case 4: BF_SW(4); break;
@@ -485,16 +449,15 @@ static void launch_swar(bifeat_params *p, const uint8_t *codes, const int64_t *i
         default: BF_SW(1); break;
     }
 #undef BF_SW
+#undef BF_SK
 }
 
-void launch_gather_mean_swar(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                             const int64_t *indices, int64_t V, int64_t E, float *out, int vec,
-                             int min_len, hipStream_t s) {
+void launch_gather_mean_swar(bifeat_params *p, const MeanCall &c, int vec, int min_len) {
     switch (p->scheme.bits) {
-        case 1: launch_swar<1>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
-        case 2: launch_swar<2>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
-        case 4: launch_swar<4>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
-        default: launch_swar<8>(p, codes, indptr, indices, V, E, out, vec, min_len, s); break;
+        case 1: launch_swar<1>(p, c, vec, min_len); break;
+        case 2: launch_swar<2>(p, c, vec, min_len); break;
+        case 4: launch_swar<4>(p, c, vec, min_len); break;
+        default: launch_swar<8>(p, c, vec, min_len); break;
     }
 }
 

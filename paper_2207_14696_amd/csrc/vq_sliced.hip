@@ -62,12 +62,6 @@ VqGeom vq_geometry(const bifeat_params *p) {
     return g;
 }
 
-__device__ inline void wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Entries per plane: the request count plus slack, so that kernels may read a
 // few entries past the end of a list (and mask them) and the pre-pass may write
 // whole 16-byte chunks; a multiple of 16 keeps every plane 64-byte aligned.
@@ -79,8 +73,9 @@ constexpr int kStripK = 4;  // row batches per wave tile of the pre-pass
 // k*MS.  A wave fetches kStripK batches of 64/c16 whole rows (16 bytes per lane),
 // parks them in LDS and writes each plane's piece of the tile as one contiguous
 // run of 16-byte stores.
+template <typename IT>
 __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
-    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int NPW,
+    const uint4 *__restrict__ codes16, int c16, const IT *__restrict__ idx, int64_t M, int NPW,
     int64_t MS, uint32_t *__restrict__ planes) {
     constexpr int K = kStripK;
     __shared__ uint4 s_raw[(kThreads / 64) * K * 64];
@@ -97,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
 #pragma unroll
         for (int k = 0; k < K; k++) {
             const int rr = min(k * RT + r, nrow - 1);
-            v[k] = codes16[idx[row0 + rr] * c16 + c];
+            v[k] = codes16[(int64_t)idx[row0 + rr] * c16 + c];
         }
         if (r < RT) {
 #pragma unroll
@@ -118,16 +113,19 @@ __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
     }
 }
 
-void launch_planes(bifeat_params *p, const uint8_t *codes, const int64_t *idx, int64_t M,
-                   hipStream_t s) {
+void launch_planes(bifeat_params *p, const uint8_t *codes, const void *idx, bool idx32, int64_t M,
+                   uint32_t *planes, hipStream_t s) {
     const int c16 = (int)(p->rb / 16), TR = (64 / c16) * kStripK;
     const int64_t tiles = (M + TR - 1) / TR;
     int64_t blocks = (tiles + 3) / 4;
     if (blocks > (1 << 16)) blocks = 1 << 16;
     if (blocks < 1) blocks = 1;
-    vq_planes_kernel<<<(unsigned)blocks, kThreads, 0, s>>>((const uint4 *)codes, c16, idx, M,
-                                                         (int)(p->rb / 4), plane_entries(M),
-                                                         (uint32_t *)p->d_scratch);
+    if (idx32)
+        vq_planes_kernel<int32_t><<<(unsigned)blocks, kThreads, 0, s>>>(
+            (const uint4 *)codes, c16, (const int32_t *)idx, M, (int)(p->rb / 4), plane_entries(M), planes);
+    else
+        vq_planes_kernel<int64_t><<<(unsigned)blocks, kThreads, 0, s>>>(
+            (const uint4 *)codes, c16, (const int64_t *)idx, M, (int)(p->rb / 4), plane_entries(M), planes);
 }
 
 // workgroup b serves slice b % NS as that slice's (b / NS)-th of ny workgroups
@@ -319,7 +317,7 @@ template <int CPL>
 __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
     const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr, int64_t V,
     int D, int P, int w, int len, int SP, int NS, int lps_log2, int cbytes, int agg_sum,
-    const float *__restrict__ cb, float *__restrict__ out) {
+    const float *__restrict__ cb, float *__restrict__ out, int alone, int32_t *__restrict__ status) {
     extern __shared__ float s_cb[];
     const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2, cbytes);
     load_slice(s_cb, cb, L.slice, SP, P, len, w);
@@ -364,6 +362,14 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
 #pragma unroll
             for (int k = 0; k < CPL; k++) res[k] = acc[k] * inv_n;
             L.store(out, v, D, res);
+        } else if (alone && L.active && v < V) {
+            // no long-list pass follows (the caller promised short lists): a row of NaNs
+            // instead of stale memory, and the handle's status word is raised
+            float res[CPL];
+#pragma unroll
+            for (int k = 0; k < CPL; k++) res[k] = __builtin_nanf("");
+            L.store(out, v, D, res);
+            if (L.g == 0 && L.slice == 0) raise_status(status, kStatusListTooLong);
         }
         asm volatile("" ::: "memory");
         beg = beg1, n = n1;
@@ -406,12 +412,6 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_long_kernel(
     }
 }
 
-inline int ilog2(int x) {
-    int l = 0;
-    while ((1 << l) < x) l++;
-    return l;
-}
-
 // The slice plus its zero row can exceed the 64 KB a workgroup gets by default.
 template <typename Kern>
 bool allow_lds(Kern kern, size_t bytes) {
@@ -437,10 +437,16 @@ int sliced_grid(const bifeat_params *p, int64_t wave_tiles, int64_t dflt, int NS
 
 }  // namespace
 
+size_t vq_gather_scratch_bytes(const bifeat_params *p, int64_t M) {
+    return (size_t)p->rb * (size_t)plane_entries(M);
+}
+
 // All return false (nothing launched) when the codebook shape is outside what
 // the sliced kernels handle (width not a power of two >= 4, D % width != 0, ...).
+// planes: the workspace for the transposed codes (vq_gather_scratch_bytes(p, M) bytes), or
+// nullptr for the handle's own, grown as needed.
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
-                                     int64_t M, float *out, hipStream_t s) {
+                                     int64_t M, float *out, hipStream_t s, uint32_t *planes) {
     const VqGeom g = vq_geometry(p);
     if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
     // a slice narrower than 256 bytes of output per row makes the stores too fine-grained
@@ -448,52 +454,52 @@ bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, con
     if (g.LPS < 16) return false;
     if (!allow_lds(gather_dequant_vq_sliced_kernel, g.lds)) return false;
     const int64_t MS = plane_entries(M);
-    if (!ensure_scratch(p, (size_t)p->rb * MS)) return false;
-    launch_planes(p, codes, idx, M, s);
+    if (!planes) {
+        if (!ensure_scratch(p, (size_t)p->rb * MS, s)) return false;
+        planes = (uint32_t *)p->d_scratch;
+    }
+    launch_planes(p, codes, idx, false, M, planes, s);
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int rpw = 64 / g.LPS;
     const int64_t tiles = (M + rpw - 1) / rpw;
     const int grid = sliced_grid(p, (tiles + BF_VQ_U - 1) / BF_VQ_U * g.NS, 2048, g.NS);
     gather_dequant_vq_sliced_kernel<<<grid, kVqThreads, g.lds, s>>>(
-        (const uint32_t *)p->d_scratch, M, MS, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS),
+        planes, M, MS, (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(g.LPS),
         p->cbytes, p->d_cb, out);
     return true;
 }
 
-// With the caller's bound on the list lengths (option mean_max_degree) at most
-// kRun, the long-list pass is not launched at all.
-bool launch_gather_mean_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *indptr,
-                                  const int64_t *indices, int64_t V, int64_t E, float *out,
-                                  hipStream_t s) {
+// With the caller's bound on the list lengths at most kRun, the long-list pass is not
+// launched at all (a longer list then gets a row of NaNs and raises the status word).
+bool launch_gather_mean_vq_sliced(bifeat_params *p, const MeanCall &c) {
     const VqGeom g = vq_geometry(p);
-    if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
-    const int64_t MS = plane_entries(E);
+    if (!g.ok || (uintptr_t)c.out % 16 || p->rb / 16 > 64) return false;
+    const int64_t MS = plane_entries(c.E);
     if (p->rb * MS >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int cpl = w % 8 == 0 ? 8 : 4;  // columns per lane
-    const bool with_long = !(p->opt_mean_max_degree > 0 && p->opt_mean_max_degree <= kRun);
+    const bool with_long = !(c.max_degree > 0 && c.max_degree <= kRun);
     if (cpl == 8 ? !(allow_lds(gather_mean_vq_short_kernel<8>, g.lds) &&
                      allow_lds(gather_mean_vq_long_kernel<8>, g.lds))
                  : !(allow_lds(gather_mean_vq_short_kernel<4>, g.lds) &&
                      allow_lds(gather_mean_vq_long_kernel<4>, g.lds)))
         return false;
-    if (!ensure_scratch(p, (size_t)p->rb * MS)) return false;
-    if (E > 0) launch_planes(p, codes, indices, E, s);
+    if (!ensure_scratch(p, (size_t)p->rb * MS, c.s)) return false;
+    if (c.E > 0) launch_planes(p, c.codes, c.indices, c.idx32, c.E, (uint32_t *)p->d_scratch, c.s);
     const int lps = g.LPS * 4 / cpl, rpw = 64 / lps;
-    const int64_t tiles = (V + rpw - 1) / rpw;
+    const int64_t tiles = (c.V + rpw - 1) / rpw;
     const int grid = sliced_grid(p, tiles * g.NS, 1024, g.NS);
-#define BF_VQL(KERNEL)                                                                       \
-    KERNEL<<<grid, kVqThreads, g.lds, s>>>((const uint32_t *)p->d_scratch, MS, indptr, V,     \
-                                           (int)p->D, p->P, w, len, g.SP, g.NS, ilog2(lps),   \
-                                           p->cbytes, p->agg_sum, p->d_cb, out)
+#define BF_VQA                                                                                  \
+    (const uint32_t *)p->d_scratch, MS, c.indptr, c.V, (int)p->D, p->P, w, len, g.SP, g.NS,     \
+        ilog2(lps), p->cbytes, c.agg_sum, p->d_cb, c.out
     if (cpl == 8) {
-        BF_VQL(gather_mean_vq_short_kernel<8>);
-        if (with_long) BF_VQL(gather_mean_vq_long_kernel<8>);
+        gather_mean_vq_short_kernel<8><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQA, with_long ? 0 : 1, c.status);
+        if (with_long) gather_mean_vq_long_kernel<8><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQA);
     } else {
-        BF_VQL(gather_mean_vq_short_kernel<4>);
-        if (with_long) BF_VQL(gather_mean_vq_long_kernel<4>);
+        gather_mean_vq_short_kernel<4><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQA, with_long ? 0 : 1, c.status);
+        if (with_long) gather_mean_vq_long_kernel<4><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQA);
     }
-#undef BF_VQL
+#undef BF_VQA
     return true;
 }
 

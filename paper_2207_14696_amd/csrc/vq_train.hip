@@ -191,18 +191,28 @@ void lloyd_round_generic(bifeat_params *p, const T *x, int64_t rows, float *dist
 
 }  // namespace
 
-bool ensure_scratch(bifeat_params *p, size_t bytes) {
+// The handle's workspace (transposed codes of a vector-code gather, code array of the generic
+// Lloyd rounds).  It only grows, and a buffer that was handed to kernels is never freed before
+// the handle is destroyed: work still in flight, and HIP graphs captured from earlier calls,
+// keep a valid address.  While `s` is being captured into a graph nothing is allocated: the
+// request then fails unless a call (or bifeat_reserve) at least as large ran before.
+bool ensure_scratch(bifeat_params *p, size_t bytes, hipStream_t s) {
     if (p->scratch_bytes >= bytes) return true;
-    if (p->d_scratch) (void)hipFree(p->d_scratch);  // waits for work that may still use it
-    p->d_scratch = nullptr;
-    p->scratch_bytes = 0;
-    void *q = nullptr;
-    if (hipMalloc(&q, bytes + bytes / 4) != hipSuccess) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess) {
         (void)hipGetLastError();
         return false;
     }
+    if (cap != hipStreamCaptureStatusNone) return false;
+    void *q = nullptr;
+    const size_t want = bytes + bytes / 4;
+    if (hipMalloc(&q, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (p->d_scratch) p->retired.push_back(p->d_scratch);
     p->d_scratch = (uint8_t *)q;
-    p->scratch_bytes = bytes + bytes / 4;
+    p->scratch_bytes = want;
     return true;
 }
 
@@ -220,7 +230,7 @@ hipError_t launch_vq_train(bifeat_params *p, const void *chunk, int dtype, int64
     const int w = p->scheme.vq_width, len = p->scheme.vq_length, P = p->P;
     const bool fused = p->scheme.vq_metric == BIFEAT_VQ_L2 && p->cbytes == 1 &&
                        sizeof(float) * ((size_t)2 * len * w + len) <= 65536;
-    if (!fused && !ensure_scratch(p, (size_t)rows * P * p->cbytes)) return hipErrorOutOfMemory;
+    if (!fused && !ensure_scratch(p, (size_t)rows * P * p->cbytes, s)) return hipErrorOutOfMemory;
     if (init) {
         if (dtype == BIFEAT_F32)
             vq_init_kernel<float><<<256, 256, 0, s>>>((const float *)chunk, (int)p->D, w, len, P, p->d_cb);

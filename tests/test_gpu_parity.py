@@ -382,9 +382,9 @@ def test_vq_variant_training_matches_oracle_distortion(bf, torch, D, w, length, 
     gcb = q.params_get_codebooks()
     gdist = q.vq_distortion(6)
     assert np.isfinite(gcb).all()
-    # same trajectory as the oracle's (fp32 atomic sums against fp64 means: small clusters
-    # may flip a few assignments, so the match is statistical)
-    assert np.allclose(gdist, odist, rtol=1e-2)
+    # same trajectory as the oracle's (fp32 atomic sums against fp64 means: measured agreement
+    # is ~5e-7 relative; the bounds are those of the one-byte Euclidean trainer's test)
+    assert np.allclose(gdist, odist, rtol=2e-3)
     bits = orc.vq_code_bits(length)
 
     def distortion(cb):
@@ -392,7 +392,7 @@ def test_vq_variant_training_matches_oracle_distortion(bf, torch, D, w, length, 
         dec = orc.gather_dequant(s, orc.pack(orc.vq_assign(held, w, cb, metric=metric), bits),
                                  np.arange(len(held)))
         return ((dec.astype(np.float64) - held) ** 2).sum(1).mean()
-    assert distortion(gcb) <= 1.02 * distortion(ocb)
+    assert distortion(gcb) <= 1.01 * distortion(ocb)
     codes = gpu_build_table(q, _dev_table(spec), spec.N, 2500, fit=False)
     assert np.array_equal(codes.cpu().numpy(),
                           orc.pack(orc.vq_assign(x, w, gcb, metric=metric), bits))

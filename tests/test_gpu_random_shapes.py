@@ -200,9 +200,9 @@ def test_random_fits(bf, torch, case):
     mn, mx, scale, inv = q.params_get_uniform()
     omn, omx = orc.fit_minmax(x)
     assert np.array_equal(mn, omn) and np.array_equal(mx, omx)
-    if not with_inf:
-        osc, oinv = orc.uniform_params(omn, omx, bits)
-        assert np.array_equal(scale, osc) and np.array_equal(inv, oinv)
+    # (a column whose range is infinite has scale = inf and inv = 0 on both sides)
+    osc, oinv = orc.uniform_params(omn, omx, bits)
+    assert np.array_equal(scale, osc) and np.array_equal(inv, oinv)
 
     frac = float(rng.choice([0.0, 0.001, 0.01, 0.1, 0.3]))
     ql = bf.Quantizer(scheme_of("log", bits), D)

@@ -1,5 +1,6 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py
-times (L minibatches per launch, whole blocks).
+times (L minibatches per launch, whole blocks, every hop with the sampler's fan-out
+passed as the bound on the list lengths) and, next to it, without that bound.
 
 The tables are far too large for the oracle to sweep (up to 187 G values), so:
   * fitted per-column min/max are checked against torch.amin/amax over the same
@@ -7,10 +8,12 @@ The tables are far too large for the oracle to sweep (up to 187 G values), so:
     host (attainment) and every sampled row is checked to lie inside (bound);
     the workloads small enough (tiny, mid) also get the oracle's full fit;
   * scale / inv derived from them must equal the oracle's bit for bit;
-  * for a sample of destinations of the outermost block, and a sample of input
-    rows, the oracle regenerates exactly the table rows involved, encodes them
-    itself, and its packed rows / decoded rows / means are compared with what
-    the GPU produced from its resident table (codes bit-exact, floats 1e-5).
+  * for a sample of input rows, and - on every hop's block - for every destination
+    of the launch's first minibatch (up to 8192), contiguous runs in the middle and
+    at the end of the block and a random sample, the oracle regenerates exactly the
+    table rows involved, encodes them itself, and its packed rows / decoded rows /
+    means are compared with what the GPU produced from its resident table (codes
+    bit-exact, floats 1e-5).
 """
 import numpy as np
 import pytest
@@ -18,13 +21,15 @@ import pytest
 import oracle as orc
 from bifeat_inputs import (WORKLOADS, BATCHES_PER_STEP, make_graph, launch_set, feature_rows,
                            feature_chunk)
-from helpers import assert_close, scheme_of
+from helpers import assert_close, column_magnitude, scheme_of
 
 pytestmark = pytest.mark.gpu
 
 CHUNK = 1 << 20
 N_DST_SAMPLE = 192
 N_ROW_SAMPLE = 1024
+RUN = 1024                     # contiguous destinations checked in the middle and at the end
+FIRST_MINIBATCH_CAP = 8192     # destinations of the first minibatch checked (all, up to this)
 
 
 @pytest.fixture(scope="module")
@@ -100,8 +105,28 @@ def _oracle_rows(w, rows, encode):
     return x, encode(x)
 
 
+def _dst_sample(w, g, h, indptr, rng):
+    """Destinations of hop h whose rows are compared: every destination of the launch-set's
+    first minibatch (a whole minibatch as one launch serves it), contiguous runs in the
+    middle and at the very end (tile tails, the last workgroup), the extremes of the list
+    lengths, and a random sample."""
+    from bifeat_inputs import draw_seeds, sample_blocks
+    V = indptr.shape[0] - 1
+    deg = np.diff(indptr)
+    first = sample_blocks(g, draw_seeds(g, w.batch, w.seed, 0, w.seed_mode), w.fanouts, w.seed, 0)[0][h].V
+    first = min(first, V, FIRST_MINIBATCH_CAP)
+    run = min(RUN, V)
+    dst = np.concatenate([np.arange(first), np.arange(V // 2, min(V, V // 2 + run)), np.arange(V - run, V),
+                          rng.choice(V, size=min(N_DST_SAMPLE, V), replace=False),
+                          [int(deg.argmax()), int(deg.argmin())]])
+    return np.unique(dst)
+
+
 def _run_iteration_checks(torch, w, q, codes, s_of, encode, bound=None):
-    """The per-iteration calls as bench.py launches them, checked on samples."""
+    """The per-iteration calls as bench.py launches them - L minibatches per launch, and every
+    hop both with the sampler's fan-out passed as the bound on the list lengths (bench.py's
+    default: one short-list kernel per hop) and without it (the two- and three-kernel
+    launch sets) - checked against the oracle on sampled rows and destinations."""
     g = make_graph(w)
     L = BATCHES_PER_STEP[w.name]
     hops, inputs = launch_set(w, g, 0, L)
@@ -109,9 +134,21 @@ def _run_iteration_checks(torch, w, q, codes, s_of, encode, bound=None):
     d_inputs = torch.from_numpy(inputs).cuda()
     feats = q.gather_dequant(codes, d_inputs)
     rows_codes = q.gather_codes(codes, d_inputs)
-    outs = []
-    for indptr, indices in hops:
-        outs.append(q.gather_mean(codes, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()))
+    d_hops = [(torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()) for indptr, indices in hops]
+    outs = {}
+    for hinted in (True, False):
+        for h, (dp, di) in enumerate(d_hops):
+            q.set_option("mean_max_degree", w.fanouts[h] if hinted else 0)
+            outs[hinted, h] = q.gather_mean(codes, dp, di)
+        q.set_option("mean_max_degree", 0)
+        assert q.poll_status()          # the sampler keeps its promise: nothing raised
+    # 32-bit list entries on the outermost hop, as a loader with a table below 2^31 rows passes them
+    outer = len(hops) - 1
+    q.set_option("mean_max_degree", w.fanouts[outer])
+    out32 = q.gather_mean(codes, d_hops[outer][0], d_hops[outer][1].to(torch.int32))
+    q.set_option("mean_max_degree", 0)
+    assert torch.equal(out32, outs[True, outer])
+    del out32
     torch.cuda.synchronize()
 
     # ---- sampled input rows: packed bytes bit-exact, decoded rows within tolerance
@@ -126,20 +163,25 @@ def _run_iteration_checks(torch, w, q, codes, s_of, encode, bound=None):
     assert_close(feats[dpick].cpu().numpy(), orc.gather_dequant(s, ocodes, inv_map), s,
                  f"{w.name} gather_dequant")
 
-    # ---- sampled destinations of every hop's block
+    # ---- destinations of every hop's block
     for h, (indptr, indices) in enumerate(hops):
-        V = indptr.shape[0] - 1
-        deg = np.diff(indptr)
-        dst = rng.choice(V, size=min(N_DST_SAMPLE, V), replace=False)
-        dst = np.unique(np.concatenate([dst, [0, V - 1, int(deg.argmax()), int(deg.argmin())]]))
+        dst = _dst_sample(w, g, h, indptr, rng)
         lists = [indices[indptr[v]:indptr[v + 1]] for v in dst]
-        uniq = np.unique(np.concatenate(lists))
+        cat = np.concatenate(lists)
+        uniq = np.unique(cat)
         x, ocodes = _oracle_rows(w, uniq, encode)
         sub_ptr = np.concatenate([[0], np.cumsum([len(l) for l in lists])]).astype(np.int64)
-        sub_idx = np.searchsorted(uniq, np.concatenate(lists)).astype(np.int64)
+        sub_idx = np.searchsorted(uniq, cat).astype(np.int64)
         want = orc.gather_mean(s, ocodes, sub_ptr, sub_idx)
-        got = outs[h][torch.from_numpy(dst).cuda()].cpu().numpy()
-        assert_close(got, want, s, f"{w.name} gather_mean hop {h}")
+        ddst = torch.from_numpy(dst).cuda()
+        for hinted in (True, False):
+            got = outs[hinted, h][ddst].cpu().numpy()
+            assert_close(got, want, s, f"{w.name} gather_mean hop {h} "
+                                       f"{'with' if hinted else 'without'} the fan-out bound")
+        # the two launch sets must also agree with each other on every destination
+        a, b = outs[True, h], outs[False, h]
+        A = torch.from_numpy(column_magnitude(s).astype(np.float32)).cuda()[None, :]
+        assert bool(((a - b).abs() <= 2e-5 * torch.maximum(a.abs(), A)).all()), f"{w.name} hop {h}: launch sets differ"
 
 
 def _uniform_case(torch, bf, names):
@@ -261,6 +303,40 @@ def test_log_2bit_clipped(torch, bf):
     assert cnt[1] <= k_lo < cnt[2] and cnt[3] <= k_hi < cnt[4]
     oT, oV = orc.log_tables(e_min, e_max, w.bits)
     assert np.array_equal(T, oT) and np.array_equal(V, oV)
+    del buf
+    (codes,), *_ = _stream_table(torch, w, [q], fit=False)
+    _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
+        encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
+    del codes
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(900)
+def test_log_1bit(torch, bf):
+    # the paper's headline scalar setting (Sec. 3.1: one bit, the sign; Appendix C calls it
+    # practical for most cases) on the largest table: the streaming fit of the extreme
+    # magnitudes is checked against a library reduction over the same chunks
+    from bifeat_inputs.device import DeviceTable
+    w = WORKLOADS["log1"]
+    q = bf.Quantizer(scheme_of("log", w.bits), w.D)
+    table = DeviceTable(w.spec)
+    buf = torch.empty((CHUNK, w.D), dtype=table.torch_dtype, device="cuda")
+    q.fit_reset()
+    lo, hi = np.inf, 0.0
+    for r0 in range(0, w.N, CHUNK):
+        n = min(CHUNK, w.N - r0)
+        x = table.chunk(r0, n, buf[:n])
+        q.fit_update(x)
+        m = x.abs().float()
+        hi = max(hi, float(m.max()))
+        lo = min(lo, float(torch.where(m > 0, m, torch.full_like(m, float("inf"))).min()))
+    assert q.fit_finalize() is False
+    e_min, e_max, T, V = q.params_get_log()
+    assert (e_min, e_max) == orc.log_range(np.array([lo, hi], dtype=np.float32))
+    oT, oV = orc.log_tables(e_min, e_max, w.bits)
+    assert len(T) == 0 and np.array_equal(V, oV)
     del buf
     (codes,), *_ = _stream_table(torch, w, [q], fit=False)
     _run_iteration_checks(
