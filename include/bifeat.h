@@ -66,7 +66,8 @@ typedef enum {
     BIFEAT_EINVAL = -1,  /* bad argument (null pointer, unsupported bits, size <= 0, ...) */
     BIFEAT_ENOTFIT = -2, /* quantizer parameters not fitted / set yet */
     BIFEAT_EHIP = -3,    /* a HIP runtime call or kernel launch failed */
-    BIFEAT_ENOTSUP = -4  /* valid request this build does not implement */
+    BIFEAT_ENOTSUP = -4, /* valid request this build does not implement */
+    BIFEAT_ELIMIT = -5   /* request larger than a fixed limit (bifeat_gather_dequant_static) */
 } bifeat_status;
 
 typedef enum {
@@ -198,6 +199,22 @@ int bifeat_gather_codes(bifeat_params *p, const uint8_t *codes, int64_t N, const
                         int64_t M, uint8_t *out, void *stream);
 int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *idx,
                           int64_t M, float *out, void *stream);
+
+/* bifeat_gather_dequant for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same results.  The one workspace the decode
+ * kernels use (vector codes: the transposed codes of the M requested rows,
+ * row_bytes * (M rounded up to 16, + 16) bytes) is a fixed array of 32 MiB
+ * that is part of the library's device code, one copy per GPU, held until the
+ * process ends; a request that needs more returns BIFEAT_ELIMIT (about 349 000
+ * rows of 96 bytes; scalar codes use no workspace and have no limit).  The call
+ * allocates nothing and never synchronises; it needs the parameters fitted or
+ * set beforehand (that is when the handle's own device block is allocated) and
+ * option "validate" off (BIFEAT_ENOTSUP otherwise).  Every call on a GPU, from
+ * any handle or thread, shares that GPU's array: calls that overlap in time on
+ * one GPU race on it - order them on one stream or with events. */
+int bifeat_gather_dequant_static(bifeat_params *p, const uint8_t *codes, int64_t N,
+                                 const int64_t *idx, int64_t M, float *out, void *stream);
 
 /* ---- fused gather + decode + neighbourhood mean (Appendix A.1).
  * For v in [0, V): out[v, :] = mean over e in [indptr[v], indptr[v+1]) of

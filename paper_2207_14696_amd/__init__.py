@@ -8,9 +8,9 @@ no CPU fallback: if the library is missing, loading fails.
 from .binding import (Quantizer, Scheme, BifeatError, load_library, library_path,
                       aggregate_rows, scale_profile, check_lists,
                       UNIFORM, LOG, VQ, VQ_L2, VQ_COSINE, F32, F16,
-                      OK, EINVAL, ENOTFIT, EHIP, ENOTSUP, FIT_AGAIN)
+                      OK, EINVAL, ENOTFIT, EHIP, ENOTSUP, ELIMIT, FIT_AGAIN)
 
 __all__ = ["Quantizer", "Scheme", "BifeatError", "load_library", "library_path",
            "aggregate_rows", "scale_profile", "check_lists",
            "UNIFORM", "LOG", "VQ", "VQ_L2", "VQ_COSINE", "F32", "F16",
-           "OK", "EINVAL", "ENOTFIT", "EHIP", "ENOTSUP", "FIT_AGAIN"]
+           "OK", "EINVAL", "ENOTFIT", "EHIP", "ENOTSUP", "ELIMIT", "FIT_AGAIN"]

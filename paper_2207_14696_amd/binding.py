@@ -15,7 +15,7 @@ _LIB_PATH = os.environ.get("BIFEAT_LIB") or os.path.join(_HERE, "libbifeat.so")
 UNIFORM, LOG, VQ = 0, 1, 2
 VQ_L2, VQ_COSINE = 0, 1
 F32, F16 = 0, 1
-OK, EINVAL, ENOTFIT, EHIP, ENOTSUP = 0, -1, -2, -3, -4
+OK, EINVAL, ENOTFIT, EHIP, ENOTSUP, ELIMIT = 0, -1, -2, -3, -4, -5
 FIT_AGAIN = 1
 
 
@@ -63,6 +63,8 @@ _SIGNATURES = {
                                       C.c_void_p, C.c_void_p]),
     "bifeat_gather_dequant": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                         C.c_void_p, C.c_void_p]),
+    "bifeat_gather_dequant_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                               C.c_void_p, C.c_void_p]),
     "bifeat_gather_mean": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_gather_sum": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -256,6 +258,18 @@ class Quantizer:
         _check(self._lib.bifeat_gather_dequant(self._h, _dev_ptr(codes, (torch.uint8,)),
                                                codes.shape[0], _dev_ptr(idx, (torch.int64,)), M,
                                                _dev_ptr(out, (torch.float32,)), _stream()))
+        return out
+
+    def gather_dequant_static(self, codes, idx, out):
+        """``bifeat_gather_dequant_static``: as gather_dequant, allocating nothing (``out`` is
+        required; the workspace is the library's fixed per-GPU array)."""
+        import torch
+        M = idx.shape[0]
+        if out.shape != (M, self.D):
+            raise ValueError("out must be [M, D]")
+        _check(self._lib.bifeat_gather_dequant_static(
+            self._h, _dev_ptr(codes, (torch.uint8,)), codes.shape[0], _dev_ptr(idx, (torch.int64,)), M,
+            _dev_ptr(out, (torch.float32,)), _stream()))
         return out
 
     def _aggregate(self, fn64, fn32, codes, indptr, indices, out):

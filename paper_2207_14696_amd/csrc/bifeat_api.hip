@@ -592,6 +592,31 @@ int bifeat_gather_dequant(bifeat_params *p, const uint8_t *codes, int64_t N, con
     return BIFEAT_OK;
 }
 
+int bifeat_gather_dequant_static(bifeat_params *p, const uint8_t *codes, int64_t N,
+                                 const int64_t *idx, int64_t M, float *out, void *stream) {
+    if (!p || M < 0 || N < 0) return BIFEAT_EINVAL;
+    if (M > 0 && (!codes || !idx || !out || N == 0)) return BIFEAT_EINVAL;
+    if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;  // fitted parameters already live on the device
+    if (p->opt_validate) return BIFEAT_ENOTSUP;  // the checker synchronises: not for these callers
+    if (M == 0) return BIFEAT_OK;
+    uint32_t *planes = nullptr;
+    if (p->scheme.kind == BIFEAT_VQ) {
+        // only the vector-code kernels use a workspace: theirs is the static array here
+        if (bf::vq_gather_scratch_bytes(p, M) > bf::static_scratch_bytes()) {
+            g_hip_error = "bifeat_gather_dequant_static: request needs " +
+                          std::to_string(bf::vq_gather_scratch_bytes(p, M)) + " bytes of workspace, the static one holds " +
+                          std::to_string(bf::static_scratch_bytes());
+            return BIFEAT_ELIMIT;
+        }
+        uint8_t *ptr = nullptr;
+        BF_HIP(bf::static_scratch_ptr(&ptr));
+        planes = (uint32_t *)ptr;
+    }
+    BF_HIP(bf::launch_gather_dequant(p, codes, idx, M, out, (hipStream_t)stream, planes));
+    return BIFEAT_OK;
+}
+
 namespace {
 int gather_aggregate(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                      const void *indices, bool idx32, int64_t V, int64_t E, int agg_sum, float *out,
@@ -732,6 +757,8 @@ const char *bifeat_strerror(int status) {
         case BIFEAT_ENOTFIT: return "quantizer parameters not fitted";
         case BIFEAT_EHIP: return g_hip_error.empty() ? "HIP error" : g_hip_error.c_str();
         case BIFEAT_ENOTSUP: return "not supported";
+        case BIFEAT_ELIMIT:
+            return g_hip_error.empty() ? "request exceeds a fixed limit of the library" : g_hip_error.c_str();
         default: return "unknown status";
     }
 }

@@ -122,6 +122,10 @@ void launch_gather_mean_swar(bifeat_params *p, const MeanCall &c, int vec, int m
 bool ensure_scratch(bifeat_params *p, size_t bytes, hipStream_t s);
 // bytes of workspace a vector-code gather of M requested rows needs
 size_t vq_gather_scratch_bytes(const bifeat_params *p, int64_t M);
+// the library's fixed per-GPU workspace (a static device array): its size, and its address
+// on the current device
+size_t static_scratch_bytes();
+hipError_t static_scratch_ptr(uint8_t **out);
 // 1/|entry| for every codebook entry, fp64 inside (cosine metric)
 void launch_vq_rnorm(bifeat_params *p, hipStream_t s);
 // nearest-entry search of `rows` rows into codes_row0 (row stride rb bytes, indices of

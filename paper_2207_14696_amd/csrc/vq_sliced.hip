@@ -19,6 +19,8 @@
 // one 16-byte LDS read and one 16-byte store each; gather_mean: 8 columns where
 // the width allows); a wave covers 64/LPS rows (gather_dequant) or destinations
 // (gather_mean).
+#include <mutex>
+
 #include "common.hpp"
 
 namespace bf {
@@ -436,6 +438,38 @@ int sliced_grid(const bifeat_params *p, int64_t wave_tiles, int64_t dflt, int NS
 }
 
 }  // namespace
+
+// ---- the fixed workspace of bifeat_gather_dequant_static: one array per GPU, part of the
+// library's code object (every GPU the library runs on holds it until the process ends).
+// `scratch` is only a host-side stand-in for the symbol: the address kernels can use is
+// looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+uint8_t *g_static_ptr[kMaxDevices] = {};
+}  // namespace
+
+size_t static_scratch_bytes() { return kStaticScratchBytes; }
+
+// The current device's copy of the array (hipSuccess and *out set, or the HIP error).
+hipError_t static_scratch_ptr(uint8_t **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_static_ptr[dev] = (uint8_t *)ptr;
+    }
+    *out = g_static_ptr[dev];
+    return hipSuccess;
+}
 
 size_t vq_gather_scratch_bytes(const bifeat_params *p, int64_t M) {
     return (size_t)p->rb * (size_t)plane_entries(M);

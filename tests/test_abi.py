@@ -72,6 +72,17 @@ def test_argument_errors_come_before_any_gpu_call(bf):
     assert lib.bifeat_scale_profile(16, 10, 4, 16, 16, 5, 2, 16, None, None) == -1   # no result array
     assert lib.bifeat_check_lists(None, None, 3, 5, 10, None) == -1                  # no arrays
     assert lib.bifeat_check_lists(16, 16, -1, 5, 10, None) == -1
+    # 32-bit list entries, the status query, the workspace calls
+    assert lib.bifeat_gather_mean_i32(h, None, 10, None, None, 3, 7, None, None) == -1
+    assert lib.bifeat_gather_sum_i32(h, 16, 1 << 31, 16, 16, 1, 1, 16, None) == -1   # ids need 32 bits
+    assert lib.bifeat_gather_mean_i32(h, 16, 10, 16, 16, 1, 1, 16, None) == -2       # not fitted
+    assert lib.bifeat_poll_status(None, None, 0) == -1
+    assert lib.bifeat_poll_status(h, None, 0) == 0               # nothing raised, no device touched
+    assert lib.bifeat_reserve(None, 5, None) == -1
+    assert lib.bifeat_reserve(h, -5, None) == -1
+    assert lib.bifeat_reserve(h, 1000, None) == 0                # scalar codes: no workspace
+    assert lib.bifeat_gather_dequant_static(h, None, 10, None, 5, None, None) == -1
+    assert lib.bifeat_gather_dequant_static(h, 16, 10, 16, 5, 16, None) == -2        # not fitted
     assert lib.bifeat_set_option(h, b"no_such_option", 1) == -1
     assert lib.bifeat_set_option(h, b"mean_slots", 4) == 0
     assert lib.bifeat_row_bytes(None) == -1
