@@ -68,6 +68,9 @@ def parse_args():
                          "ratio) of this workload's codes on a materialised graph of the same family")
     ap.add_argument("--profile-nodes", type=int, default=1 << 20,
                     help="nodes (= leading rows of the table) of the scale-profile graph")
+    ap.add_argument("--idx32", action="store_true",
+                    help="pass the blocks' list entries as int32 (bifeat_gather_mean_i32): 4 instead of 8 "
+                         "index bytes per entry, in the traffic and in the algorithmic bytes")
     ap.add_argument("--aggregator", default="mean", choices=["mean", "sum"],
                     help="which fused aggregation the hops run (the metric's workload is mean)")
     return ap.parse_args()
@@ -191,7 +194,8 @@ def main():
         say(f"launch-set {si + 1} of {B} sampled")
     for s in sets:
         s["d_inputs"] = torch.from_numpy(s["inputs"]).to(dev)
-        s["d_hops"] = [(torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)) for a, b in s["hops"]]
+        s["d_hops"] = [(torch.from_numpy(a).to(dev),
+                        torch.from_numpy(b.astype(np.int32) if args.idx32 else b).to(dev)) for a, b in s["hops"]]
         s["rows"] = int(s["inputs"].shape[0] + sum(b.shape[0] for _, b in s["hops"]))
     max_in = max(s["inputs"].shape[0] for s in sets)
     max_v = [max(s["hops"][h][0].shape[0] - 1 for s in sets) for h in range(len(w.fanouts))]
@@ -265,8 +269,9 @@ def main():
         for indptr, indices in s["hops"]:
             V, E = indptr.shape[0] - 1, indices.shape[0]
             U = np.unique(indices).shape[0]
-            bm.append((8 * (V + 1) + 8 * E + rb * U + 4 * w.D * V, V, E, U,
-                       8 * (V + 1) + 8 * E + rb * E + 4 * w.D * V))
+            ib = 4 if args.idx32 else 8      # bytes per list entry
+            bm.append((8 * (V + 1) + ib * E + rb * U + 4 * w.D * V, V, E, U,
+                       8 * (V + 1) + ib * E + rb * E + 4 * w.D * V))
         s["bytes_mean"] = bm
     t_deq = sum(e[0].elapsed_time(e[1]) for e in events)
     t_inner = sum(e[1].elapsed_time(e[2]) for e in events)
@@ -350,7 +355,8 @@ def main():
                    "row_bytes": rb, "graph": w.graph, "avg_degree": w.avg_degree,
                    "fanouts": list(w.fanouts), "batch": w.batch, "batches_per_step": L,
                    "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B,
-                   "aggregator": args.aggregator, "hip_graph": bool(args.graph)},
+                   "aggregator": args.aggregator, "hip_graph": bool(args.graph),
+                   "index_bits": 32 if args.idx32 else 64},
         "rows_per_step": int(rows_total / args.steps),
         "uncompressed_equiv_GBps": round(value * w.D * esz / 1e9, 1),
         "roofline": roofline,

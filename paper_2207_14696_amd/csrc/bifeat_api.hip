@@ -636,7 +636,7 @@ int gather_aggregate(bifeat_params *p, const uint8_t *codes, int64_t N, const in
     }
     int rc = ensure_device(p);
     if (rc) return rc;
-    const bf::MeanCall c{codes, indptr, indices, idx32, V, E, out, agg_sum, p->opt_mean_max_degree,
+    const bf::MeanCall c{codes, N, indptr, indices, idx32, V, E, out, agg_sum, p->opt_mean_max_degree,
                          p->d_status, (hipStream_t)stream};
     BF_HIP(bf::launch_gather_mean(p, c));
     return BIFEAT_OK;

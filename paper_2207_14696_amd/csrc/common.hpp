@@ -98,6 +98,7 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
 // One fused gather + aggregate request as the launchers of the mean kernels see it.
 struct MeanCall {
     const uint8_t *codes;   // packed table
+    int64_t N;              // its rows
     const int64_t *indptr;  // [V + 1]
     const void *indices;    // [E] row ids, int64 or (idx32) int32
     bool idx32;
@@ -186,6 +187,10 @@ __device__ inline float4 load4(const __half *p) {
 // (non-temporal) stores keep them from evicting the packed table from the
 // caches the gathers depend on.
 __device__ inline void store_stream(float4 *p, const float4 v) {
+#ifdef BF_PLAIN_STORE
+    *p = v;
+    return;
+#endif
     __builtin_nontemporal_store(v.x, &p->x);
     __builtin_nontemporal_store(v.y, &p->y);
     __builtin_nontemporal_store(v.z, &p->z);

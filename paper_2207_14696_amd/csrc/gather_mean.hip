@@ -153,6 +153,9 @@ hipError_t launch_gather_mean(bifeat_params *p, const MeanCall &c) {
     // runs alone: the pass that looks for longer lists is not launched, and a list that breaks
     // the promise gets a row of NaNs and raises the handle's status word.
     const bool promised = c.max_degree > 0;
+    // the short-list kernels keep row ids in 32 bits; a table of 2^32 rows or more (possible
+    // with 16-byte rows) stays with the general kernels
+    const bool ids32 = c.N <= (int64_t)UINT32_MAX;
     const int64_t avg = V > 0 ? E / V : 0;
     const int64_t need = promised ? c.max_degree : 2 * avg;
     // 1-bit logarithmic codes (Sec. 3.1: sign only) decode affinely, V[0] + q*(V[1]-V[0]),
@@ -165,7 +168,7 @@ hipError_t launch_gather_mean(bifeat_params *p, const MeanCall &c) {
         // kernel's field width.
         const bool wide = need > lean_capacity(p->scheme.bits, false);
         const int thr = lean_capacity(p->scheme.bits, wide);
-        const bool lean = p->opt_mean_lean && p->opt_mean_slots == 0 && vec && V > 0 && need <= thr &&
+        const bool lean = p->opt_mean_lean && p->opt_mean_slots == 0 && vec && V > 0 && need <= thr && ids32 &&
                           launch_gather_mean_lean(p, c, thr, wide, -1, promised);
         const bool all_short = lean && promised;
         if (!all_short) {
@@ -186,7 +189,7 @@ hipError_t launch_gather_mean(bifeat_params *p, const MeanCall &c) {
         // longer lists: the table look-up kernel, each skipping the other's destinations
         const bool wide = need > lean_capacity(1, false);
         const int thr = lean_capacity(1, wide);
-        const bool lean = p->opt_mean_lean && V > 0 && need <= thr &&
+        const bool lean = p->opt_mean_lean && V > 0 && need <= thr && ids32 &&
                           launch_gather_mean_lean_log2(p, c, thr, wide, -1, promised);
         const bool all_short = lean && promised;
         if (!all_short) {
@@ -202,7 +205,7 @@ hipError_t launch_gather_mean(bifeat_params *p, const MeanCall &c) {
         // short lists: the look-up kernel with whole 16-byte code loads; longer lists: the
         // general kernel, each skipping the other's destinations
         const int thr = logf_capacity();
-        const bool tiled = p->opt_mean_lean && V > 0 && need <= thr &&
+        const bool tiled = p->opt_mean_lean && V > 0 && need <= thr && ids32 &&
                            launch_gather_mean_logf(p, c, thr, promised);
         const bool all_short = tiled && promised;
         if (!all_short) launch_float<MK_LOG>(p, c, p->d_V, nullptr, vec, tiled ? thr : -1);

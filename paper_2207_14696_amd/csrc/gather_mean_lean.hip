@@ -45,7 +45,13 @@ int lean_capacity(int bits, bool wide) {
 
 namespace {
 
-constexpr int kWaves = kThreads / 64;
+#ifndef BF_LEAN_THREADS
+#define BF_LEAN_THREADS 256
+#endif
+constexpr int kLeanThreads = BF_LEAN_THREADS;
+constexpr int kLeanWaves = kLeanThreads / 64;
+constexpr int kIdxStage = 256;  // list entries a wave parks in LDS per tile
+constexpr int kStageMinLprLog2 = 3;  // ... when at least 8 lanes share a destination
 #ifndef BF_LEAN_U
 #define BF_LEAN_U 4
 #endif
@@ -63,8 +69,9 @@ constexpr int kWaves = kThreads / 64;
 // IT: the type of a list entry (int64_t or int32_t).  alone: no other kernel takes the lists
 // longer than thr (the caller promised there are none): such a list gets a row of NaNs and
 // raises the status word.
-template <int BITS, int CW, bool WIDE, bool SUM, bool PAIR, typename IT>
-__global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel(
+// STAGE: the tile's list entries are fetched once by the wave and parked in LDS (see below).
+template <int BITS, int CW, bool WIDE, bool SUM, bool PAIR, bool STAGE, typename IT>
+__global__ __launch_bounds__(kLeanThreads, BF_LEAN_WPE) void gather_mean_lean_kernel(
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr,
     const IT *__restrict__ indices, int64_t V, int D, int Dp, const float *__restrict__ mn,
     const float *__restrict__ sc, const uint8_t *__restrict__ zero_row, float *__restrict__ out,
@@ -79,14 +86,12 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
     extern __shared__ uint32_t smem[];
     float *s_sc = reinterpret_cast<float *>(smem);  // [scale Dp | min Dp], Dp % 4 == 0
     float *s_mn = s_sc + Dp;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    // wave-uniform values kept in scalar registers: the tile bookkeeping runs on the scalar unit
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float *meta = reinterpret_cast<float *>(smem + 2 * Dp) + wave * 64;
-    uint32_t *stage = smem + 2 * Dp + 64 * kWaves + wave * (64 * R);
-    for (int i = threadIdx.x; i < Dp; i += kThreads) {
-        s_sc[i] = sc[i];
-        s_mn[i] = mn[i];
-    }
-    __syncthreads();
+    uint32_t *stage = smem + 2 * Dp + 64 * kLeanWaves + wave * (64 * R);
+    uint32_t *sidx = smem + 2 * Dp + 64 * kLeanWaves + kLeanWaves * (64 * R) + wave * kIdxStage;
 
     const int LPR = 1 << lpr_log2;
     const int dpw_log2 = 6 - lpr_log2;
@@ -99,21 +104,51 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
     const int step_d = 64 / nf4, step_f = 64 % nf4;
     const int lane_d = lane / nf4, lane_f = lane % nf4;
     const int64_t tiles = (V + dpw - 1) >> dpw_log2;
-    const int64_t n_waves = (int64_t)gridDim.x * kWaves;
+    const int64_t n_waves = (int64_t)gridDim.x * kLeanWaves;
 
-    for (int64_t tile = (int64_t)blockIdx.x * kWaves + wave; tile < tiles; tile += n_waves) {
+    // list bounds of the destination this lane serves in `tile`
+    auto bounds = [&](int64_t tile, int64_t &beg, int64_t &end) {
+        const int64_t v = (tile << dpw_log2) + d_local;
+        beg = end = 0;
+        if (tile < tiles && v < V) {
+            beg = indptr[v];
+            end = indptr[v + 1];
+        }
+    };
+    int64_t tile = (int64_t)blockIdx.x * kLeanWaves + wave;
+    int64_t beg, end;
+    bounds(tile, beg, end);  // in flight while the parameters are staged
+    for (int i = threadIdx.x; i < Dp; i += kLeanThreads) {
+        s_sc[i] = sc[i];
+        s_mn[i] = mn[i];
+    }
+    __syncthreads();
+
+    for (; tile < tiles; tile += n_waves) {
         const int64_t v_tile = tile << dpw_log2;
         const int ndst = (int)min((int64_t)dpw, V - v_tile);
-        int64_t beg = 0, end = 0;
-        if (d_local < ndst) {
-            beg = indptr[v_tile + d_local];
-            end = indptr[v_tile + d_local + 1];
-        }
         const int64_t n64 = end - beg;
         // longer lists: the general kernel; lists of up to `lo`: an earlier launch of the narrow form
         const bool mine = d_local < ndst && n64 <= thr && n64 > lo;
         const bool over = alone && d_local < ndst && n64 > thr;  // a broken promise
-        if (__ballot(mine || over) == 0) continue;  // nothing for this launch in the tile
+        if (__ballot(mine || over) == 0) {  // nothing for this launch in the tile
+            bounds(tile + n_waves, beg, end);
+            continue;
+        }
+        // STAGE (tables whose rows take 8 or more lanes): the tile's lists are one contiguous
+        // run of `indices`; when it is short the wave fetches it once, coalesced, and parks the
+        // row ids in LDS (they fit 32 bits: the launcher only takes tables of fewer than 2^32
+        // rows), instead of every lane of a destination fetching every entry of its list again.
+        // With 1-4 lanes per row the direct fetch is as cheap, and measured faster.
+        int64_t tbeg = 0;
+        bool staged = false;
+        if constexpr (STAGE) {
+            tbeg = __shfl(beg, 0);
+            const int64_t tlen = __shfl(end, (ndst - 1) << lpr_log2) - tbeg;
+            staged = tlen <= kIdxStage;
+            if (staged)
+                for (int i = lane; i < (int)tlen; i += 64) sidx[i] = (uint32_t)indices[tbeg + i];
+        }
         const int n = mine ? (int)n64 : 0;
         if (lane_chunk == 0) {
             // > 0: scale of the sum; 0: empty list; < 0: another kernel's destination; NaN: over
@@ -121,35 +156,45 @@ __global__ __launch_bounds__(kThreads, BF_LEAN_WPE) void gather_mean_lean_kernel
                                  : (over ? __builtin_nanf("") : -1.0f);
             if (over) raise_status(status, kStatusListTooLong);
         }
+        if constexpr (STAGE) wave_sync();  // the parked row ids are read next
 
         uint32_t acc[R];
 #pragma unroll
         for (int r = 0; r < R; r++) acc[r] = 0u;
-        const IT *ip = indices + beg;
         const int cnt = chunk_ok ? n : 0;
-        for (int k = 0; k < cnt; k += U) {
-            IT row[U];
-            uint32_t w[U][CW];
-#pragma unroll
-            for (int u = 0; u < U; u++) row[u] = ip[min(k + u, cnt - 1)];
-            // keep the U index loads together and unconditional (the compiler would
-            // otherwise sink each one into a branch on its slot's validity and
-            // serialise the row loads behind them)
-#pragma unroll
-            for (int u = 0; u < U; u++) asm volatile("" : "+v"(row[u]));
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const uint8_t *src = (k + u < cnt) ? codes + (uint64_t)row[u] * rb + coff : zero_row;
-                load_words<CW>(src, w[u]);
+        // U rows per step: their ids first, all together and unconditional (the compiler would
+        // otherwise sink each read into a branch on its slot's validity and serialise the row
+        // loads behind them), then the U row loads, then the field-parallel adds; slots past
+        // the list's end read a zero row
+#define BF_LEAN_STEP(ROW_OF)                                                                      \
+    for (int k = 0; k < cnt; k += U) {                                                            \
+        uint32_t row[U];                                                                          \
+        uint32_t w[U][CW];                                                                        \
+        _Pragma("unroll") for (int u = 0; u < U; u++) row[u] = (uint32_t)ROW_OF[min(k + u, cnt - 1)]; \
+        _Pragma("unroll") for (int u = 0; u < U; u++) asm volatile("" : "+v"(row[u]));            \
+        _Pragma("unroll") for (int u = 0; u < U; u++) {                                           \
+            const uint8_t *src = (k + u < cnt) ? codes + (uint64_t)row[u] * rb + coff : zero_row; \
+            load_words<CW>(src, w[u]);                                                            \
+        }                                                                                         \
+        _Pragma("unroll") for (int u = 0; u < U; u++)                                             \
+            _Pragma("unroll") for (int c = 0; c < CW; c++)                                        \
+                _Pragma("unroll") for (int i = 0; i < W::kN; i++)                                 \
+                    acc[c * W::kN + i] += (w[u][c] >> (BITS * i)) & W::kMask;                     \
+    }
+        const IT *ip = indices + beg;
+        if constexpr (STAGE) {
+            if (staged) {
+                const uint32_t *lp = sidx + (int)(beg - tbeg);
+                BF_LEAN_STEP(lp)
+            } else {
+                BF_LEAN_STEP(ip)
             }
-#pragma unroll
-            for (int u = 0; u < U; u++)
-#pragma unroll
-                for (int c = 0; c < CW; c++)
-#pragma unroll
-                    for (int i = 0; i < W::kN; i++)
-                        acc[c * W::kN + i] += (w[u][c] >> (BITS * i)) & W::kMask;
+        } else {
+            BF_LEAN_STEP(ip)
         }
+#undef BF_LEAN_STEP
+        // the next tile's list bounds travel while this tile's rows are written
+        bounds(tile + n_waves, beg, end);
         {
             uint32_t *sp = stage + lane * R;
 #pragma unroll
@@ -275,24 +320,31 @@ bool launch_lean_bits(bifeat_params *p, const MeanCall &c, int thr, int lo, bool
     const int dpw = 64 / lpr;
     const int64_t tiles = (V + dpw - 1) / dpw;
     const int64_t cap = p->opt_mean_blocks > 0 ? p->opt_mean_blocks : (1 << 16);
-    int64_t want = (tiles + kWaves - 1) / kWaves;
+    int64_t want = (tiles + kLeanWaves - 1) / kLeanWaves;
     const int blocks = (int)(want < cap ? (want < 1 ? 1 : want) : cap);
     const int D = (int)p->D, Dp = PAIR ? 2 * D : D;
     const int R = cw * W::kN;
-    const size_t shm = sizeof(uint32_t) * ((size_t)2 * Dp + 64 * kWaves + (size_t)kWaves * 64 * R);
-#define BF_LK(CWV, SUMV, IT)                                                                   \
-    gather_mean_lean_kernel<BITS, CWV, WIDE, SUMV, PAIR, IT><<<blocks, kThreads, shm, c.s>>>(      \
+    const size_t shm = sizeof(uint32_t) * ((size_t)2 * Dp + 64 * kLeanWaves + (size_t)kLeanWaves * 64 * R +
+                                           (size_t)kLeanWaves * kIdxStage);
+    const bool stage = ilog2(lpr) >= kStageMinLprLog2;
+#define BF_LK(CWV, SUMV, STG, IT)                                                                  \
+    gather_mean_lean_kernel<BITS, CWV, WIDE, SUMV, PAIR, STG, IT><<<blocks, kLeanThreads, shm, c.s>>>( \
         c.codes, (uint32_t)rb, c.indptr, (const IT *)c.indices, V, D, Dp, mn, sc, p->d_zero,       \
         c.out, ilog2(lpr), chunks, thr, lo, alone ? 1 : 0, c.status)
+#define BF_LS(CWV, SUMV)                                                                           \
+    do {                                                                                           \
+        if (stage) {                                                                               \
+            if (c.idx32) BF_LK(CWV, SUMV, true, int32_t);                                          \
+            else BF_LK(CWV, SUMV, true, int64_t);                                                  \
+        } else {                                                                                   \
+            if (c.idx32) BF_LK(CWV, SUMV, false, int32_t);                                         \
+            else BF_LK(CWV, SUMV, false, int64_t);                                                 \
+        }                                                                                          \
+    } while (0)
 #define BF_LN(CWV)                                                                                 \
     do {                                                                                           \
-        if (c.agg_sum) {                                                                           \
-            if (c.idx32) BF_LK(CWV, true, int32_t);                                                \
-            else BF_LK(CWV, true, int64_t);                                                        \
-        } else {                                                                                   \
-            if (c.idx32) BF_LK(CWV, false, int32_t);                                               \
-            else BF_LK(CWV, false, int64_t);                                                       \
-        }                                                                                          \
+        if (c.agg_sum) BF_LS(CWV, true);                                                           \
+        else BF_LS(CWV, false);                                                                    \
     } while (0)
     switch (cw) {
         case 4: BF_LN(4); break;
@@ -301,6 +353,7 @@ bool launch_lean_bits(bifeat_params *p, const MeanCall &c, int thr, int lo, bool
         default: BF_LN(1); break;
     }
 #undef BF_LN
+#undef BF_LS
 #undef BF_LK
     return true;
 }
