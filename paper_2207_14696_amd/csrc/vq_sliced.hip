@@ -303,6 +303,52 @@ struct MeanLane {
             store_stream(reinterpret_cast<float4 *>(out + v * D + col + 4 * k),
                          make_float4(res[4 * k], res[4 * k + 1], res[4 * k + 2], res[4 * k + 3]));
     }
+
+    // The same for a whole wave tile of 8-column lanes, without holes.  A lane's 32 bytes
+    // are two 16-byte halves; stored half by half, each store instruction would write
+    // every other 16 bytes of the tile's rows - a pattern that streaming stores drain at half
+    // speed.  Instead the two halves of the wave trade: lanes 32..63 hand their first half to
+    // lanes 0..31 in exchange for those lanes' second half (one cross-half swap per register),
+    // so that the first instruction writes both halves of the destinations owned by lanes
+    // 0..31 and the second both halves of the others: whole 128-byte lines per instruction.
+    // `write`: this lane's destination is to be written; v: its destination.
+    __device__ void store_tile(float *__restrict__ out, int64_t v, int D, const float (&res)[CPL],
+                               bool write) const {
+        static_assert(CPL == 8, "two 16-byte halves per lane");
+        const unsigned long long wmask = __ballot(write);
+        uint32_t a[4], b[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            // a: [first halves of lanes 0..31 | second halves of lanes 0..31]
+            // b: [first halves of lanes 32..63 | second halves of lanes 32..63]
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(res[k]), __float_as_uint(res[4 + k]),
+                                                            false, false);
+            a[k] = r[0];
+            b[k] = r[1];
+        }
+        const bool upper = lane >= 32;
+        const int64_t half_dst = 32 >> (6 - rpw_log2);  // destinations owned by half a wave
+        // first instruction: destinations of lanes 0..31 (upper lanes write their partner's second half)
+        const int64_t v0 = upper ? v - half_dst : v;
+        const bool w0 = (wmask >> (lane & 31)) & 1ull;
+        // second instruction: destinations of lanes 32..63 (lower lanes write their partner's first half)
+        const int64_t v1 = upper ? v : v + half_dst;
+        const bool w1 = (wmask >> (32 + (lane & 31))) & 1ull;
+        const int c0 = col + (upper ? 4 : 0);
+#ifdef BF_VQ_PLAIN
+        if (w0) *reinterpret_cast<uint4 *>(out + v0 * D + c0) = make_uint4(a[0], a[1], a[2], a[3]);
+        if (w1) *reinterpret_cast<uint4 *>(out + v1 * D + c0) = make_uint4(b[0], b[1], b[2], b[3]);
+        return;
+#endif
+        if (w0)
+            store_stream(reinterpret_cast<float4 *>(out + v0 * D + c0),
+                         make_float4(__uint_as_float(a[0]), __uint_as_float(a[1]), __uint_as_float(a[2]),
+                                     __uint_as_float(a[3])));
+        if (w1)
+            store_stream(reinterpret_cast<float4 *>(out + v1 * D + c0),
+                         make_float4(__uint_as_float(b[0]), __uint_as_float(b[1]), __uint_as_float(b[2]),
+                                     __uint_as_float(b[3])));
+    }
 };
 
 // Short lists.  On this hardware a wave's loads return in issue order with its
@@ -350,6 +396,12 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
 
         const int64_t v = (tile << L.rpw_log2) + L.r_in;
         const bool mine = L.active && v < V && n <= (uint32_t)kRun;
+        // no long-list pass follows when the caller promised short lists: a longer list gets a
+        // row of NaNs instead of stale memory, and the handle's status word is raised
+        const bool over = alone && L.active && v < V && !mine;
+        float res[CPL];
+#pragma unroll
+        for (int k = 0; k < CPL; k++) res[k] = __builtin_nanf("");
         if (mine) {
             float acc[CPL];
 #pragma unroll
@@ -360,18 +412,14 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_short_kernel(
             if (n > 4 * kPre) L.run(beg + 4 * kPre, beg + n, acc);
             // 1 ulp reciprocal: far inside the 1e-5 budget
             const float inv_n = agg_sum ? 1.0f : (n > 0 ? __builtin_amdgcn_rcpf((float)n) : 0.0f);
-            float res[CPL];
 #pragma unroll
             for (int k = 0; k < CPL; k++) res[k] = acc[k] * inv_n;
-            L.store(out, v, D, res);
-        } else if (alone && L.active && v < V) {
-            // no long-list pass follows (the caller promised short lists): a row of NaNs
-            // instead of stale memory, and the handle's status word is raised
-            float res[CPL];
-#pragma unroll
-            for (int k = 0; k < CPL; k++) res[k] = __builtin_nanf("");
-            L.store(out, v, D, res);
-            if (L.g == 0 && L.slice == 0) raise_status(status, kStatusListTooLong);
+        }
+        if (over && L.g == 0 && L.slice == 0) raise_status(status, kStatusListTooLong);
+        if constexpr (CPL == 8) {
+            L.store_tile(out, v, D, res, mine || over);
+        } else {
+            if (mine || over) L.store(out, v, D, res);
         }
         asm volatile("" ::: "memory");
         beg = beg1, n = n1;
