@@ -68,6 +68,9 @@ def parse_args():
                          "ratio) of this workload's codes on a materialised graph of the same family")
     ap.add_argument("--profile-nodes", type=int, default=1 << 20,
                     help="nodes (= leading rows of the table) of the scale-profile graph")
+    ap.add_argument("--row-align", type=int, default=16, choices=[16, 128],
+                    help="row stride of the packed table: 16 = rows back to back, 128 = line-aligned rows "
+                         "(a 96-byte row then costs one 128-byte line per gather instead of 1.5)")
     ap.add_argument("--idx32", action="store_true",
                     help="pass the blocks' list entries as int32 (bifeat_gather_mean_i32): 4 instead of 8 "
                          "index bytes per entry, in the traffic and in the algorithmic bytes")
@@ -115,7 +118,8 @@ def main():
     kind = {"uniform": bf.UNIFORM, "log": bf.LOG, "vq": bf.VQ}[w.kind]
     q = bf.Quantizer(bf.Scheme(kind, w.bits, w.vq_width if w.kind == "vq" else 0,
                                w.vq_length if w.kind == "vq" else 0,
-                               bf.VQ_COSINE if w.vq_metric == "cosine" else bf.VQ_L2), w.D)
+                               bf.VQ_COSINE if w.vq_metric == "cosine" else bf.VQ_L2), w.D,
+                     row_align=args.row_align)
     for opt in ("mean_slots", "mean_blocks", "max_blocks"):
         if getattr(args, opt):
             q.set_option(opt, getattr(args, opt))
@@ -123,8 +127,10 @@ def main():
         name, value = kv.split("=")
         q.set_option(name, int(value))
     table = DeviceTable(w.spec)
-    rb = q.row_bytes
-    codes = torch.empty((w.N, rb), dtype=torch.uint8, device=dev)
+    stride = q.row_bytes                       # bytes from row to row in the resident table
+    rb = bf.Quantizer(bf.Scheme(kind, w.bits, w.vq_width if w.kind == "vq" else 0,
+                                w.vq_length if w.kind == "vq" else 0), w.D).row_bytes  # bytes of codes per row
+    codes = torch.empty((w.N, stride), dtype=torch.uint8, device=dev)
     chunk_rows = min(args.chunk_rows, w.N)
     buf = torch.empty((chunk_rows, w.D), dtype=table.torch_dtype, device=dev)
     esz = 4 if w.dtype == "f32" else 2
@@ -179,10 +185,10 @@ def main():
         quant_ms += a.elapsed_time(b)
         if (r0 // chunk_rows) % 64 == 63:
             say(f"quantize pass: {r0 + n} of {w.N} rows")
-    say(f"table built: {w.N} rows x {rb} B")
+    say(f"table built: {w.N} rows x {stride} B")
     pre["quantize_GBps"] = (w.N * w.D * esz + w.N * rb) / quant_ms / 1e6
     pre["quantize_rows_per_s"] = w.N / quant_ms * 1e3
-    pre["table_GB"] = w.N * rb / 1e9
+    pre["table_GB"] = w.N * stride / 1e9
     del buf
 
     # ------------------------------------------------- pre-sampled launch-sets
@@ -352,7 +358,7 @@ def main():
         "config": {"workload": w.name, "N": w.N, "D": w.D, "scheme": w.kind,
                    "bits": w.bits if w.kind != "vq" else None,
                    "vq": [w.vq_width, w.vq_length, w.vq_metric] if w.kind == "vq" else None,
-                   "row_bytes": rb, "graph": w.graph, "avg_degree": w.avg_degree,
+                   "row_bytes": rb, "row_stride": stride, "graph": w.graph, "avg_degree": w.avg_degree,
                    "fanouts": list(w.fanouts), "batch": w.batch, "batches_per_step": L,
                    "seed_mode": w.seed_mode, "seed": w.seed, "distinct_launch_sets": B,
                    "aggregator": args.aggregator, "hip_graph": bool(args.graph),

@@ -132,13 +132,17 @@ class Quantizer:
     """Owns a ``bifeat_params`` handle.  Method names follow the C entry points
     (``bifeat_`` prefix dropped)."""
 
-    def __init__(self, scheme: Scheme, D: int):
+    def __init__(self, scheme: Scheme, D: int, row_align: int = 16):
+        """row_align: option "row_align" of the library (16: rows back to back; 128: rows laid
+        out so that none straddles a 128-byte line needlessly), set before anything is packed."""
         self._lib = load_library()
         self.scheme, self.D = scheme, int(D)
         h = C.c_void_p()
         cs = _CScheme(scheme.kind, scheme.bits, scheme.vq_width, scheme.vq_length, scheme.vq_metric)
         _check(self._lib.bifeat_params_create(C.byref(cs), self.D, C.byref(h)))
         self._h = h
+        if row_align != 16:
+            self.set_option("row_align", row_align)
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

@@ -39,6 +39,19 @@ bool scheme_ok(const bifeat_scheme *s, int64_t D) {
 
 int64_t round16(int64_t n) { return (n + 15) / 16 * 16; }
 
+// Row stride for the table's alignment option.  16: rows back to back.  128: rows of up to 128
+// bytes take the next power of two (a row then never straddles a 128-byte line), longer rows a
+// whole number of lines.
+int64_t row_stride(int64_t payload, int align) {
+    if (align < 128) return payload;
+    if (payload <= 128) {
+        int64_t s = 16;
+        while (s < payload) s *= 2;
+        return s;
+    }
+    return (payload + 127) / 128 * 128;
+}
+
 // allocate the device block on first GPU use
 int ensure_device(bifeat_params *p) {
     if (p->d_block) return BIFEAT_OK;
@@ -306,12 +319,13 @@ int bifeat_params_create(const bifeat_scheme *scheme, int64_t D, bifeat_params *
         p->P = (int)((D + scheme->vq_width - 1) / scheme->vq_width);
         p->ncodes = p->P;
         p->cbytes = scheme->vq_length <= 256 ? 1 : 2;
-        p->rb = round16((int64_t)p->P * p->cbytes);
+        p->payload = round16((int64_t)p->P * p->cbytes);
         p->scheme.bits = 8 * p->cbytes;
     } else {
         p->ncodes = D;
-        p->rb = round16((D * scheme->bits + 7) / 8);
+        p->payload = round16((D * scheme->bits + 7) / 8);
     }
+    p->rb = row_stride(p->payload, p->opt_row_align);
     *out = p;
     return BIFEAT_OK;
 }
@@ -340,6 +354,10 @@ int bifeat_set_option(bifeat_params *p, const char *name, int value) {
     else if (!strcmp(name, "vq_sliced")) p->opt_vq_sliced = value;
     else if (!strcmp(name, "vq_iters") && value >= 1 && value <= 64) p->opt_vq_iters = value;
     else if (!strcmp(name, "mean_max_degree")) p->opt_mean_max_degree = value;
+    else if (!strcmp(name, "row_align") && (value == 16 || value == 128)) {
+        p->opt_row_align = value;
+        p->rb = row_stride(p->payload, value);
+    }
     else return BIFEAT_EINVAL;
     return BIFEAT_OK;
 }

@@ -14,7 +14,9 @@ struct bifeat_params {
     bifeat_scheme scheme{};
     int64_t D = 0;
     int64_t ncodes = 0;  // codes per row: D, or P for vector codes
-    int64_t rb = 0;      // packed bytes per row, multiple of 16
+    int64_t rb = 0;      // bytes from one packed row to the next, multiple of 16
+    int64_t payload = 0; // bytes of a row that hold codes, rounded up to 16 (rb >= payload; the
+                         // rest is zero padding of a line-aligned table, option "row_align")
     int P = 0;           // vector codes: number of parts
     int cbytes = 1;      // vector codes: bytes per stored index (2 beyond 256 entries)
 
@@ -70,6 +72,7 @@ struct bifeat_params {
     int opt_dequant_flat = 0;  // 1: gather_dequant without the LDS-staged tile kernel
     int opt_mean_generic = 0;  // 1: route uniform tables through the float-accumulate kernel
     int opt_validate = 0;      // 1: check indices / list bounds on the GPU before every gather (synchronises)
+    int opt_row_align = 16;    // 16: rows packed back to back; 128: no row straddles a 128-byte line needlessly
 };
 
 namespace bf {

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_sq_kernel(
 // written with consecutive 16-byte stores, granule m of the span by lane m%64.
 template <int BITS, int DEC>
 __global__ __launch_bounds__(kThreads) void gather_dequant_tile_kernel(
-    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int D,
+    const uint4 *__restrict__ codes16, int c16, int s16, const int64_t *__restrict__ idx, int64_t M, int D,
     const float *__restrict__ pa, const float *__restrict__ pb, float *__restrict__ out) {
     extern __shared__ uint32_t smem[];
     constexpr int kLut = 1 << BITS;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_tile_kernel(
     for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < tiles; tile += n_waves) {
         const int64_t row0 = tile * RT;
         const int nrow = (int)min((int64_t)RT, M - row0);
-        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * c16 + c];  // lane = r*c16 + c
+        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * s16 + c];  // lane = r*c16 + c
         wave_sync();
         float4 *span = reinterpret_cast<float4 *>(out + row0 * D);
         const int ngran = nrow * nf4;
@@ -250,7 +250,7 @@ constexpr int kVqInFlight = 8;
 
 template <int CB>
 __global__ __launch_bounds__(kThreads) void gather_dequant_vq_tile_kernel(
-    const uint4 *__restrict__ codes16, int c16, const int64_t *__restrict__ idx, int64_t M, int D,
+    const uint4 *__restrict__ codes16, int c16, int s16, const int64_t *__restrict__ idx, int64_t M, int D,
     int w, int len, const float *__restrict__ cb, float *__restrict__ out) {
     __shared__ uint4 s_raw[kThreads];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void gather_dequant_vq_tile_kernel(
     for (int64_t tile = (int64_t)blockIdx.x * (kThreads / 64) + wave; tile < tiles; tile += n_waves) {
         const int64_t row0 = tile * RT;
         const int nrow = (int)min((int64_t)RT, M - row0);
-        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * c16 + c];  // lane = r*c16 + c
+        if (r < nrow) raw[lane] = codes16[idx[row0 + r] * s16 + c];  // lane = r*c16 + c
         wave_sync();
         float4 *span = reinterpret_cast<float4 *>(out + row0 * D);
         const int ngran = nrow * nf4;
@@ -309,7 +309,7 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
         if (p->opt_vq_sliced && launch_gather_dequant_vq_sliced(p, codes, idx, M, out, s, planes))
             return hipGetLastError();
         const int w = p->scheme.vq_width;
-        const int c16v = (int)(p->rb / 16);
+        const int c16v = (int)(p->payload / 16), s16v = (int)(p->rb / 16);
         if (w % 4 == 0 && vec && c16v <= 64 && !p->opt_dequant_flat) {
             const int RT = 64 / c16v;
             const int64_t tiles = (M + RT - 1) / RT;
@@ -317,9 +317,9 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
             const int64_t want = (tiles + 3) / 4;
             const int tb = (int)(want < cap ? want : cap);
             if (p->cbytes == 1)
-                gather_dequant_vq_tile_kernel<1><<<tb, kThreads, 0, s>>>((const uint4 *)codes, c16v, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
+                gather_dequant_vq_tile_kernel<1><<<tb, kThreads, 0, s>>>((const uint4 *)codes, c16v, s16v, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
             else
-                gather_dequant_vq_tile_kernel<2><<<tb, kThreads, 0, s>>>((const uint4 *)codes, c16v, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
+                gather_dequant_vq_tile_kernel<2><<<tb, kThreads, 0, s>>>((const uint4 *)codes, c16v, s16v, idx, M, D, w, p->scheme.vq_length, p->d_cb, out);
             return hipGetLastError();
         }
 #define BF_GV(W4, CB) \
@@ -334,7 +334,7 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
 #undef BF_GV
         return hipGetLastError();
     }
-    const int c16 = (int)(p->rb / 16);
+    const int c16 = (int)(p->payload / 16), s16 = (int)(p->rb / 16);  // lanes per row / row stride
     // LDS of the tile kernel: the parameters (2*D floats for uniform codes) plus one 16-byte
     // slot per lane; tables too wide for the 64 KB a workgroup gets by default take the
     // flat kernel below
@@ -351,7 +351,7 @@ hipError_t launch_gather_dequant(bifeat_params *p, const uint8_t *codes, const i
         const int tb = (int)(want < cap ? want : cap);
         const size_t shm = tile_lds;
 #define BF_GT(B, DEC, A, Bp) \
-    gather_dequant_tile_kernel<B, DEC><<<tb, kThreads, shm, s>>>((const uint4 *)codes, c16, idx, M, D, A, Bp, out)
+    gather_dequant_tile_kernel<B, DEC><<<tb, kThreads, shm, s>>>((const uint4 *)codes, c16, s16, idx, M, D, A, Bp, out)
         if (kind == BIFEAT_SQ_UNIFORM) {
             switch (bits) {
                 case 1: BF_GT(1, DEC_UNIFORM, p->d_min, p->d_scale); break;

@@ -301,12 +301,12 @@ bool launch_lean_bits(bifeat_params *p, const MeanCall &c, int thr, int lo, bool
                       const float *mn, const float *sc) {
     using W = LeanSwar<BITS, WIDE>;
     const int64_t V = c.V;
-    const int64_t rb = p->rb;
+    const int64_t rb = p->rb, payload = p->payload;  // row stride / bytes the lanes fetch
     int cw = 0;
     double best_eff = -1.0;
     for (int cand = 4; cand >= 1; cand--) {
-        if (rb % (4 * cand)) continue;
-        const int chunks = (int)(rb / (4 * cand));
+        if (payload % (4 * cand)) continue;
+        const int chunks = (int)(payload / (4 * cand));
         if (chunks > 64) continue;
         const double eff = (double)chunks / pow2ceil(chunks);
         if (eff > best_eff + 1e-9) {
@@ -315,7 +315,7 @@ bool launch_lean_bits(bifeat_params *p, const MeanCall &c, int thr, int lo, bool
         }
     }
     if (!cw) return false;  // packed row longer than 64 lane loads
-    const int chunks = (int)(rb / (4 * cw));
+    const int chunks = (int)(payload / (4 * cw));
     const int lpr = pow2ceil(chunks);
     const int dpw = 64 / lpr;
     const int64_t tiles = (V + dpw - 1) / dpw;

@@ -144,7 +144,7 @@ int logf_capacity() { return 64; }
 // False (nothing launched) when the shape is outside what the kernel handles.
 bool launch_gather_mean_logf(bifeat_params *p, const MeanCall &c, int thr, bool alone) {
     const int bits = p->scheme.bits;
-    const int64_t c16 = p->rb / 16;
+    const int64_t c16 = p->payload / 16;  // lanes that fetch a row (its stride is p->rb)
     if ((bits != 4 && bits != 8) || p->D % 4 || (uintptr_t)c.out % 16 || (uintptr_t)c.codes % 16 ||
         c16 > 64 || c.V <= 0)
         return false;

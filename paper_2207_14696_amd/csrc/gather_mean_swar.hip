@@ -390,14 +390,14 @@ __global__ __launch_bounds__(kThreads, BF_SWAR_WPE) void gather_mean_swar_kernel
 template <int BITS>
 static void launch_swar(bifeat_params *p, const MeanCall &c, int vec, int min_len) {
     using W = Swar<BITS>;
-    const int64_t rb = p->rb, V = c.V, E = c.E;
+    const int64_t rb = p->rb, payload = p->payload, V = c.V, E = c.E;  // row stride / bytes fetched
     // words per lane: every row chunk must be whole; prefer the choice that
     // leaves the fewest idle lanes, then the widest load
     int cw = 4;
     double best_eff = -1.0;
     for (int cand = 4; cand >= 1; cand--) {
-        if (rb % (4 * cand)) continue;
-        int chunks = (int)(rb / (4 * cand));
+        if (payload % (4 * cand)) continue;
+        int chunks = (int)(payload / (4 * cand));
         int lpr = pow2ceil(chunks > 64 ? 64 : chunks);
         int passes = (chunks + lpr - 1) / lpr;
         double eff = (double)chunks / ((double)lpr * passes);
@@ -406,7 +406,7 @@ static void launch_swar(bifeat_params *p, const MeanCall &c, int vec, int min_le
             cw = cand;
         }
     }
-    const int chunks = (int)(rb / (4 * cw));
+    const int chunks = (int)(payload / (4 * cw));
     const int lpr = pow2ceil(chunks > 64 ? 64 : chunks);
     // slots per destination: about one per 16 neighbours of the average list
     int S = p->opt_mean_slots;

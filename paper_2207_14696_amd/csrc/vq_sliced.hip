@@ -77,7 +77,7 @@ constexpr int kStripK = 4;  // row batches per wave tile of the pre-pass
 // run of 16-byte stores.
 template <typename IT>
 __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
-    const uint4 *__restrict__ codes16, int c16, const IT *__restrict__ idx, int64_t M, int NPW,
+    const uint4 *__restrict__ codes16, int c16, int s16, const IT *__restrict__ idx, int64_t M, int NPW,
     int64_t MS, uint32_t *__restrict__ planes) {
     constexpr int K = kStripK;
     __shared__ uint4 s_raw[(kThreads / 64) * K * 64];
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
 #pragma unroll
         for (int k = 0; k < K; k++) {
             const int rr = min(k * RT + r, nrow - 1);
-            v[k] = codes16[(int64_t)idx[row0 + rr] * c16 + c];
+            v[k] = codes16[(int64_t)idx[row0 + rr] * s16 + c];
         }
         if (r < RT) {
 #pragma unroll
@@ -117,17 +117,17 @@ __global__ __launch_bounds__(kThreads) void vq_planes_kernel(
 
 void launch_planes(bifeat_params *p, const uint8_t *codes, const void *idx, bool idx32, int64_t M,
                    uint32_t *planes, hipStream_t s) {
-    const int c16 = (int)(p->rb / 16), TR = (64 / c16) * kStripK;
+    const int c16 = (int)(p->payload / 16), s16 = (int)(p->rb / 16), TR = (64 / c16) * kStripK;
     const int64_t tiles = (M + TR - 1) / TR;
     int64_t blocks = (tiles + 3) / 4;
     if (blocks > (1 << 16)) blocks = 1 << 16;
     if (blocks < 1) blocks = 1;
     if (idx32)
         vq_planes_kernel<int32_t><<<(unsigned)blocks, kThreads, 0, s>>>(
-            (const uint4 *)codes, c16, (const int32_t *)idx, M, (int)(p->rb / 4), plane_entries(M), planes);
+            (const uint4 *)codes, c16, s16, (const int32_t *)idx, M, (int)(p->payload / 4), plane_entries(M), planes);
     else
         vq_planes_kernel<int64_t><<<(unsigned)blocks, kThreads, 0, s>>>(
-            (const uint4 *)codes, c16, (const int64_t *)idx, M, (int)(p->rb / 4), plane_entries(M), planes);
+            (const uint4 *)codes, c16, s16, (const int64_t *)idx, M, (int)(p->payload / 4), plane_entries(M), planes);
 }
 
 // workgroup b serves slice b % NS as that slice's (b / NS)-th of ny workgroups
@@ -520,7 +520,7 @@ hipError_t static_scratch_ptr(uint8_t **out) {
 }
 
 size_t vq_gather_scratch_bytes(const bifeat_params *p, int64_t M) {
-    return (size_t)p->rb * (size_t)plane_entries(M);
+    return (size_t)p->payload * (size_t)plane_entries(M);
 }
 
 // All return false (nothing launched) when the codebook shape is outside what
@@ -530,14 +530,14 @@ size_t vq_gather_scratch_bytes(const bifeat_params *p, int64_t M) {
 bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, const int64_t *idx,
                                      int64_t M, float *out, hipStream_t s, uint32_t *planes) {
     const VqGeom g = vq_geometry(p);
-    if (!g.ok || (uintptr_t)out % 16 || p->rb / 16 > 64) return false;
+    if (!g.ok || (uintptr_t)out % 16 || p->payload / 16 > 64) return false;
     // a slice narrower than 256 bytes of output per row makes the stores too fine-grained
     // (measured: slower than decoding from L2 with whole rows per wave)
     if (g.LPS < 16) return false;
     if (!allow_lds(gather_dequant_vq_sliced_kernel, g.lds)) return false;
     const int64_t MS = plane_entries(M);
     if (!planes) {
-        if (!ensure_scratch(p, (size_t)p->rb * MS, s)) return false;
+        if (!ensure_scratch(p, (size_t)p->payload * MS, s)) return false;
         planes = (uint32_t *)p->d_scratch;
     }
     launch_planes(p, codes, idx, false, M, planes, s);
@@ -555,9 +555,9 @@ bool launch_gather_dequant_vq_sliced(bifeat_params *p, const uint8_t *codes, con
 // launched at all (a longer list then gets a row of NaNs and raises the status word).
 bool launch_gather_mean_vq_sliced(bifeat_params *p, const MeanCall &c) {
     const VqGeom g = vq_geometry(p);
-    if (!g.ok || (uintptr_t)c.out % 16 || p->rb / 16 > 64) return false;
+    if (!g.ok || (uintptr_t)c.out % 16 || p->payload / 16 > 64) return false;
     const int64_t MS = plane_entries(c.E);
-    if (p->rb * MS >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
+    if (p->payload * MS >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
     const int cpl = w % 8 == 0 ? 8 : 4;  // columns per lane
     const bool with_long = !(c.max_degree > 0 && c.max_degree <= kRun);
@@ -566,7 +566,7 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const MeanCall &c) {
                  : !(allow_lds(gather_mean_vq_short_kernel<4>, g.lds) &&
                      allow_lds(gather_mean_vq_long_kernel<4>, g.lds)))
         return false;
-    if (!ensure_scratch(p, (size_t)p->rb * MS, c.s)) return false;
+    if (!ensure_scratch(p, (size_t)p->payload * MS, c.s)) return false;
     if (c.E > 0) launch_planes(p, c.codes, c.indices, c.idx32, c.E, (uint32_t *)p->d_scratch, c.s);
     const int lps = g.LPS * 4 / cpl, rpw = 64 / lps;
     const int64_t tiles = (c.V + rpw - 1) / rpw;

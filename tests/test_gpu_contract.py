@@ -220,3 +220,56 @@ def test_vector_code_workspace_reserve_growth_and_capture(bf, torch):
             assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, huge[0], huge[1]), s, "after growth")
     q.set_option("mean_max_degree", 0)
     assert q.poll_status()
+
+
+ALIGN_CASES = [("uniform", 1, 768, 96, 128), ("uniform", 4, 100, 64, 64), ("uniform", 4, 96, 48, 64),
+               ("uniform", 2, 128, 32, 32), ("uniform", 8, 200, 208, 256), ("uniform", 4, 768, 384, 384),
+               ("log", 1, 768, 96, 128), ("log", 2, 300, 80, 128), ("log", 4, 160, 80, 128),
+               ("vq", 8, 768, 96, 128), ("vq", 8, 64, 16, 16)]
+
+
+@pytest.mark.parametrize("kind,bits,D,payload,stride", ALIGN_CASES)
+def test_line_aligned_table_layout(bf, torch, kind, bits, D, payload, stride):
+    # option "row_align" = 128: same codes, same decoded values and means; only the distance
+    # from row to row changes, and the bytes between the codes and the next row are zero
+    from bifeat_inputs import FeatureSpec, feature_chunk
+    from bifeat_inputs.device import DeviceTable
+    from helpers import gpu_build_table
+    w, length = 8, 256 if D == 768 else 32
+    q0, s, codes, _ = _tables(bf, torch, kind, bits, D, N=2003, w=w, length=length)
+    assert codes.shape[1] == payload == q0.row_bytes
+    q = bf.Quantizer(q0.scheme, D, row_align=128)
+    assert q.row_bytes == stride
+    if kind == "uniform":
+        q.params_set_uniform(*q0.params_get_uniform()[:2])
+    elif kind == "log":
+        q.params_set_log(*q0.params_get_log()[:2])
+    else:
+        q.params_set_codebooks(q0.params_get_codebooks())
+    table = gpu_build_table(q, DeviceTable(FeatureSpec(2003, D, 6)), 2003, 700, fit=False)
+    got = table.cpu().numpy()
+    assert got.shape == (2003, stride)
+    assert np.array_equal(got[:, :payload], codes) and not got[:, payload:].any()
+    rng = np.random.default_rng(8)
+    idx = rng.integers(0, 2003, 1501).astype(np.int64)
+    didx = torch.from_numpy(idx).cuda()
+    assert np.array_equal(q.gather_codes(table, didx).cpu().numpy()[:, :payload], orc.gather_codes(codes, idx))
+    assert_close(q.gather_dequant(table, didx).cpu().numpy(), orc.gather_dequant(s, codes, idx), s, "dequant")
+    if kind != "vq":
+        q.set_option("dequant_flat", 1)
+        assert_close(q.gather_dequant(table, didx).cpu().numpy(), orc.gather_dequant(s, codes, idx), s, "flat")
+        q.set_option("dequant_flat", 0)
+    indptr, indices = random_csr(907, 2003, 11, rng, hubs=(15, 17, 40, 65, 300))
+    dptr, dind = torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda()
+    want = orc.gather_mean(s, codes, indptr, indices)
+    assert_close(q.gather_mean(table, dptr, dind).cpu().numpy(), want, s, "mean")
+    for opt in ("mean_lean", "vq_sliced"):
+        q.set_option(opt, 0)
+    assert_close(q.gather_mean(table, dptr, dind).cpu().numpy(), want, s, "mean, general kernels")
+    for opt in ("mean_lean", "vq_sliced"):
+        q.set_option(opt, 1)
+    indptr, indices = random_csr(500, 2003, 9, rng)
+    q.set_option("mean_max_degree", 9)
+    got = q.gather_mean(table, torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda())
+    assert_close(got.cpu().numpy(), orc.gather_mean(s, codes, indptr, indices), s, "mean, bounded lists")
+    assert q.poll_status()
