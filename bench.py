@@ -152,7 +152,7 @@ def main():
         del sample
         say(f"codebooks trained on {ns} rows")
     else:
-        fit_ms = 0.0
+        fit_ms = gen_ms = 0.0
         if w.kind == "log" and w.log_clip > 0:
             q.fit_set_log_clip(w.log_clip)      # exact clipped range: three passes over the table
         q.fit_reset()
@@ -160,12 +160,14 @@ def main():
         while again:
             for r0 in range(0, w.N, chunk_rows):
                 n = min(chunk_rows, w.N - r0)
+                g0, a, b = ev(), ev(), ev()
+                g0.record()
                 table.chunk(r0, n, buf[:n])
-                a, b = ev(), ev()
                 a.record()
                 q.fit_update(buf[:n])
                 b.record()
                 b.synchronize()
+                gen_ms += g0.elapsed_time(a)
                 fit_ms += a.elapsed_time(b)
                 if (r0 // chunk_rows) % 64 == 63:
                     say(f"fit pass {passes + 1}: {r0 + n} of {w.N} rows")
@@ -173,6 +175,7 @@ def main():
             passes += 1
         pre["fit_GBps"] = passes * w.N * w.D * esz / fit_ms / 1e6
         pre["fit_passes"] = passes
+        pre["chunk_generation_ms_per_pass"] = gen_ms / passes
     quant_ms = 0.0
     for r0 in range(0, w.N, chunk_rows):
         n = min(chunk_rows, w.N - r0)
@@ -190,6 +193,40 @@ def main():
     pre["quantize_rows_per_s"] = w.N / quant_ms * 1e3
     pre["table_GB"] = w.N * stride / 1e9
     del buf
+    if w.kind == "uniform" or (w.kind == "log" and w.log_clip == 0):
+        # the same preprocessing with the table produced inside the library's kernels (the
+        # synthetic generator as a row source, include/bifeat_produce.hpp): the raw chunk is
+        # never written or read, only codes reach memory.  A second handle is fitted that way
+        # and re-encodes the resident table in place - to the same bytes.
+        q2 = bf.Quantizer(q.scheme, w.D, row_align=args.row_align)
+        head = codes[:min(w.N, 1 << 18)].clone()
+        tail = codes[-min(w.N, 1 << 18):].clone()
+        q2.fit_reset()
+        a, b, c = ev(), ev(), ev()
+        a.record()
+        for r0 in range(0, w.N, 16 * chunk_rows):
+            table.fit_into(q2, r0, min(16 * chunk_rows, w.N - r0))
+        q2.fit_finalize()
+        b.record()
+        for r0 in range(0, w.N, 16 * chunk_rows):
+            table.quantize_into(q2, codes, r0, min(16 * chunk_rows, w.N - r0))
+        c.record()
+        c.synchronize()
+        same = (q2.params_get_uniform() if w.kind == "uniform" else q2.params_get_log()[:2])
+        ref = (q.params_get_uniform() if w.kind == "uniform" else q.params_get_log()[:2])
+        same = all(np.array_equal(x, y) for x, y in zip(same, ref)) and bool(
+            torch.equal(head, codes[:head.shape[0]]) and torch.equal(tail, codes[-tail.shape[0]:]))
+        pre["produced_fit_ms"] = a.elapsed_time(b)
+        pre["produced_quantize_ms"] = b.elapsed_time(c)
+        pre["produced_fit_Gvalues_per_s"] = w.N * w.D / a.elapsed_time(b) / 1e6
+        pre["produced_quantize_Gvalues_per_s"] = w.N * w.D / b.elapsed_time(c) / 1e6
+        pre["produced_quantize_written_GBps"] = w.N * stride / b.elapsed_time(c) / 1e6
+        pre["produced_equals_chunked"] = 1.0 if same else 0.0
+        pre["chunked_fit_ms"] = fit_ms
+        pre["chunked_quantize_ms"] = quant_ms
+        del q2, head, tail
+        say(f"produced-table pass: fit {pre['produced_fit_ms']:.1f} ms, encode {pre['produced_quantize_ms']:.1f} ms, "
+            f"same parameters and codes: {same}")
 
     # ------------------------------------------------- pre-sampled launch-sets
     g = make_graph(w)

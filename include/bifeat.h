@@ -197,6 +197,16 @@ int bifeat_vq_distortion(bifeat_params *p, float *out, int32_t n);
 int bifeat_quantize(bifeat_params *p, const void *chunk, int32_t dtype, int64_t rows,
                     uint8_t *codes, int64_t row0, void *stream);
 
+/* ---- host bookkeeping of include/bifeat_produce.hpp (fit and encode of a table whose values
+ * are produced inside the kernels by a caller-defined source; the kernels themselves are C++
+ * templates in that header).  fit_begin: what bifeat_fit_update does before its kernel (opens
+ * the fit if none is open); BIFEAT_ENOTSUP for vector codes and for a logarithmic fit with a
+ * clip fraction.  fit_end: accounts `rows` more fitted rows.  quantize_check: the argument and
+ * state checks of bifeat_quantize (BIFEAT_ENOTSUP for vector codes). */
+int bifeat_produce_fit_begin(bifeat_params *p, void *stream);
+int bifeat_produce_fit_end(bifeat_params *p, int64_t rows);
+int bifeat_produce_quantize_check(bifeat_params *p, const uint8_t *codes, int64_t rows, int64_t row0);
+
 /* ---- per-iteration load (Sec. 3.3).  codes: DEVICE packed table of N rows.
  * gather_codes:   out[i, :] = codes[idx[i], :]              out: DEVICE [M x row_bytes]
  * gather_dequant: out[i, j] = decode(codes[idx[i]])[j]      out: DEVICE [M x D] fp32

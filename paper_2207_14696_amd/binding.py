@@ -57,6 +57,9 @@ _SIGNATURES = {
     "bifeat_params_set_codebooks": (C.c_int, [C.c_void_p, C.c_void_p]),
     "bifeat_params_get_codebooks": (C.c_int, [C.c_void_p, C.c_void_p]),
     "bifeat_vq_distortion": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32]),
+    "bifeat_produce_fit_begin": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "bifeat_produce_fit_end": (C.c_int, [C.c_void_p, C.c_int64]),
+    "bifeat_produce_quantize_check": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]),
     "bifeat_quantize": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p,
                                   C.c_int64, C.c_void_p]),
     "bifeat_gather_codes": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,

@@ -570,6 +570,27 @@ int bifeat_quantize(bifeat_params *p, const void *chunk, int32_t dtype, int64_t 
     return BIFEAT_OK;
 }
 
+int bifeat_produce_fit_begin(bifeat_params *p, void *stream) {
+    if (!p) return BIFEAT_EINVAL;
+    if (p->scheme.kind == BIFEAT_VQ || (p->scheme.kind == BIFEAT_SQ_LOG && p->clip_fraction > 0.0))
+        return BIFEAT_ENOTSUP;
+    if (!p->fit_open) return bifeat_fit_reset(p, stream);
+    return BIFEAT_OK;
+}
+
+int bifeat_produce_fit_end(bifeat_params *p, int64_t rows) {
+    if (!p || rows < 0 || !p->fit_open) return BIFEAT_EINVAL;
+    p->fit_rows += rows;
+    return BIFEAT_OK;
+}
+
+int bifeat_produce_quantize_check(bifeat_params *p, const uint8_t *codes, int64_t rows, int64_t row0) {
+    if (!p || rows < 0 || row0 < 0 || (rows > 0 && !codes) || (uintptr_t)codes % 16) return BIFEAT_EINVAL;
+    if (p->scheme.kind == BIFEAT_VQ) return BIFEAT_ENOTSUP;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    return BIFEAT_OK;
+}
+
 namespace {
 // option "validate": the caller's index contract checked on the GPU before the gather
 int check_inputs(bifeat_params *p, const int64_t *idx, int64_t M, int64_t N, const int64_t *indptr,

@@ -6,6 +6,7 @@
 // is a multiple of the groups per row), so per-column parameters live in
 // registers while consecutive lanes still read consecutive addresses.
 #include "common.hpp"
+#include "stream_kernels.hpp"
 
 namespace bf {
 
@@ -27,86 +28,6 @@ hipError_t launch_fit_reset(bifeat_params *p, hipStream_t s) {
         fit_reset_kernel<<<1, 64, 0, s>>>(p->d_fit, 1, 0x7F800000, 0);
     }
     return hipGetLastError();
-}
-
-// per-column min / max of a chunk merged into the running state.
-// VEC = 4 needs D % 4 == 0 and a 16-byte (fp16: 8-byte) aligned chunk.
-template <typename T, int VEC>
-__global__ __launch_bounds__(kThreads) void fit_minmax_kernel(const T *__restrict__ x,
-                                                             int64_t rows, int D, int G,
-                                                             int32_t *state, int use_lds) {
-    extern __shared__ int32_t lds[];
-    if (use_lds) {
-        for (int i = threadIdx.x; i < D; i += kThreads) {
-            lds[i] = kKeyPosInf;
-            lds[D + i] = kKeyNegInf;
-        }
-        __syncthreads();
-    }
-    // A workgroup streams one contiguous piece of the chunk: kThreads/G whole rows per
-    // iteration when a row's G column groups fit a workgroup (a wave's lanes then read
-    // consecutive 16 bytes), else groups of G threads across the grid walk consecutive rows.
-    const bool by_block = G <= kThreads;
-    const int rpi = by_block ? kThreads / G : 0;  // rows per iteration of a workgroup
-    const uint32_t total = gridDim.x * kThreads;
-    const uint32_t rows_per_pass = total / (uint32_t)G;
-    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
-    const bool active = by_block ? (int)threadIdx.x < rpi * G : t < rows_per_pass * (uint32_t)G;
-    if (active) {
-        const int g = by_block ? (int)threadIdx.x % G : (int)(t % (uint32_t)G);
-        float mn[VEC], mx[VEC];
-#pragma unroll
-        for (int k = 0; k < VEC; k++) {
-            mn[k] = INFINITY;
-            mx[k] = -INFINITY;
-        }
-        const T *src = x + (int64_t)g * VEC;
-        int64_t rbeg, rend, rstep;
-        if (by_block) {
-            const int64_t per_block = (rows + gridDim.x - 1) / gridDim.x;
-            rbeg = (int64_t)blockIdx.x * per_block + (int)threadIdx.x / G;
-            rend = min(rows, (int64_t)(blockIdx.x + 1) * per_block);
-            rstep = rpi;
-        } else {
-            const int64_t K = (rows + rows_per_pass - 1) / rows_per_pass;
-            rbeg = (int64_t)(t / G) * K;
-            rend = min(rows, rbeg + K);
-            rstep = 1;
-        }
-#pragma unroll 4
-        for (int64_t r = rbeg; r < rend; r += rstep) {
-            float v[VEC];
-            if constexpr (VEC == 4) {
-                float4 q = load4(src + r * D);
-                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-            } else {
-                v[0] = load1(src + r * D);
-            }
-#pragma unroll
-            for (int k = 0; k < VEC; k++) {
-                if (v[k] < mn[k]) mn[k] = v[k];  // NaN compares false: skipped
-                if (v[k] > mx[k]) mx[k] = v[k];
-            }
-        }
-        int32_t *lo = use_lds ? lds : state;
-#pragma unroll
-        for (int k = 0; k < VEC; k++) {
-            int col = g * VEC + k;
-            atomicMin(&lo[col], float_key(mn[k]));
-            atomicMax(&lo[D + col], float_key(mx[k]));
-        }
-    }
-    if (use_lds) {
-        __syncthreads();
-        // thousands of workgroups would hammer the same 2*D words: only those that improve
-        // on the value already there (read without ordering: a stale read merely costs one
-        // atomic that changes nothing) issue the atomic
-        for (int i = threadIdx.x; i < D; i += kThreads) {
-            const int32_t lo_k = lds[i], hi_k = lds[D + i];
-            if (lo_k < __builtin_nontemporal_load(&state[i])) atomicMin(&state[i], lo_k);
-            if (hi_k > __builtin_nontemporal_load(&state[D + i])) atomicMax(&state[D + i], hi_k);
-        }
-    }
 }
 
 // smallest nonzero and largest finite magnitude of a chunk (log scheme);
@@ -169,23 +90,8 @@ hipError_t launch_fit_update(bifeat_params *p, const void *chunk, int dtype, int
     }
     const size_t esz = dtype == BIFEAT_F32 ? 4 : 2;
     const bool vec = (D % 4 == 0) && ((uintptr_t)chunk % (4 * esz) == 0);
-    const int VEC = vec ? 4 : 1;
-    const int G = (D + VEC - 1) / VEC;
-    int64_t want = (rows * G + 7) / 8;  // about 8 rows per thread
-    if (want < G) want = G;
-    int blocks = blocks_for(want);
-    if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
-    const int use_lds = D <= 8192;
-    const size_t shm = use_lds ? sizeof(int32_t) * 2 * (size_t)D : 0;
-#define BF_FIT(T, V) \
-    fit_minmax_kernel<T, V><<<blocks, kThreads, shm, s>>>((const T *)chunk, rows, D, G, p->d_fit, use_lds)
-    if (dtype == BIFEAT_F32) {
-        if (vec) BF_FIT(float, 4); else BF_FIT(float, 1);
-    } else {
-        if (vec) BF_FIT(__half, 4); else BF_FIT(__half, 1);
-    }
-#undef BF_FIT
-    return hipGetLastError();
+    if (dtype == BIFEAT_F32) return launch_fit_minmax_src(p, ChunkSrc<float>{(const float *)chunk, D}, rows, vec, s);
+    return launch_fit_minmax_src(p, ChunkSrc<__half>{(const __half *)chunk, D}, rows, vec, s);
 }
 
 // scale_j = (max_j - min_j)/L and inv_j = L/(max_j - min_j): fp64 subtraction
@@ -215,124 +121,6 @@ hipError_t launch_finalize_uniform(bifeat_params *p, hipStream_t s) {
     finalize_uniform_kernel<<<(D + 255) / 256, 256, 0, s>>>(p->d_fit, D, p->scheme.bits, p->d_min,
                                                             p->d_max, p->d_scale, p->d_inv);
     return hipGetLastError();
-}
-
-// ------------------------------------------------------------ scalar encoders
-struct UniformCoder {
-    static constexpr bool kEdges = false;
-    const float *mn, *inv;
-    float L;
-    struct Ctx { float mn[4], inv[4]; };
-    __device__ void prepare(Ctx &c, int col0, int D) const {
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            bool ok = col0 + k < D;
-            c.mn[k] = ok ? mn[col0 + k] : 0.0f;
-            c.inv[k] = ok ? inv[col0 + k] : 0.0f;
-        }
-    }
-    // q = clamp(rne((x - min) * inv), 0, L); sub, mul, round are separate fp32
-    // operations; max/min discard NaN, so NaN -> 0
-    __device__ uint32_t code(const Ctx &c, float x, int k) const {
-        float d = __fsub_rn(x, c.mn[k]);
-        float t = __fmul_rn(d, c.inv[k]);
-        float r = rintf(t);
-        r = fminf(fmaxf(r, 0.0f), L);
-        return (uint32_t)(int)r;
-    }
-};
-
-struct LogCoder {
-    static constexpr bool kEdges = true;
-    const float *T;  // global, H-1 edges
-    int H;
-    struct Ctx { const float *edges; };
-    __device__ void prepare(Ctx &c, int, int) const { c.edges = nullptr; }
-    // l = #{i : |x| >= T_i} by bisection over the sorted edges (in LDS)
-    __device__ uint32_t code(const Ctx &c, float x, int) const {
-        float m = fabsf(x);
-        int lo = 0, hi = H - 1;
-        while (lo < hi) {
-            int mid = (lo + hi) >> 1;
-            if (m >= c.edges[mid]) lo = mid + 1; else hi = mid;
-        }
-        return (uint32_t)((x > 0.0f) ? H + lo : H - 1 - lo);
-    }
-};
-
-// One thread encodes 4 consecutive columns (4*BITS bits); 8/BITS neighbouring
-// lanes OR their pieces into one 32-bit word and one of them stores it.  Every
-// word of the padded row is written (columns >= D encode as 0).
-template <typename T, int BITS, typename Coder, bool VEC>
-__global__ __launch_bounds__(kThreads) void quantize_sq_kernel(const T *__restrict__ x,
-                                                              int64_t rows, int D, int64_t rb,
-                                                              Coder coder,
-                                                              uint8_t *__restrict__ codes) {
-    __shared__ float s_edges[128];
-    typename Coder::Ctx ctx;
-    constexpr int LG = 8 / BITS;  // lanes per 32-bit word
-    const int GW = (int)(2 * rb / BITS);  // 4-column groups per padded row; multiple of 4*LG
-    if constexpr (Coder::kEdges) {
-        for (int i = threadIdx.x; i < coder.H - 1; i += kThreads) s_edges[i] = coder.T[i];
-        __syncthreads();
-    }
-    const uint32_t total = gridDim.x * kThreads;
-    const uint32_t rows_per_pass = total / (uint32_t)GW;
-    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
-    if (t >= rows_per_pass * (uint32_t)GW) return;
-    const int g = (int)(t % (uint32_t)GW);
-    const int col0 = 4 * g;
-    coder.prepare(ctx, col0, D);
-    if constexpr (Coder::kEdges) ctx.edges = s_edges;
-    const int sub = g % LG;
-    uint32_t *dst_word = reinterpret_cast<uint32_t *>(codes) + (g / LG);
-    const int64_t rw = rb / 4;
-    // rows interleaved across the grid: a wave's stores stay contiguous (consecutive rows
-    // per thread, as in the fit kernel, measured 15 % slower here)
-    for (int64_t r = t / GW; r < rows; r += rows_per_pass) {
-        float v[4] = {0.f, 0.f, 0.f, 0.f};
-        const T *src = x + r * D + col0;
-        if (VEC) {
-            if (col0 < D) {
-                float4 q = load4(src);
-                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; k++)
-                if (col0 + k < D) v[k] = load1(src + k);
-        }
-        uint32_t piece = 0;
-#pragma unroll
-        for (int k = 0; k < 4; k++) {
-            uint32_t q = (col0 + k < D) ? coder.code(ctx, v[k], k) : 0u;
-            piece |= q << (BITS * k);
-        }
-        piece <<= (4 * BITS) * sub;
-#pragma unroll
-        for (int o = 1; o < LG; o <<= 1) piece |= (uint32_t)__shfl_xor((int)piece, o);
-        if (sub == 0) dst_word[r * rw] = piece;
-    }
-}
-
-template <typename T, typename Coder>
-static void launch_sq(const T *x, int64_t rows, int D, int64_t rb, int bits, Coder coder,
-                      uint8_t *codes, bool vec, hipStream_t s) {
-    const int GW = (int)(2 * rb / bits);
-    int64_t want = (rows * GW + 3) / 4;
-    if (want < GW) want = GW;
-    int blocks = blocks_for(want);
-    if ((int64_t)blocks * kThreads < GW) blocks = (GW + kThreads - 1) / kThreads;
-#define BF_Q(B)                                                                                 \
-    if (vec) quantize_sq_kernel<T, B, Coder, true><<<blocks, kThreads, 0, s>>>(x, rows, D, rb, coder, codes); \
-    else quantize_sq_kernel<T, B, Coder, false><<<blocks, kThreads, 0, s>>>(x, rows, D, rb, coder, codes)
-    switch (bits) {
-        case 1: BF_Q(1); break;
-        case 2: BF_Q(2); break;
-        case 4: BF_Q(4); break;
-        default: BF_Q(8); break;
-    }
-#undef BF_Q
 }
 
 // Vector codes (Sec. 3.2): workgroup = one part x strips of 256 rows, thread =
@@ -463,14 +251,10 @@ hipError_t launch_quantize(bifeat_params *p, const void *chunk, int dtype, int64
     if (p->scheme.kind == BIFEAT_VQ) {
         if (dtype == BIFEAT_F32) launch_vq_assign(p, (const float *)chunk, rows, codes, p->rb, s);
         else launch_vq_assign(p, (const __half *)chunk, rows, codes, p->rb, s);
-    } else if (p->scheme.kind == BIFEAT_SQ_UNIFORM) {
-        UniformCoder c{p->d_min, p->d_inv, (float)((1u << p->scheme.bits) - 1u)};
-        if (dtype == BIFEAT_F32) launch_sq((const float *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
-        else launch_sq((const __half *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
+    } else if (dtype == BIFEAT_F32) {
+        return launch_quantize_sq_src(p, ChunkSrc<float>{(const float *)chunk, D}, rows, codes, vec, s);
     } else {
-        LogCoder c{p->d_T, 1 << (p->scheme.bits - 1)};
-        if (dtype == BIFEAT_F32) launch_sq((const float *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
-        else launch_sq((const __half *)chunk, rows, D, p->rb, p->scheme.bits, c, codes, vec, s);
+        return launch_quantize_sq_src(p, ChunkSrc<__half>{(const __half *)chunk, D}, rows, codes, vec, s);
     }
     return hipGetLastError();
 }

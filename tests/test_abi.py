@@ -83,6 +83,10 @@ def test_argument_errors_come_before_any_gpu_call(bf):
     assert lib.bifeat_reserve(h, 1000, None) == 0                # scalar codes: no workspace
     assert lib.bifeat_gather_dequant_static(h, None, 10, None, 5, None, None) == -1
     assert lib.bifeat_gather_dequant_static(h, 16, 10, 16, 5, 16, None) == -2        # not fitted
+    assert lib.bifeat_produce_fit_begin(None, None) == -1
+    assert lib.bifeat_produce_fit_end(h, 3) == -1                # no fit open
+    assert lib.bifeat_produce_quantize_check(h, 16, 4, 0) == -2  # not fitted
+    assert lib.bifeat_set_option(h, b"row_align", 64) == -1      # 16 or 128
     assert lib.bifeat_set_option(h, b"no_such_option", 1) == -1
     assert lib.bifeat_set_option(h, b"mean_slots", 4) == 0
     assert lib.bifeat_row_bytes(None) == -1
