@@ -342,6 +342,19 @@ def aggregate_rows(x, indptr, indices, sum: bool = False) -> np.ndarray:
     return out
 
 
+def gather_mean_2hop(s: Scheme, codes, indptr1, indices1, indptr2, indices2) -> np.ndarray:
+    """Appendix A.1 applied twice with nothing in between: the mean over the seed
+    block's lists of the means over the outer block's lists of decoded rows."""
+    codes = _u8(codes)
+    indptr1, indices1, indptr2, indices2 = _i64(indptr1), _i64(indices1), _i64(indptr2), _i64(indices2)
+    assert codes.shape[1] == s.row_bytes
+    V2 = indptr2.shape[0] - 1
+    out = np.empty((V2, s.D), dtype=np.float32)
+    lib().orc_gather_mean_2hop(C.byref(s._c), _p(codes), _p(indptr1), _p(indices1), _p(indptr2),
+                               _p(indices2), C.c_int64(V2), _p(out))
+    return out
+
+
 def scale_profile(x, indptr, indices, layers: int) -> np.ndarray:
     """Appendix A.1 / A.5: mean row length after 0..layers rounds of
     neighbourhood averaging over the whole graph (fp64)."""

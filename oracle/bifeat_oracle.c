@@ -622,6 +622,47 @@ void orc_aggregate_rows(const float *x, int64_t D, const int64_t *indptr, const 
     }
 }
 
+/* Two rounds of Appendix A.1's averaging with nothing in between, straight from
+ * the packed table: g1[u] = (1/|N1(u)|) sum_{w in N1(u)} decode(codes[w]) for the
+ * destinations u of the outer block (lists of table rows), and
+ * out[v] = (1/|N2(v)|) sum_{u in N2(v)} g1[u] for the destinations v of the seed
+ * block (lists of outer-block destinations, 0 <= u < V1).  Lists in the order
+ * given, repeats with multiplicity; an empty N1(u) makes g1[u] a zero row that
+ * still counts in |N2(v)|; an empty N2(v) gives a zero row.  fp64 throughout,
+ * g1 is not rounded, one rounding to fp32 at the end. */
+void orc_gather_mean_2hop(const orc_scheme *s, const uint8_t *codes, const int64_t *indptr1,
+                          const int64_t *indices1, const int64_t *indptr2, const int64_t *indices2,
+                          int64_t V2, float *out) {
+    int64_t rb = orc_scheme_row_bytes(s), D = s->D;
+#pragma omp parallel
+    {
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)D);
+        double *g1 = (double *)malloc(sizeof(double) * (size_t)D);
+        double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t v = 0; v < V2; v++) {
+            int64_t n2 = indptr2[v + 1] - indptr2[v];
+            for (int64_t j = 0; j < D; j++) acc[j] = 0.0;
+            for (int64_t e2 = indptr2[v]; e2 < indptr2[v + 1]; e2++) {
+                int64_t u = indices2[e2];
+                int64_t n1 = indptr1[u + 1] - indptr1[u];
+                for (int64_t j = 0; j < D; j++) g1[j] = 0.0;
+                for (int64_t e1 = indptr1[u]; e1 < indptr1[u + 1]; e1++) {
+                    decode_row(s, codes + indices1[e1] * rb, tmp);
+                    for (int64_t j = 0; j < D; j++) g1[j] += tmp[j];
+                }
+                if (n1 > 0)
+                    for (int64_t j = 0; j < D; j++) acc[j] += g1[j] / (double)n1;
+            }
+            for (int64_t j = 0; j < D; j++)
+                out[v * D + j] = (n2 > 0) ? (float)(acc[j] / (double)n2) : 0.0f;
+        }
+        free(tmp);
+        free(g1);
+        free(acc);
+    }
+}
+
 /* Appendix A.1 defines, per node i and depth l, the factors C^e_{i,l} and
  * C^f_{i,l}: by how much l rounds of neighbourhood averaging shrink a
  * quantisation error (independent between nodes) and the features themselves
