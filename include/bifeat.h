@@ -260,6 +260,33 @@ int bifeat_gather_sum(bifeat_params *p, const uint8_t *codes, int64_t N, const i
 int bifeat_gather_sum_i32(bifeat_params *p, const uint8_t *codes, int64_t N, const int64_t *indptr,
                           const int32_t *indices, int64_t V, int64_t E, float *out, void *stream);
 
+/* ---- two rounds of the neighbourhood mean with nothing in between, straight
+ * from the packed table (Appendix A.1 writes every layer's aggregation as
+ * g_i = 1/|N(i)| sum_{j in N(i)} g_j and analyses how errors shrink when it is
+ * applied repeatedly; this is that linear propagation for two layers of a
+ * sampled minibatch).  The outer block (indptr1 [V1+1], indices1 [E1]) lists
+ * table rows for each of its V1 destinations; the seed block (indptr2 [V2+1],
+ * indices2 [E2], entries in [0, V1)) lists outer-block destinations for each
+ * of the V2 seeds.  For v in [0, V2):
+ *     out[v, :] = mean over u in list2(v) of ( mean over w in list1(u) of decode(codes[w]) ),
+ * lists taken as given; an empty list1(u) is a zero row that still counts in
+ * the length of list2(v); an empty list2(v) gives a zero row.  The same result
+ * as bifeat_gather_mean over the outer block followed by bifeat_aggregate_rows
+ * over the seed block, without the [V1 x D] fp32 rows in between ever being
+ * written.  All pointers DEVICE; out: [V2 x D] fp32, within 1e-5 *
+ * max(|exact|, A_j) of the exact value as for bifeat_gather_mean.
+ * With option "mean_max_degree" = m (1 <= m <= 64) promising that no list of
+ * either block is longer than m, scalar codes that decode affinely (uniform;
+ * logarithmic of 1 or 2 bits) take a kernel that sums codes as integers and
+ * keeps the running means in registers; a list that breaks the promise gives a
+ * NaN row and raises the status word as described below.  Without the promise,
+ * and for the other codes, a general kernel of any list length runs.
+ * Option "validate" checks both blocks first.  V2 = 0 is a no-op. */
+int bifeat_gather_mean_2hop(bifeat_params *p, const uint8_t *codes, int64_t N,
+                            const int64_t *indptr1, const int64_t *indices1, int64_t V1, int64_t E1,
+                            const int64_t *indptr2, const int64_t *indices2, int64_t V2, int64_t E2,
+                            float *out, void *stream);
+
 /* A promise the caller made through option "mean_max_degree" and a list broke
  * (Appendix A.1's mean needs every neighbour of the list): the kernel that
  * meets such a list writes NaN into its whole output row and raises the

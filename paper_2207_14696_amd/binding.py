@@ -72,6 +72,10 @@ _SIGNATURES = {
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_gather_sum": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "bifeat_gather_mean_2hop": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                          C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                          C.c_void_p, C.c_void_p]),
     "bifeat_gather_mean_i32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                          C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "bifeat_gather_sum_i32": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -300,6 +304,23 @@ class Quantizer:
     def gather_sum(self, codes, indptr, indices, out=None):
         return self._aggregate(self._lib.bifeat_gather_sum, self._lib.bifeat_gather_sum_i32,
                                codes, indptr, indices, out)
+
+    def gather_mean_2hop(self, codes, indptr1, indices1, indptr2, indices2, out=None):
+        """``bifeat_gather_mean_2hop``: mean over the seed block's lists (entries = destinations
+        of the outer block) of the means over the outer block's lists of decoded rows."""
+        import torch
+        V1, V2 = indptr1.shape[0] - 1, indptr2.shape[0] - 1
+        if out is None:
+            out = torch.empty((V2, self.D), dtype=torch.float32, device=codes.device)
+        elif out.shape != (V2, self.D):
+            raise ValueError("out must be [V2, D]")
+        i64 = (torch.int64,)
+        _check(self._lib.bifeat_gather_mean_2hop(
+            self._h, _dev_ptr(codes, (torch.uint8,)), codes.shape[0],
+            _dev_ptr(indptr1, i64), _dev_ptr(indices1, i64), V1, indices1.shape[0],
+            _dev_ptr(indptr2, i64), _dev_ptr(indices2, i64), V2, indices2.shape[0],
+            _dev_ptr(out, (torch.float32,)), _stream()))
+        return out
 
     def poll_status(self, wait: bool = True) -> bool:
         """``bifeat_poll_status``: False if a kernel of an earlier call met a list longer

@@ -702,6 +702,30 @@ int bifeat_gather_sum_i32(bifeat_params *p, const uint8_t *codes, int64_t N, con
     return gather_aggregate(p, codes, N, indptr, indices, true, V, E, 1, out, stream);
 }
 
+int bifeat_gather_mean_2hop(bifeat_params *p, const uint8_t *codes, int64_t N,
+                            const int64_t *indptr1, const int64_t *indices1, int64_t V1, int64_t E1,
+                            const int64_t *indptr2, const int64_t *indices2, int64_t V2, int64_t E2,
+                            float *out, void *stream) {
+    if (!p || N < 0 || V1 < 0 || E1 < 0 || V2 < 0 || E2 < 0) return BIFEAT_EINVAL;
+    if (V2 > 0 && (!codes || !indptr2 || !out || (E2 > 0 && (!indices2 || !indptr1 || V1 == 0)) ||
+                   (E1 > 0 && !indices1)))
+        return BIFEAT_EINVAL;
+    if ((uintptr_t)codes % 16 || (uintptr_t)out % 4) return BIFEAT_EINVAL;
+    if (!p->fitted) return BIFEAT_ENOTFIT;
+    if (take_status(p)) return BIFEAT_EINVAL;
+    if (V2 == 0) return BIFEAT_OK;
+    if (p->opt_validate) {
+        if (int rc = check_inputs(p, indices1, E1, N, indptr1, V1, E1, (hipStream_t)stream)) return rc;
+        if (int rc = check_inputs(p, indices2, E2, V1, indptr2, V2, E2, (hipStream_t)stream)) return rc;
+    }
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    const bf::HopCall c{codes, N, indptr1, indices1, V1, E1, indptr2, indices2, V2, E2, out,
+                        p->opt_mean_max_degree, p->d_status, (hipStream_t)stream};
+    BF_HIP(bf::launch_gather_mean_2hop(p, c));
+    return BIFEAT_OK;
+}
+
 int bifeat_poll_status(bifeat_params *p, void *stream, int32_t wait) {
     if (!p) return BIFEAT_EINVAL;
     if (wait) BF_HIP(hipStreamSynchronize((hipStream_t)stream));

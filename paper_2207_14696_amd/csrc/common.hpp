@@ -163,6 +163,25 @@ bool launch_gather_mean_lean_log2(bifeat_params *p, const MeanCall &c, int thr, 
 bool launch_gather_mean_lean(bifeat_params *p, const MeanCall &c, int thr, bool wide, int lo,
                              bool alone);
 
+// Two rounds of the neighbourhood mean from the packed table: the outer block's lists hold
+// table rows (one list per first-round destination), the seed block's lists hold first-round
+// destinations.
+struct HopCall {
+    const uint8_t *codes;
+    int64_t N;
+    const int64_t *indptr1, *indices1;  // [V1 + 1], [E1]
+    int64_t V1, E1;
+    const int64_t *indptr2, *indices2;  // [V2 + 1], [E2], entries in [0, V1)
+    int64_t V2, E2;
+    float *out;      // [V2 x D]
+    int max_degree;  // the caller's bound on every list length of both blocks (0 = none given)
+    int32_t *status;
+    hipStream_t s;
+};
+hipError_t launch_gather_mean_2hop(bifeat_params *p, const HopCall &c);
+bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, bool pair);
+int hop_lean_max_list();
+
 // ---- order-preserving float <-> int keys for atomic min/max
 __host__ __device__ inline int32_t float_key(float f) {
     union { float f; int32_t i; } u;
@@ -239,6 +258,18 @@ __device__ inline void load_words(const uint8_t *p, uint32_t *w) {
         w[0] = *reinterpret_cast<const uint32_t *>(p);
     }
 }
+
+// ---- field-parallel integer sums of packed code words (the short-list aggregation kernels)
+template <int BITS, bool WIDE> struct LeanSwar;
+// kF: field width, kN: registers per 32-bit word; register i, field f holds the
+// sum of code number i + f*kN; kCap = rows a field can sum.  The WIDE forms
+// spend more shift+mask work per word on fields that hold longer lists.
+template <bool WIDE> struct LeanSwar<8, WIDE> { static constexpr int kF = 16, kN = 2, kCap = 257; static constexpr uint32_t kMask = 0x00FF00FFu; };
+template <> struct LeanSwar<4, false> { static constexpr int kF = 8, kN = 2, kCap = 17; static constexpr uint32_t kMask = 0x0F0F0F0Fu; };
+template <> struct LeanSwar<4, true> { static constexpr int kF = 16, kN = 4, kCap = 4369; static constexpr uint32_t kMask = 0x000F000Fu; };
+template <bool WIDE> struct LeanSwar<2, WIDE> { static constexpr int kF = 8, kN = 4, kCap = 85; static constexpr uint32_t kMask = 0x03030303u; };
+template <> struct LeanSwar<1, false> { static constexpr int kF = 4, kN = 4, kCap = 15; static constexpr uint32_t kMask = 0x11111111u; };
+template <> struct LeanSwar<1, true> { static constexpr int kF = 8, kN = 8, kCap = 255; static constexpr uint32_t kMask = 0x01010101u; };
 
 // a kernel reports a broken caller promise: a plain system-scope store of the code into the
 // mapped status word (no read-modify-write across the bus; the word holds the last code raised)

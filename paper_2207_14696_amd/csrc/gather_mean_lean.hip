@@ -20,17 +20,6 @@
 
 namespace bf {
 
-template <int BITS, bool WIDE> struct LeanSwar;
-// kF: field width, kN: registers per 32-bit word; register i, field f holds the
-// sum of code number i + f*kN; kCap = rows a field can sum.  The WIDE forms
-// spend more shift+mask work per word on fields that hold longer lists.
-template <bool WIDE> struct LeanSwar<8, WIDE> { static constexpr int kF = 16, kN = 2, kCap = 257; static constexpr uint32_t kMask = 0x00FF00FFu; };
-template <> struct LeanSwar<4, false> { static constexpr int kF = 8, kN = 2, kCap = 17; static constexpr uint32_t kMask = 0x0F0F0F0Fu; };
-template <> struct LeanSwar<4, true> { static constexpr int kF = 16, kN = 4, kCap = 4369; static constexpr uint32_t kMask = 0x000F000Fu; };
-template <bool WIDE> struct LeanSwar<2, WIDE> { static constexpr int kF = 8, kN = 4, kCap = 85; static constexpr uint32_t kMask = 0x03030303u; };
-template <> struct LeanSwar<1, false> { static constexpr int kF = 4, kN = 4, kCap = 15; static constexpr uint32_t kMask = 0x11111111u; };
-template <> struct LeanSwar<1, true> { static constexpr int kF = 8, kN = 8, kCap = 255; static constexpr uint32_t kMask = 0x01010101u; };
-
 static int cap64(int cap) { return cap < 64 ? cap : 64; }
 
 // longest list the short-list kernel takes, in its narrow and wide forms

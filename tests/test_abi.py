@@ -76,6 +76,10 @@ def test_argument_errors_come_before_any_gpu_call(bf):
     assert lib.bifeat_gather_mean_i32(h, None, 10, None, None, 3, 7, None, None) == -1
     assert lib.bifeat_gather_sum_i32(h, 16, 1 << 31, 16, 16, 1, 1, 16, None) == -1   # ids need 32 bits
     assert lib.bifeat_gather_mean_i32(h, 16, 10, 16, 16, 1, 1, 16, None) == -2       # not fitted
+    assert lib.bifeat_gather_mean_2hop(h, None, 10, None, None, 3, 7, None, None, 2, 4, None, None) == -1
+    assert lib.bifeat_gather_mean_2hop(h, 16, 10, 16, 16, 3, 7, 16, 16, -2, 4, 16, None) == -1
+    assert lib.bifeat_gather_mean_2hop(h, 16, 10, 16, 16, 0, 0, 16, 16, 2, 4, 16, None) == -1  # entries but no outer block
+    assert lib.bifeat_gather_mean_2hop(h, 16, 10, 16, 16, 3, 7, 16, 16, 2, 4, 16, None) == -2  # not fitted
     assert lib.bifeat_poll_status(None, None, 0) == -1
     assert lib.bifeat_poll_status(h, None, 0) == 0               # nothing raised, no device touched
     assert lib.bifeat_reserve(None, 5, None) == -1
