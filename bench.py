@@ -62,6 +62,8 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="replay each launch-set's step from a captured HIP graph (whole-step "
                          "timing; per-kernel figures still come from an eager pass)")
+    ap.add_argument("--no-two-hop", action="store_true",
+                    help="skip the two-round aggregation leg (fused call against the two-call chain)")
     ap.add_argument("--scale-profile", type=int, default=0, metavar="LAYERS",
                     help="after the timed region, also run the aggregation scale profile (error and "
                          "feature scale after 1..LAYERS rounds of neighbourhood averaging, and their "
@@ -385,6 +387,7 @@ def main():
         cpu = cpu_baseline(w, g, args.cpu_seconds)
 
     sp = scale_profile_leg(args, w, q, codes, table) if args.scale_profile > 0 else None
+    two = two_hop_leg(w, q, codes, g, L) if len(w.fanouts) >= 2 and not args.no_two_hop else None
 
     value = rows_total / wall
     res = {
@@ -410,7 +413,69 @@ def main():
     }
     if sp is not None:
         res["scale_profile"] = sp
+    if two is not None:
+        res["two_hop"] = two
     print(json.dumps(res))
+
+
+def two_hop_leg(w, q, codes, g, L):
+    """Two rounds of the neighbourhood mean with nothing in between (Appendix A.1's linear
+    propagation) over the two outermost blocks of L minibatches: ``bifeat_gather_mean_2hop``
+    against ``bifeat_gather_mean`` + ``bifeat_aggregate_rows``, outside the timed region."""
+    import torch
+    import paper_2207_14696_amd as bf
+    from bifeat_inputs import draw_seeds, sample_blocks
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    H = len(w.fanouts)
+    p1, i1, p2, i2 = [np.zeros(1, np.int64)], [], [np.zeros(1, np.int64)], []
+    o1 = o2 = voff = 0
+    for bi in range(L):
+        blocks, _ = sample_blocks(g, draw_seeds(g, w.batch, w.seed, bi, w.seed_mode), w.fanouts, w.seed, bi)
+        outer, inner = blocks[H - 1], blocks[H - 2]
+        # the inner block's entries as positions among the outer block's (sorted) destinations
+        local = np.searchsorted(outer.dst, inner.indices)
+        p1.append(outer.indptr[1:] + o1)
+        i1.append(outer.indices)
+        p2.append(inner.indptr[1:] + o2)
+        i2.append(local + voff)
+        o1 += outer.E
+        o2 += inner.E
+        voff += outer.V
+    p1, i1, p2, i2 = (np.concatenate(a) for a in (p1, i1, p2, i2))
+    V1, V2 = p1.shape[0] - 1, p2.shape[0] - 1
+    d = lambda a: torch.from_numpy(a).cuda()
+    dp1, di1, dp2, di2 = d(p1), d(i1), d(p2), d(i2)
+    h1 = torch.empty((V1, w.D), dtype=torch.float32, device="cuda")
+    h2 = torch.empty((V2, w.D), dtype=torch.float32, device="cuda")
+    hf = torch.empty_like(h2)
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / reps * 1e3
+
+    q.set_option("mean_max_degree", w.fanouts[H - 1])
+    t1 = timed(lambda: q.gather_mean(codes, dp1, di1, h1))
+    t2 = timed(lambda: bf.aggregate_rows(h1, dp2, di2, out=h2))
+    q.set_option("mean_max_degree", max(w.fanouts[H - 1], w.fanouts[H - 2]))
+    tf = timed(lambda: q.gather_mean_2hop(codes, dp1, di1, dp2, di2, hf))
+    ok = q.poll_status(wait=True)
+    q.set_option("mean_max_degree", 0)
+    fetches = int(np.diff(p1)[i2].sum())
+    say(f"two rounds: chain {t1:.1f} + {t2:.1f} us, one call {tf:.1f} us")
+    return {"dst": V2, "entries": int(i2.shape[0]), "outer_dst": V1, "outer_edges": int(i1.shape[0]),
+            "chain_us": round(t1 + t2, 1), "chain_layer1_us": round(t1, 1), "chain_layer2_us": round(t2, 1),
+            "fused_us": round(tf, 1), "fused_row_fetches": fetches,
+            "fused_fetched_GBps": round(fetches * q.row_bytes / tf / 1e3, 1),
+            "intermediate_MB_avoided": round(V1 * w.D * 4 / 1e6, 1),
+            "max_abs_diff_to_chain": float((hf - h2).abs().max().item()), "status_ok": bool(ok)}
 
 
 def scale_profile_leg(args, w, q, codes, table):

@@ -9,9 +9,12 @@
 //   out[v, j] = min_j * (#non-empty N1(u))/|N2(v)| + scale_j * (1/|N2(v)|) sum_u S_u[j]/|N1(u)|.
 //
 // This form needs the caller's bound on the list lengths (at most 64): every list sum then
-// fits one field and a destination adds at most 64 terms in fp32 (relative error below
-// 66 * 2^-24 of a sum of non-negative terms).  Anything else takes the general kernel in
-// gather_mean.hip.
+// fits one field (4-bit codes: lists of 18 to 32 rows as two pieces in narrow fields) and a
+// destination adds at most 64 terms in fp32 (relative error below 66 * 2^-24 of a sum of
+// non-negative terms).  Anything else takes the general kernel in gather_mean.hip.
+// A wave's time is a chain of dependent fetches (seed list -> outer lists' bounds -> row ids
+// -> rows), so the kernel lives on resident waves: what was measured to matter is one wave
+// per workgroup, no register spills, and the cheapest field form the bound allows.
 #include "common.hpp"
 
 namespace bf {
@@ -25,6 +28,10 @@ namespace {
 constexpr int kHopThreads = BF_HOP_THREADS;
 constexpr int kHopWaves = kHopThreads / 64;
 constexpr int kHopIds = 256;  // row ids a wave parks in LDS at a time: 4 per lane
+constexpr int kHopPiece = 16;  // rows per piece of a split list
+#ifndef BF_HOP_SPLIT16
+#define BF_HOP_SPLIT16 1
+#endif
 #ifndef BF_HOP_U
 #define BF_HOP_U 4
 #endif
@@ -37,8 +44,11 @@ constexpr int kHopIds = 256;  // row ids a wave parks in LDS at a time: 4 per la
 // across the groups at the end.  A wave serves 64 / (LPR * G2) destinations.
 // PAIR: 2-bit logarithmic codes read as 2*D one-bit columns whose affine maps add pairwise
 // (see launch_gather_mean_lean_log2); Dp = number of parameter columns (D, or 2*D).
-template <int BITS, int CW, bool WIDE, bool PAIR>
-__global__ __launch_bounds__(kHopThreads, BF_HOP_WPE) void gather_mean_2hop_lean_kernel(
+// SPLIT: outer lists of more than kHopPiece rows are summed as two pieces, each within what a
+// narrow field holds (the bound is then at most 2 * kHopPiece, and a destination still adds at
+// most 64 fp32 terms); cheaper per row than the wide fields.
+template <int BITS, int CW, bool WIDE, bool PAIR, bool SPLIT>
+__global__ __launch_bounds__(kHopThreads, (BITS == 4 && CW == 4 && WIDE) ? 3 : BF_HOP_WPE) void gather_mean_2hop_lean_kernel(
     const uint8_t *__restrict__ codes, uint32_t rb, const int64_t *__restrict__ indptr1,
     const int64_t *__restrict__ indices1, const int64_t *__restrict__ indptr2,
     const int64_t *__restrict__ indices2, int64_t V2, int D, int Dp, const float *__restrict__ mn,
@@ -64,8 +74,11 @@ __global__ __launch_bounds__(kHopThreads, BF_HOP_WPE) void gather_mean_2hop_lean
     const int lv = lane & (VL - 1);
     const int ROUND = 4 * LPR;  // row ids a group parks at a time
     uint32_t *sidx = smem + wave * kHopIds + (lane >> lpr_log2) * ROUND;
-    // per destination: (start, length) of the outer list of every seed-list entry
-    uint2 *smeta = reinterpret_cast<uint2 *>(smem + kHopWaves * kHopIds) + (wave * vpw + vslot) * thr;
+    // per destination, for every piece of work (the outer list of a seed-list entry, or one of
+    // its two pieces): x = where its row ids start, y = rows | whole list's length << 8 |
+    // (first piece) << 16
+    uint2 *smeta = reinterpret_cast<uint2 *>(smem + kHopWaves * kHopIds) +
+                   (wave * vpw + vslot) * (SPLIT ? 2 * thr : thr);
     const bool chunk_ok = sub < chunks;
     const uint32_t coff = (uint32_t)sub * (CW * 4);
     const uint64_t vmask = (VL == 64 ? ~0ull : ((1ull << VL) - 1ull)) << (vslot << vl_log2);
@@ -91,12 +104,29 @@ __global__ __launch_bounds__(kHopThreads, BF_HOP_WPE) void gather_mean_2hop_lean
         if (heavy > 0 && (__ballot(e2 - b2 > heavy) != 0) == second) continue;
         bool bad = e2 - b2 > thr;  // a list beyond the promised bound
         const int n2 = bad ? 0 : (int)(e2 - b2);
-        for (int j = lv; j < n2; j += VL) {
-            const int64_t u = indices2[b2 + j];
-            const int64_t b1 = indptr1[u], e1 = indptr1[u + 1];
-            const bool over = e1 - b1 > thr;
-            bad |= over;
-            smeta[j] = make_uint2((uint32_t)b1, over ? 0u : (uint32_t)(e1 - b1));
+        int npiece = n2;
+        for (int j0 = 0; __ballot(j0 + lv < n2) != 0; j0 += VL) {
+            const int j = j0 + lv;
+            uint32_t b1 = 0u, len = 0u;
+            if (j < n2) {
+                const int64_t u = indices2[b2 + j];
+                const int64_t beg = indptr1[u], end = indptr1[u + 1];
+                const bool over = end - beg > thr;
+                bad |= over;
+                b1 = (uint32_t)beg;
+                len = over ? 0u : (uint32_t)(end - beg);
+                const uint32_t head = SPLIT ? min(len, (uint32_t)kHopPiece) : len;
+                smeta[j] = make_uint2(b1, head | (len << 8) | (1u << 16));
+            }
+            if constexpr (SPLIT) {
+                // second pieces go behind the n2 first ones, in the order of their entries
+                const bool more = len > (uint32_t)kHopPiece;
+                const uint64_t mine = (__ballot(more) & vmask) >> (vslot << vl_log2);
+                if (more)
+                    smeta[npiece + __popcll(mine & ((1ull << lv) - 1ull))] =
+                        make_uint2(b1 + kHopPiece, (len - kHopPiece) | (len << 8));
+                npiece += __popcll(mine);
+            }
         }
         wave_sync();
 
@@ -107,32 +137,33 @@ __global__ __launch_bounds__(kHopThreads, BF_HOP_WPE) void gather_mean_2hop_lean
         int j = q;
         uint32_t idn[4];  // the first row ids of the next outer list, fetched one list ahead
         {
-            const uint2 m = j < n2 ? smeta[j] : make_uint2(0u, 0u);
+            const uint2 m = j < npiece ? smeta[j] : make_uint2(0u, 0u);
 #pragma unroll
             for (int r = 0; r < 4; r++) {
                 const uint32_t i = (uint32_t)(r * LPR + sub);
-                idn[r] = i < m.y ? (uint32_t)indices1[(uint64_t)m.x + i] : 0u;
+                idn[r] = i < (m.y & 0xFFu) ? (uint32_t)indices1[(uint64_t)m.x + i] : 0u;
             }
         }
-        for (; __ballot(j < n2) != 0; j += G2) {
-            const uint2 m = j < n2 ? smeta[j] : make_uint2(0u, 0u);
-            const int n1 = (int)m.y;
+        for (; __ballot(j < npiece) != 0; j += G2) {
+            const uint2 m = j < npiece ? smeta[j] : make_uint2(0u, 0u);
+            const int n1 = (int)(m.y & 0xFFu);           // rows of this piece
+            const int whole = (int)((m.y >> 8) & 0xFFu);  // rows of the list it belongs to
 #pragma unroll
             for (int r = 0; r < 4; r++) sidx[r * LPR + sub] = idn[r];
             wave_sync();
             {
                 const int jn = j + G2;
-                const uint2 mx = jn < n2 ? smeta[jn] : make_uint2(0u, 0u);
+                const uint2 mx = jn < npiece ? smeta[jn] : make_uint2(0u, 0u);
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     const uint32_t i = (uint32_t)(r * LPR + sub);
-                    idn[r] = i < mx.y ? (uint32_t)indices1[(uint64_t)mx.x + i] : 0u;
+                    idn[r] = i < (mx.y & 0xFFu) ? (uint32_t)indices1[(uint64_t)mx.x + i] : 0u;
                 }
             }
             uint32_t acc[R];
 #pragma unroll
             for (int r = 0; r < R; r++) acc[r] = 0u;
-            const float inv = n1 > 0 ? 1.0f / (float)n1 : 0.0f;
+            const float inv = whole > 0 ? 1.0f / (float)whole : 0.0f;
             // field sums / |N1(u)| into the running means; the fields start over
 #define BF_HOP_FLUSH()                                                                            \
     _Pragma("unroll") for (int c = 0; c < CW; c++)                                                \
@@ -179,7 +210,7 @@ __global__ __launch_bounds__(kHopThreads, BF_HOP_WPE) void gather_mean_2hop_lean
             }
 #undef BF_HOP_STEP
             wave_sync();  // the id slots are rewritten by the next entry
-            nonempty += n1 > 0 ? 1 : 0;
+            nonempty += (m.y >> 16) != 0u && whole > 0 ? 1 : 0;
             BF_HOP_FLUSH()
 #undef BF_HOP_FLUSH
         }
@@ -243,10 +274,11 @@ __global__ __launch_bounds__(kHopThreads, BF_HOP_WPE) void gather_mean_2hop_lean
     }
 }
 
-template <int BITS, bool WIDE, bool PAIR>
+template <int BITS, bool WIDE, bool PAIR, bool SPLIT = false>
 bool launch_hop_bits(bifeat_params *p, const HopCall &c, int thr, const float *mn, const float *sc) {
     using W = LeanSwar<BITS, WIDE>;
-    if (thr > W::kCap) return false;
+    static_assert(!SPLIT || kHopPiece <= W::kCap, "a field holds a piece");
+    if (thr > (SPLIT ? 2 * kHopPiece : W::kCap)) return false;
     const int64_t payload = p->payload;
     // words per lane: at most 32 columns per lane stay in registers as fp32 accumulators
     const int cw_max = PAIR ? 1 : (BITS == 8 ? 4 : BITS);
@@ -282,9 +314,9 @@ bool launch_hop_bits(bifeat_params *p, const HopCall &c, int thr, const float *m
     const int64_t want = ((heavy ? 2 : 1) * tiles + kHopWaves - 1) / kHopWaves;
     const int blocks = (int)(want < cap ? (want < 1 ? 1 : want) : cap);
     const int D = (int)p->D, Dp = PAIR ? 2 * D : D;
-    const size_t shm = sizeof(uint32_t) * (size_t)kHopWaves * kHopIds + sizeof(uint2) * (size_t)kHopWaves * vpw * thr;
+    const size_t shm = sizeof(uint32_t) * (size_t)kHopWaves * kHopIds + sizeof(uint2) * (size_t)kHopWaves * vpw * (SPLIT ? 2 * thr : thr);
 #define BF_HK(CWV)                                                                                 \
-    gather_mean_2hop_lean_kernel<BITS, CWV, WIDE, PAIR><<<blocks, kHopThreads, shm, c.s>>>(        \
+    gather_mean_2hop_lean_kernel<BITS, CWV, WIDE, PAIR, SPLIT><<<blocks, kHopThreads, shm, c.s>>>(        \
         c.codes, (uint32_t)p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, Dp, mn, sc, \
         p->d_zero, c.out, lpr_log2, ilog2(g2), chunks, thr, heavy, c.status)
     if constexpr (PAIR) {
@@ -325,8 +357,9 @@ bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, b
                                                   : launch_hop_bits<1, false, false>(p, c, thr, mn, sc);
         case 2: return launch_hop_bits<2, false, false>(p, c, thr, mn, sc);
         case 4:
-            return thr > LeanSwar<4, false>::kCap ? launch_hop_bits<4, true, false>(p, c, thr, mn, sc)
-                                                  : launch_hop_bits<4, false, false>(p, c, thr, mn, sc);
+            if (thr <= LeanSwar<4, false>::kCap) return launch_hop_bits<4, false, false>(p, c, thr, mn, sc);
+            if (thr <= 2 * kHopPiece && BF_HOP_SPLIT16) return launch_hop_bits<4, false, false, true>(p, c, thr, mn, sc);
+            return launch_hop_bits<4, true, false>(p, c, thr, mn, sc);
         default: return launch_hop_bits<8, false, false>(p, c, thr, mn, sc);
     }
 }
