@@ -424,25 +424,13 @@ def two_hop_leg(w, q, codes, g, L):
     against ``bifeat_gather_mean`` + ``bifeat_aggregate_rows``, outside the timed region."""
     import torch
     import paper_2207_14696_amd as bf
-    from bifeat_inputs import draw_seeds, sample_blocks
+    from bifeat_inputs import two_round_set
 
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
     H = len(w.fanouts)
-    p1, i1, p2, i2 = [np.zeros(1, np.int64)], [], [np.zeros(1, np.int64)], []
-    o1 = o2 = voff = 0
-    for bi in range(L):
-        blocks, _ = sample_blocks(g, draw_seeds(g, w.batch, w.seed, bi, w.seed_mode), w.fanouts, w.seed, bi)
-        outer, inner = blocks[H - 1], blocks[H - 2]
-        # the inner block's entries as positions among the outer block's (sorted) destinations
-        local = np.searchsorted(outer.dst, inner.indices)
-        p1.append(outer.indptr[1:] + o1)
-        i1.append(outer.indices)
-        p2.append(inner.indptr[1:] + o2)
-        i2.append(local + voff)
-        o1 += outer.E
-        o2 += inner.E
-        voff += outer.V
-    p1, i1, p2, i2 = (np.concatenate(a) for a in (p1, i1, p2, i2))
+    # the outer block's lists hold table rows, the seed-side block's lists positions among
+    # the outer block's destinations
+    p1, i1, p2, i2 = two_round_set(w, g, 0, L)
     V1, V2 = p1.shape[0] - 1, p2.shape[0] - 1
     d = lambda a: torch.from_numpy(a).cuda()
     dp1, di1, dp2, di2 = d(p1), d(i1), d(p2), d(i2)

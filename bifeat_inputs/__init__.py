@@ -13,11 +13,11 @@ bit-identically, on the host (numpy, here) and on the device
 from .features import (column_params, feature_rows, feature_chunk, mix64,
                        stream_key, FeatureSpec)
 from .graphs import UniformGraph, PowerLawGraph, sample_blocks, draw_seeds, Block, full_csr
-from .workloads import WORKLOADS, Workload, make_graph, launch_set, BATCHES_PER_STEP
+from .workloads import WORKLOADS, Workload, make_graph, launch_set, two_round_set, BATCHES_PER_STEP
 
 __all__ = [
     "column_params", "feature_rows", "feature_chunk", "mix64", "stream_key",
     "FeatureSpec", "UniformGraph", "PowerLawGraph", "sample_blocks",
-    "draw_seeds", "Block", "full_csr", "WORKLOADS", "Workload", "make_graph", "launch_set",
+    "draw_seeds", "Block", "full_csr", "WORKLOADS", "Workload", "make_graph", "launch_set", "two_round_set",
     "BATCHES_PER_STEP",
 ]

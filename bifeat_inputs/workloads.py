@@ -102,3 +102,31 @@ def launch_set(w: Workload, graph, set_index: int, L: int):
             off += blocks[h].E
         hops.append((np.concatenate(ptr), np.concatenate([b[h].indices for b, _ in mbs])))
     return hops, np.concatenate([inp for _, inp in mbs])
+
+
+def two_round_set(w: Workload, graph, set_index: int, L: int):
+    """The two outermost blocks of launch-set ``set_index`` for a two-round
+    aggregation: L minibatches concatenated, the outer block's lists holding
+    table rows and the seed-side block's lists renumbered to positions among the
+    outer block's destinations (each minibatch's frontier is sorted, so a binary
+    search renumbers them).  Returns (indptr1, indices1, indptr2, indices2)."""
+    import numpy as np
+    from .graphs import draw_seeds, sample_blocks
+    H = len(w.fanouts)
+    assert H >= 2
+    p1, i1, p2, i2 = [np.zeros(1, np.int64)], [], [np.zeros(1, np.int64)], []
+    o1 = o2 = voff = 0
+    for l in range(L):
+        bi = set_index * L + l
+        blocks, _ = sample_blocks(graph, draw_seeds(graph, w.batch, w.seed, bi, w.seed_mode), w.fanouts, w.seed, bi)
+        outer, inner = blocks[H - 1], blocks[H - 2]
+        local = np.searchsorted(outer.dst, inner.indices)
+        assert np.array_equal(outer.dst[local], inner.indices)
+        p1.append(outer.indptr[1:] + o1)
+        i1.append(outer.indices)
+        p2.append(inner.indptr[1:] + o2)
+        i2.append(local + voff)
+        o1 += outer.E
+        o2 += inner.E
+        voff += outer.V
+    return tuple(np.concatenate(a).astype(np.int64) for a in (p1, i1, p2, i2))

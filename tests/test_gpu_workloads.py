@@ -19,8 +19,8 @@ import numpy as np
 import pytest
 
 import oracle as orc
-from bifeat_inputs import (WORKLOADS, BATCHES_PER_STEP, make_graph, launch_set, feature_rows,
-                           feature_chunk)
+from bifeat_inputs import (WORKLOADS, BATCHES_PER_STEP, make_graph, launch_set, two_round_set,
+                           feature_rows, feature_chunk)
 from helpers import assert_close, column_magnitude, scheme_of
 
 pytestmark = pytest.mark.gpu
@@ -184,6 +184,52 @@ def _run_iteration_checks(torch, w, q, codes, s_of, encode, bound=None):
         assert bool(((a - b).abs() <= 2e-5 * torch.maximum(a.abs(), A)).all()), f"{w.name} hop {h}: launch sets differ"
 
 
+def _run_two_round_checks(torch, w, q, codes, s_of, encode):
+    """bifeat_gather_mean_2hop over the two outermost blocks of the launch-set, as bench.py's
+    two-round leg calls it (the larger fan-out passed as the bound) and without the bound:
+    sampled seeds against the oracle, which regenerates and encodes exactly the rows involved."""
+    if len(w.fanouts) < 2:
+        return
+    g = make_graph(w)
+    L = BATCHES_PER_STEP[w.name]
+    p1, i1, p2, i2 = two_round_set(w, g, 0, L)
+    cu = lambda a: torch.from_numpy(a).cuda()
+    dp1, di1, dp2, di2 = cu(p1), cu(i1), cu(p2), cu(i2)
+    H = len(w.fanouts)
+    outs = {}
+    for hinted in (True, False):
+        q.set_option("mean_max_degree", max(w.fanouts[H - 1], w.fanouts[H - 2]) if hinted else 0)
+        outs[hinted] = q.gather_mean_2hop(codes, dp1, di1, dp2, di2)
+        q.set_option("mean_max_degree", 0)
+        assert q.poll_status()
+    rng = np.random.default_rng(1)
+    V2 = p2.shape[0] - 1
+    run = min(RUN, V2)
+    deg2 = np.diff(p2)
+    dst = np.unique(np.concatenate([np.arange(min(w.batch, V2)), np.arange(V2 - run, V2),
+                                    rng.choice(V2, size=min(N_DST_SAMPLE, V2), replace=False),
+                                    [int(deg2.argmax()), int(deg2.argmin())]]))
+    # compact copy of what those seeds touch: their lists, the outer lists they name, the rows
+    lists2 = [i2[p2[v]:p2[v + 1]] for v in dst]
+    us = np.unique(np.concatenate(lists2))
+    lists1 = [i1[p1[u]:p1[u + 1]] for u in us]
+    rows = np.unique(np.concatenate(lists1))
+    _, ocodes = _oracle_rows(w, rows, encode)
+    sp1 = np.concatenate([[0], np.cumsum([len(l) for l in lists1])]).astype(np.int64)
+    si1 = np.searchsorted(rows, np.concatenate(lists1)).astype(np.int64)
+    sp2 = np.concatenate([[0], np.cumsum([len(l) for l in lists2])]).astype(np.int64)
+    si2 = np.searchsorted(us, np.concatenate(lists2)).astype(np.int64)
+    s = s_of()
+    want = orc.gather_mean_2hop(s, ocodes, sp1, si1, sp2, si2)
+    ddst = cu(dst)
+    for hinted in (True, False):
+        assert_close(outs[hinted][ddst].cpu().numpy(), want, s,
+                     f"{w.name} two rounds {'with' if hinted else 'without'} the bound")
+    A = torch.from_numpy(column_magnitude(s).astype(np.float32)).cuda()[None, :]
+    a, b = outs[True], outs[False]
+    assert bool(((a - b).abs() <= 2e-5 * torch.maximum(a.abs(), A)).all()), f"{w.name}: the two kernels differ"
+
+
 def _uniform_case(torch, bf, names):
     ws = [WORKLOADS[n] for n in names]
     qs = [bf.Quantizer(scheme_of("uniform", w.bits), w.D) for w in ws]
@@ -195,6 +241,10 @@ def _uniform_case(torch, bf, names):
             s_of=lambda: orc.Scheme.uniform(mn, scale, w.bits),
             encode=lambda x: orc.pack(orc.uniform_encode(x, w.bits, mn, inv), w.bits),
             bound=(mn, mx))
+        _run_two_round_checks(
+            torch, w, q, c,
+            s_of=lambda: orc.Scheme.uniform(mn, scale, w.bits),
+            encode=lambda x: orc.pack(orc.uniform_encode(x, w.bits, mn, inv), w.bits))
     del codes
     torch.cuda.empty_cache()
 
@@ -241,6 +291,10 @@ def test_vq_96x256(torch, bf):
         torch, w, q, codes,
         s_of=lambda: orc.Scheme.vq(w.D, cb),
         encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb), 8))
+    _run_two_round_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.vq(w.D, cb),
+        encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb), 8))
     del codes
     torch.cuda.empty_cache()
 
@@ -260,6 +314,10 @@ def test_vq_16x2048_cosine_two_byte(torch, bf):
     q.params_set_codebooks(cb)
     (codes,), *_ = _stream_table(torch, w, [q], fit=False)
     _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.vq(w.D, cb),
+        encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb, metric=w.vq_metric), 16))
+    _run_two_round_checks(
         torch, w, q, codes,
         s_of=lambda: orc.Scheme.vq(w.D, cb),
         encode=lambda x: orc.pack(orc.vq_assign(x, w.vq_width, cb, metric=w.vq_metric), 16))
@@ -309,6 +367,10 @@ def test_log_2bit_clipped(torch, bf):
         torch, w, q, codes,
         s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
         encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
+    _run_two_round_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
+        encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
     del codes
     torch.cuda.empty_cache()
 
@@ -343,6 +405,10 @@ def test_log_1bit(torch, bf):
         torch, w, q, codes,
         s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
         encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
+    _run_two_round_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
+        encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
     del codes
     torch.cuda.empty_cache()
 
@@ -361,6 +427,10 @@ def test_log_4bit(torch, bf):
     assert np.array_equal(T, oT) and np.array_equal(V, oV)
     (codes,), *_ = _stream_table(torch, w, [q], fit=False)
     _run_iteration_checks(
+        torch, w, q, codes,
+        s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
+        encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
+    _run_two_round_checks(
         torch, w, q, codes,
         s_of=lambda: orc.Scheme.log(w.D, oV, w.bits),
         encode=lambda x: orc.pack(orc.log_encode(x, w.bits, oT), w.bits))
