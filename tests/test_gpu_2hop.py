@@ -207,3 +207,47 @@ def test_sampled_minibatch_blocks_and_the_chain(bf, torch, kind, bits, D, fanout
     assert_close(fused, want, s, "bounded kernel")
     A = np.abs(orc.gather_dequant(s, codes, np.arange(N))).max(axis=0).astype(np.float64)[None, :]
     assert (np.abs(fused.astype(np.float64) - chain) <= 2e-5 * np.maximum(np.abs(chain), A)).all()
+
+
+def test_random_shapes_bounds_and_row_strides(bf, torch):
+    # lane geometries of the bounded kernel: rows of 16 bytes to 1 KB (1 to 64 lanes per row, one
+    # to sixteen groups per seed), bounds from 1 to 64, seed counts that leave ragged tiles, both
+    # row strides; every element against the oracle
+    rng = np.random.default_rng(2024)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    for case in range(48):
+        bits = int(rng.choice([1, 2, 4, 8]))
+        D = 4 * int(rng.integers(1, {1: 512, 2: 256, 4: 256, 8: 96}[bits] + 1))
+        kind = "log" if bits <= 2 and rng.random() < 0.4 else "uniform"
+        m = int(rng.choice([1, 2, 3, 7, 15, 16, 17, 18, 31, 32, 33, 48, 64]))
+        align = int(rng.choice([16, 128]))
+        N = int(rng.integers(200, 1500))
+        spec = FeatureSpec(N, D, 100 + case)
+        x = feature_chunk(spec, 0, N)
+        if kind == "uniform":
+            _, (mn, mx, _, _), s, codes = oracle_uniform_table(spec, bits)
+            q = bf.Quantizer(scheme_of("uniform", bits), D, row_align=align)
+            q.params_set_uniform(mn, mx)
+        else:
+            e_min, e_max = orc.log_range(orc.log_fit(x))
+            T, Vt = orc.log_tables(e_min, e_max, bits)
+            codes = orc.pack(orc.log_encode(x, bits, T), bits)
+            s = orc.Scheme.log(D, Vt, bits)
+            q = bf.Quantizer(scheme_of("log", bits), D, row_align=align)
+            q.params_set_log(e_min, e_max)
+        table = np.zeros((N, q.row_bytes), np.uint8)           # the library's row stride, payload first
+        table[:, :codes.shape[1]] = codes
+        V1, V2 = int(rng.integers(1, 400)), int(rng.integers(1, 300))
+        d1 = rng.integers(0, m + 1, V1)
+        d2 = rng.integers(0, m + 1, V2)
+        if rng.random() < 0.5:
+            d2 = np.minimum(d2, rng.integers(1, 6))            # short seed lists: few groups per seed
+        indptr1 = np.concatenate([[0], np.cumsum(d1)]).astype(np.int64)
+        indices1 = rng.integers(0, N, int(indptr1[-1])).astype(np.int64)
+        indptr2 = np.concatenate([[0], np.cumsum(d2)]).astype(np.int64)
+        indices2 = rng.integers(0, V1, int(indptr2[-1])).astype(np.int64)
+        want = orc.gather_mean_2hop(s, codes, indptr1, indices1, indptr2, indices2)
+        q.set_option("mean_max_degree", m)
+        got = q.gather_mean_2hop(cu(table), cu(indptr1), cu(indices1), cu(indptr2), cu(indices2))
+        assert q.poll_status(wait=True), f"case {case}"
+        assert_close(got.cpu().numpy(), want, s, f"case {case}: {kind} {bits}-bit D={D} m={m} stride {q.row_bytes}")
