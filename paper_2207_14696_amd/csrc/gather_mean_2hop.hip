@@ -29,8 +29,12 @@ constexpr int kHopThreads = BF_HOP_THREADS;
 constexpr int kHopWaves = kHopThreads / 64;
 constexpr int kHopIds = 256;  // row ids a wave parks in LDS at a time: 4 per lane
 constexpr int kHopPiece = 16;  // rows per piece of a split list
+// build-time switches for A/B measurements (the defaults are what was measured best)
+#ifndef BF_HOP_SPLIT
+#define BF_HOP_SPLIT 1  // heavy destinations first
+#endif
 #ifndef BF_HOP_SPLIT16
-#define BF_HOP_SPLIT16 1
+#define BF_HOP_SPLIT16 1  // 4-bit lists of 18..32 rows as two narrow-field pieces
 #endif
 #ifndef BF_HOP_U
 #define BF_HOP_U 4
@@ -305,18 +309,16 @@ bool launch_hop_bits(bifeat_params *p, const HopCall &c, int thr, const float *m
     const int vpw = 64 / (g2 * lpr);
     const int64_t tiles = (c.V2 + vpw - 1) / vpw;
     const int64_t cap = p->opt_mean_blocks > 0 ? p->opt_mean_blocks : (1 << 16);
-#ifndef BF_HOP_SPLIT
-#define BF_HOP_SPLIT 1
-#endif
     // heavy-first order pays when a wave serves a single destination (measured: 7-15 % there,
     // a loss with two or more per wave); the threshold is the average seed-list length
     const int heavy = BF_HOP_SPLIT && vpw == 1 && avg2 >= 2 ? (int)(avg2 < thr ? avg2 : thr) : 0;
     const int64_t want = ((heavy ? 2 : 1) * tiles + kHopWaves - 1) / kHopWaves;
     const int blocks = (int)(want < cap ? (want < 1 ? 1 : want) : cap);
     const int D = (int)p->D, Dp = PAIR ? 2 * D : D;
-    const size_t shm = sizeof(uint32_t) * (size_t)kHopWaves * kHopIds + sizeof(uint2) * (size_t)kHopWaves * vpw * (SPLIT ? 2 * thr : thr);
+    const size_t shm = sizeof(uint32_t) * (size_t)kHopWaves * kHopIds +
+                       sizeof(uint2) * (size_t)kHopWaves * vpw * (SPLIT ? 2 * thr : thr);
 #define BF_HK(CWV)                                                                                 \
-    gather_mean_2hop_lean_kernel<BITS, CWV, WIDE, PAIR, SPLIT><<<blocks, kHopThreads, shm, c.s>>>(        \
+    gather_mean_2hop_lean_kernel<BITS, CWV, WIDE, PAIR, SPLIT><<<blocks, kHopThreads, shm, c.s>>>( \
         c.codes, (uint32_t)p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, Dp, mn, sc, \
         p->d_zero, c.out, lpr_log2, ilog2(g2), chunks, thr, heavy, c.status)
     if constexpr (PAIR) {
