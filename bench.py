@@ -455,15 +455,17 @@ def two_hop_leg(w, q, codes, g, L):
     q.set_option("mean_max_degree", max(w.fanouts[H - 1], w.fanouts[H - 2]))
     tf = timed(lambda: q.gather_mean_2hop(codes, dp1, di1, dp2, di2, hf))
     ok = q.poll_status(wait=True)
+    diff = float((hf - h2).abs().max().item())
     q.set_option("mean_max_degree", 0)
+    tu = timed(lambda: q.gather_mean_2hop(codes, dp1, di1, dp2, di2, hf), reps=5)
     fetches = int(np.diff(p1)[i2].sum())
     say(f"two rounds: chain {t1:.1f} + {t2:.1f} us, one call {tf:.1f} us")
     return {"dst": V2, "entries": int(i2.shape[0]), "outer_dst": V1, "outer_edges": int(i1.shape[0]),
             "chain_us": round(t1 + t2, 1), "chain_layer1_us": round(t1, 1), "chain_layer2_us": round(t2, 1),
-            "fused_us": round(tf, 1), "fused_row_fetches": fetches,
+            "fused_us": round(tf, 1), "fused_without_bound_us": round(tu, 1), "fused_row_fetches": fetches,
             "fused_fetched_GBps": round(fetches * q.row_bytes / tf / 1e3, 1),
             "intermediate_MB_avoided": round(V1 * w.D * 4 / 1e6, 1),
-            "max_abs_diff_to_chain": float((hf - h2).abs().max().item()), "status_ok": bool(ok)}
+            "max_abs_diff_to_chain": diff, "status_ok": bool(ok)}
 
 
 def scale_profile_leg(args, w, q, codes, table):

@@ -179,7 +179,9 @@ struct HopCall {
     hipStream_t s;
 };
 hipError_t launch_gather_mean_2hop(bifeat_params *p, const HopCall &c);
-bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, bool pair);
+// alone: no other kernel takes the destinations with a list longer than thr (they get NaN rows
+// and raise the status word); otherwise they are left unwritten for the general kernel
+bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, bool pair, bool alone);
 int hop_lean_max_list();
 
 // ---- order-preserving float <-> int keys for atomic min/max

@@ -146,103 +146,128 @@ static void launch_float(bifeat_params *p, const MeanCall &c, const float *pa, c
 
 // ------------------------------------------------ two rounds, general form
 // out[v] = mean over the seed list of v of the means over the outer lists of decoded rows, for
-// every kind of code and any list length: lane = 4 output columns of one destination; an outer
-// list is summed in fp32 runs of kRun rows combined in fp64, and the rounds' divisions and the
-// seed list's sum are fp64.
+// every kind of code and any list length.  A wave owns a destination; its lanes take 4 output
+// columns each (in rounds of 256 columns); an outer list is summed in fp32 runs of kRun rows
+// combined in fp64, and the rounds' divisions and the seed list's sum are fp64.
+// only_over > 0: the bounded kernel ran first with that bound and left out the destinations
+// that have a list longer than it; only those are done here (the wave looks at its seed
+// list's entries 64 at a time).
 template <int KIND, int BITS, bool VEC>
 __global__ __launch_bounds__(kThreads) void gather_mean_2hop_float_kernel(
     const uint8_t *__restrict__ codes, int64_t rb, const int64_t *__restrict__ indptr1,
     const int64_t *__restrict__ indices1, const int64_t *__restrict__ indptr2,
     const int64_t *__restrict__ indices2, int64_t V2, int D, const float *__restrict__ pa,
-    const float *__restrict__ pb, int w, int len, float *__restrict__ out) {
+    const float *__restrict__ pb, int w, int len, int only_over, float *__restrict__ out) {
     __shared__ float s_lut[KIND == MK_LOG ? (1 << (BITS & 15)) : 1];
     if constexpr (KIND == MK_LOG) {
         for (int i = threadIdx.x; i < (1 << BITS); i += kThreads) s_lut[i] = pa[i];
         __syncthreads();
     }
     const int G = (D + 3) / 4;
-    const uint32_t total = gridDim.x * kThreads;
-    const uint32_t per_pass = total / (uint32_t)G;
-    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
-    if (t >= per_pass * (uint32_t)G) return;
-    const int g = (int)(t % (uint32_t)G), col0 = 4 * g;
-    float mn[4], sc[4];
-    int part[4], dim[4];
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const bool ok = col0 + k < D;
-        if constexpr (KIND == MK_UNIFORM) {
-            mn[k] = ok ? pa[col0 + k] : 0.f;
-            sc[k] = ok ? pb[col0 + k] : 0.f;
-        }
-        if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
-            part[k] = (col0 + k) / w;
-            dim[k] = (col0 + k) % w;
-        }
-    }
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
     constexpr uint32_t mask = (1u << BITS) - 1u;
     constexpr int kRun = 32;
-    for (int64_t v = t / G; v < V2; v += per_pass) {
+    for (int64_t v = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); v < V2; v += n_waves) {
         const int64_t beg2 = indptr2[v], end2 = indptr2[v + 1];
-        double outer[4] = {0.0, 0.0, 0.0, 0.0};
-        for (int64_t e2 = beg2; e2 < end2; e2++) {
-            const int64_t u = indices2[e2];
-            const int64_t beg = indptr1[u], end = indptr1[u + 1];
-            if (end == beg) continue;  // a zero row
-            double total1[4] = {0.0, 0.0, 0.0, 0.0};
-            for (int64_t c0 = beg; c0 < end; c0 += kRun) {
-                const int64_t c1 = min(end, c0 + kRun);
-                float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-                for (int64_t e = c0; e < c1; e++) {
-                    const uint8_t *row = codes + indices1[e] * rb;
-                    if constexpr (KIND == MK_UNIFORM || KIND == MK_LOG) {
-                        const uint32_t bits = mean_code_bits4<BITS>(row, g);
-#pragma unroll
-                        for (int k = 0; k < 4; k++) {
-                            const uint32_t q = (bits >> (BITS * k)) & mask;
-                            if constexpr (KIND == MK_UNIFORM) acc[k] += fmaf((float)q, sc[k], mn[k]);
-                            else acc[k] += s_lut[q];
-                        }
-                    } else if constexpr (KIND == MK_VQ4) {
-                        const int q = mean_vq_index<BITS>(row, part[0]);
-                        const float4 c = *reinterpret_cast<const float4 *>(pa + ((int64_t)part[0] * len + q) * w + dim[0]);
-                        acc[0] += c.x; acc[1] += c.y; acc[2] += c.z; acc[3] += c.w;
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < 4; k++)
-                            if (col0 + k < D) acc[k] += pa[((int64_t)part[k] * len + mean_vq_index<BITS>(row, part[k])) * w + dim[k]];
-                    }
+        if (only_over > 0) {
+            bool over = end2 - beg2 > only_over;
+            for (int64_t j0 = beg2; !over && j0 < end2; j0 += 64) {
+                bool mine = false;
+                if (j0 + lane < end2) {
+                    const int64_t u = indices2[j0 + lane];
+                    mine = indptr1[u + 1] - indptr1[u] > only_over;
                 }
-#pragma unroll
-                for (int k = 0; k < 4; k++) total1[k] += (double)acc[k];
+                over = __ballot(mine) != 0;
             }
-            const double inv1 = 1.0 / (double)(end - beg);
-#pragma unroll
-            for (int k = 0; k < 4; k++) outer[k] += total1[k] * inv1;
+            if (!over) continue;
         }
-        const double inv2 = end2 > beg2 ? 1.0 / (double)(end2 - beg2) : 0.0;
-        float res[4];
+        for (int g = lane; g < G; g += 64) {
+            const int col0 = 4 * g;
+            float mn[4], sc[4];
+            int part[4], dim[4];
 #pragma unroll
-        for (int k = 0; k < 4; k++) res[k] = (float)(outer[k] * inv2);
-        float *dst = out + v * D + col0;
-        if constexpr (VEC) {
-            *reinterpret_cast<float4 *>(dst) = make_float4(res[0], res[1], res[2], res[3]);
-        } else {
+            for (int k = 0; k < 4; k++) {
+                const bool ok = col0 + k < D;
+                if constexpr (KIND == MK_UNIFORM) {
+                    mn[k] = ok ? pa[col0 + k] : 0.f;
+                    sc[k] = ok ? pb[col0 + k] : 0.f;
+                }
+                if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
+                    part[k] = (col0 + k) / w;
+                    dim[k] = (col0 + k) % w;
+                }
+            }
+            double outer[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int64_t e2 = beg2; e2 < end2; e2++) {
+                const int64_t u = indices2[e2];
+                const int64_t beg = indptr1[u], end = indptr1[u + 1];
+                if (end == beg) continue;  // a zero row
+                double total1[4] = {0.0, 0.0, 0.0, 0.0};
+                for (int64_t c0 = beg; c0 < end; c0 += kRun) {
+                    const int64_t c1 = min(end, c0 + kRun);
+                    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                    for (int64_t e = c0; e < c1; e++) {
+                        const uint8_t *row = codes + indices1[e] * rb;
+                        if constexpr (KIND == MK_UNIFORM || KIND == MK_LOG) {
+                            const uint32_t bits = mean_code_bits4<BITS>(row, g);
 #pragma unroll
-            for (int k = 0; k < 4; k++)
-                if (col0 + k < D) dst[k] = res[k];
+                            for (int k = 0; k < 4; k++) {
+                                const uint32_t q = (bits >> (BITS * k)) & mask;
+                                if constexpr (KIND == MK_UNIFORM) acc[k] += fmaf((float)q, sc[k], mn[k]);
+                                else acc[k] += s_lut[q];
+                            }
+                        } else if constexpr (KIND == MK_VQ4) {
+                            const int q = mean_vq_index<BITS>(row, part[0]);
+                            const float4 c = *reinterpret_cast<const float4 *>(pa + ((int64_t)part[0] * len + q) * w + dim[0]);
+                            acc[0] += c.x; acc[1] += c.y; acc[2] += c.z; acc[3] += c.w;
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < 4; k++)
+                                if (col0 + k < D) acc[k] += pa[((int64_t)part[k] * len + mean_vq_index<BITS>(row, part[k])) * w + dim[k]];
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; k++) total1[k] += (double)acc[k];
+                }
+                const double inv1 = 1.0 / (double)(end - beg);
+#pragma unroll
+                for (int k = 0; k < 4; k++) outer[k] += total1[k] * inv1;
+            }
+            const double inv2 = end2 > beg2 ? 1.0 / (double)(end2 - beg2) : 0.0;
+            float res[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) res[k] = (float)(outer[k] * inv2);
+            float *dst = out + v * D + col0;
+            if constexpr (VEC) {
+                *reinterpret_cast<float4 *>(dst) = make_float4(res[0], res[1], res[2], res[3]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+                    if (col0 + k < D) dst[k] = res[k];
+            }
         }
     }
 }
 
 template <int KIND>
-static void launch_2hop_float(bifeat_params *p, const HopCall &c, const float *pa, const float *pb, int vec) {
-    const int D = (int)p->D, G = (D + 3) / 4;
-    int blocks = blocks_for(c.V2 * G, 1 << 16);
-    if ((int64_t)blocks * kThreads < G) blocks = (G + kThreads - 1) / kThreads;
+static void launch_2hop_float(bifeat_params *p, const HopCall &c, const float *pa, const float *pb,
+                              int vec, int only_over) {
+    const int D = (int)p->D;
+    const int blocks = blocks_for(c.V2 * 64, 1 << 16);  // a wave per destination
     const int w = p->scheme.vq_width, len = p->scheme.vq_length;
-#define BF_HF(B)                                                                                      do {                                                                                                  if (vec)                                                                                              gather_mean_2hop_float_kernel<KIND, B, true><<<blocks, kThreads, 0, c.s>>>(                           c.codes, p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, pa, pb, w, len, c.out);         else                                                                                                  gather_mean_2hop_float_kernel<KIND, B, false><<<blocks, kThreads, 0, c.s>>>(                          c.codes, p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, pa, pb, w, len, c.out);     } while (0)
+#define BF_HF(B)                                                                                   \
+    do {                                                                                           \
+        if (vec)                                                                                   \
+            gather_mean_2hop_float_kernel<KIND, B, true><<<blocks, kThreads, 0, c.s>>>(            \
+                c.codes, p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, pa, pb, w,  \
+                len, only_over, c.out);                                                            \
+        else                                                                                       \
+            gather_mean_2hop_float_kernel<KIND, B, false><<<blocks, kThreads, 0, c.s>>>(           \
+                c.codes, p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, pa, pb, w,  \
+                len, only_over, c.out);                                                            \
+    } while (0)
     if constexpr (KIND == MK_VQ4 || KIND == MK_VQ) {
         if (p->cbytes == 2) BF_HF(16);
         else BF_HF(8);
@@ -263,22 +288,28 @@ hipError_t launch_gather_mean_2hop(bifeat_params *p, const HopCall &c) {
     const int kind = p->scheme.kind, bits = p->scheme.bits;
     const bool affine = kind == BIFEAT_SQ_UNIFORM || (kind == BIFEAT_SQ_LOG && bits == 1);
     const bool pair = kind == BIFEAT_SQ_LOG && bits == 2;
-    // The register-accumulator form relies on the caller's bound on the list lengths (lists
-    // beyond it get NaN rows and raise the status word); it keeps row ids and the outer block's
-    // list offsets in 32 bits.
+    // The register-accumulator form takes lists of at most `thr` entries: the caller's bound
+    // (then it runs alone: lists beyond it get NaN rows and raise the status word), or, without
+    // one, the longest it can take - the destinations with a longer list are then left to the
+    // general kernel, which looks for them.  It keeps row ids and the outer block's list
+    // offsets in 32 bits.
     const bool promised = c.max_degree > 0 && c.max_degree <= hop_lean_max_list();
-    if ((affine || pair) && promised && vec && !p->opt_mean_generic && p->opt_mean_lean &&
+    const int thr = promised ? c.max_degree : hop_lean_max_list();
+    int only_over = 0;
+    if ((affine || pair) && vec && !p->opt_mean_generic && p->opt_mean_lean && c.max_degree <= hop_lean_max_list() &&
         c.N <= (int64_t)UINT32_MAX && c.E1 <= (int64_t)UINT32_MAX &&
-        launch_gather_mean_2hop_lean(p, c, c.max_degree, pair))
-        return hipGetLastError();
+        launch_gather_mean_2hop_lean(p, c, thr, pair, promised)) {
+        if (promised) return hipGetLastError();
+        only_over = thr;
+    }
     if (kind == BIFEAT_SQ_UNIFORM) {
-        launch_2hop_float<MK_UNIFORM>(p, c, p->d_min, p->d_scale, vec);
+        launch_2hop_float<MK_UNIFORM>(p, c, p->d_min, p->d_scale, vec, only_over);
     } else if (kind == BIFEAT_SQ_LOG) {
-        launch_2hop_float<MK_LOG>(p, c, p->d_V, nullptr, vec);
+        launch_2hop_float<MK_LOG>(p, c, p->d_V, nullptr, vec, only_over);
     } else {
         const int w = p->scheme.vq_width;
-        if (w % 4 == 0 && vec) launch_2hop_float<MK_VQ4>(p, c, p->d_cb, nullptr, vec);
-        else launch_2hop_float<MK_VQ>(p, c, p->d_cb, nullptr, vec);
+        if (w % 4 == 0 && vec) launch_2hop_float<MK_VQ4>(p, c, p->d_cb, nullptr, vec, only_over);
+        else launch_2hop_float<MK_VQ>(p, c, p->d_cb, nullptr, vec, only_over);
     }
     return hipGetLastError();
 }

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kHopThreads, (BITS == 4 && CW == 4 && WIDE) ? 3 : B
     const int64_t *__restrict__ indices1, const int64_t *__restrict__ indptr2,
     const int64_t *__restrict__ indices2, int64_t V2, int D, int Dp, const float *__restrict__ mn,
     const float *__restrict__ sc, const uint8_t *__restrict__ zero_row, float *__restrict__ out,
-    int lpr_log2, int g2_log2, int chunks, int thr, int heavy, int32_t *__restrict__ status) {
+    int lpr_log2, int g2_log2, int chunks, int thr, int heavy, int alone, int32_t *__restrict__ status) {
     using W = LeanSwar<BITS, WIDE>;
     constexpr int R = CW * W::kN;    // field registers per lane
     constexpr int CPW = 32 / BITS;   // codes per word
@@ -228,8 +228,8 @@ __global__ __launch_bounds__(kHopThreads, (BITS == 4 && CW == 4 && WIDE) ? 3 : B
             nonempty += __shfl_xor(nonempty, mask);
         }
         const bool badv = (__ballot(bad) & vmask) != 0;
-        if (badv && valid && lv == 0) raise_status(status, kStatusListTooLong);
-        if (valid && q == 0 && chunk_ok) {
+        if (badv && alone && valid && lv == 0) raise_status(status, kStatusListTooLong);
+        if (valid && q == 0 && chunk_ok && (alone || !badv)) {
             const float inv2 = n2 > 0 ? 1.0f / (float)n2 : 0.0f;
             const float frac = nonempty == n2 ? 1.0f : (float)nonempty * inv2;
             const bool some = n2 > 0;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kHopThreads, (BITS == 4 && CW == 4 && WIDE) ? 3 : B
 }
 
 template <int BITS, bool WIDE, bool PAIR, bool SPLIT = false>
-bool launch_hop_bits(bifeat_params *p, const HopCall &c, int thr, const float *mn, const float *sc) {
+bool launch_hop_bits(bifeat_params *p, const HopCall &c, int thr, bool alone, const float *mn, const float *sc) {
     using W = LeanSwar<BITS, WIDE>;
     static_assert(!SPLIT || kHopPiece <= W::kCap, "a field holds a piece");
     if (thr > (SPLIT ? 2 * kHopPiece : W::kCap)) return false;
@@ -320,7 +320,7 @@ bool launch_hop_bits(bifeat_params *p, const HopCall &c, int thr, const float *m
 #define BF_HK(CWV)                                                                                 \
     gather_mean_2hop_lean_kernel<BITS, CWV, WIDE, PAIR, SPLIT><<<blocks, kHopThreads, shm, c.s>>>( \
         c.codes, (uint32_t)p->rb, c.indptr1, c.indices1, c.indptr2, c.indices2, c.V2, D, Dp, mn, sc, \
-        p->d_zero, c.out, lpr_log2, ilog2(g2), chunks, thr, heavy, c.status)
+        p->d_zero, c.out, lpr_log2, ilog2(g2), chunks, thr, heavy, alone ? 1 : 0, c.status)
     if constexpr (PAIR) {
         BF_HK(1);
     } else if constexpr (BITS == 1) {
@@ -347,22 +347,22 @@ int hop_lean_max_list() { return 64; }
 // The register-accumulator form for affine codes (uniform, 1-bit logarithmic; pair = 2-bit
 // logarithmic codes as two bit planes) under the caller's bound `thr` on every list length;
 // returns false (nothing launched) when the table's shape is outside what it handles.
-bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, bool pair) {
+bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, bool pair, bool alone) {
     const float *mn = p->d_min, *sc = p->d_scale;
     if (pair) {
-        return thr > LeanSwar<1, false>::kCap ? launch_hop_bits<1, true, true>(p, c, thr, mn, sc)
-                                              : launch_hop_bits<1, false, true>(p, c, thr, mn, sc);
+        return thr > LeanSwar<1, false>::kCap ? launch_hop_bits<1, true, true>(p, c, thr, alone, mn, sc)
+                                              : launch_hop_bits<1, false, true>(p, c, thr, alone, mn, sc);
     }
     switch (p->scheme.bits) {
         case 1:
-            return thr > LeanSwar<1, false>::kCap ? launch_hop_bits<1, true, false>(p, c, thr, mn, sc)
-                                                  : launch_hop_bits<1, false, false>(p, c, thr, mn, sc);
-        case 2: return launch_hop_bits<2, false, false>(p, c, thr, mn, sc);
+            return thr > LeanSwar<1, false>::kCap ? launch_hop_bits<1, true, false>(p, c, thr, alone, mn, sc)
+                                                  : launch_hop_bits<1, false, false>(p, c, thr, alone, mn, sc);
+        case 2: return launch_hop_bits<2, false, false>(p, c, thr, alone, mn, sc);
         case 4:
-            if (thr <= LeanSwar<4, false>::kCap) return launch_hop_bits<4, false, false>(p, c, thr, mn, sc);
-            if (thr <= 2 * kHopPiece && BF_HOP_SPLIT16) return launch_hop_bits<4, false, false, true>(p, c, thr, mn, sc);
-            return launch_hop_bits<4, true, false>(p, c, thr, mn, sc);
-        default: return launch_hop_bits<8, false, false>(p, c, thr, mn, sc);
+            if (thr <= LeanSwar<4, false>::kCap) return launch_hop_bits<4, false, false>(p, c, thr, alone, mn, sc);
+            if (thr <= 2 * kHopPiece && BF_HOP_SPLIT16) return launch_hop_bits<4, false, false, true>(p, c, thr, alone, mn, sc);
+            return launch_hop_bits<4, true, false>(p, c, thr, alone, mn, sc);
+        default: return launch_hop_bits<8, false, false>(p, c, thr, alone, mn, sc);
     }
 }
 
