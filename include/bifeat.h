@@ -281,9 +281,10 @@ int bifeat_gather_sum_i32(bifeat_params *p, const uint8_t *codes, int64_t N, con
  * keeps the running means in registers; a list that breaks the promise gives a
  * NaN row and raises the status word as described below.  Without the promise
  * that kernel takes the seeds all of whose lists have at most 64 entries and a
- * general kernel (any list length) the others; the other codes take the
- * general kernel throughout (vector codes: slower than the two-call chain,
- * whose kernels keep the codebooks in on-chip memory).
+ * general kernel (any list length) the others.  Vector codes of power-of-two
+ * width take a kernel with the codebooks in on-chip memory (any list length;
+ * uses the handle's workspace like bifeat_gather_mean, sized by E1); the
+ * remaining codes take the general kernel throughout.
  * Option "validate" checks both blocks first.  V2 = 0 is a no-op. */
 int bifeat_gather_mean_2hop(bifeat_params *p, const uint8_t *codes, int64_t N,
                             const int64_t *indptr1, const int64_t *indices1, int64_t V1, int64_t E1,

@@ -183,6 +183,7 @@ hipError_t launch_gather_mean_2hop(bifeat_params *p, const HopCall &c);
 // and raise the status word); otherwise they are left unwritten for the general kernel
 bool launch_gather_mean_2hop_lean(bifeat_params *p, const HopCall &c, int thr, bool pair, bool alone);
 int hop_lean_max_list();
+bool launch_gather_mean_2hop_vq_sliced(bifeat_params *p, const HopCall &c);
 
 // ---- order-preserving float <-> int keys for atomic min/max
 __host__ __device__ inline int32_t float_key(float f) {

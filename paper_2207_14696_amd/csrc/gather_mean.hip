@@ -307,6 +307,8 @@ hipError_t launch_gather_mean_2hop(bifeat_params *p, const HopCall &c) {
     } else if (kind == BIFEAT_SQ_LOG) {
         launch_2hop_float<MK_LOG>(p, c, p->d_V, nullptr, vec, only_over);
     } else {
+        // codebooks in LDS where the sliced kernels' shapes allow (and the workspace can be had)
+        if (vec && p->opt_vq_sliced && launch_gather_mean_2hop_vq_sliced(p, c)) return hipGetLastError();
         const int w = p->scheme.vq_width;
         if (w % 4 == 0 && vec) launch_2hop_float<MK_VQ4>(p, c, p->d_cb, nullptr, vec, only_over);
         else launch_2hop_float<MK_VQ>(p, c, p->d_cb, nullptr, vec, only_over);

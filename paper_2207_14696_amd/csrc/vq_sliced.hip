@@ -244,7 +244,9 @@ struct MeanLane {
         base = reinterpret_cast<const uint8_t *>(planes);
         // the part's index: cbytes bytes at byte (part * cbytes) of the packed row
         const int boff = (slice * SP + pl) * cbytes;
-        plane_off = (uint32_t)((boff >> 2) * MS), shift = 8 * (boff & 3);
+        // (lanes past the table's last part read plane 0: they fetch codes like the others and
+        // drop them, and a plane of their own part number need not exist)
+        plane_off = active ? (uint32_t)((boff >> 2) * MS) : 0u, shift = 8 * (boff & 3);
         cmask = cbytes == 1 ? 0xFFu : 0xFFFFu;
         cs_log2 = __ffs(SP * w * 4) - 1;  // log2 of the bytes between entry rows in LDS
         lds = reinterpret_cast<const uint8_t *>(s_cb);
@@ -462,6 +464,97 @@ __global__ __launch_bounds__(kVqThreads) void gather_mean_vq_long_kernel(
     }
 }
 
+// Two rounds of the mean (Appendix A.1 applied twice, nothing in between) for vector codes:
+// planes hold the transposed codes of the outer block's list entries, in list order, so the
+// outer list of seed-list entry u is the run [indptr1[u], indptr1[u+1]) of every plane.  A lane
+// group owns a seed's slice columns: per entry it sums the selected codebook entries of that
+// run (fp32 runs of kRun combined in fp64), divides by the run's length, and adds up in fp64.
+// The chain seed list -> outer list's bounds -> codes is taken off the critical path: the
+// group's lanes fetch the bounds of as many entries as the group has lanes at once and hand
+// them round by lane exchange, and an entry's first kPre*4 codes are requested while the
+// entry before it is summed.
+template <int CPL>
+__global__ __launch_bounds__(kVqThreads) void gather_mean_vq_2hop_kernel(
+    const uint32_t *__restrict__ planes, int64_t MS, const int64_t *__restrict__ indptr1,
+    const int64_t *__restrict__ indptr2, const int64_t *__restrict__ indices2, int64_t V2, int D,
+    int P, int w, int len, int SP, int NS, int lps_log2, int cbytes, const float *__restrict__ cb,
+    float *__restrict__ out) {
+    extern __shared__ float s_cb[];
+    const MeanLane<CPL> L(planes, MS, s_cb, P, w, len, SP, NS, lps_log2, cbytes);
+    load_slice(s_cb, cb, L.slice, SP, P, len, w);
+    const int64_t tiles = (V2 + (1 << L.rpw_log2) - 1) >> L.rpw_log2;
+    const int64_t stride = (int64_t)L.ny * L.nw;
+    const int lps = 1 << lps_log2;
+    const int first_lane = L.lane & ~(lps - 1);  // lane 0 of this lane's group
+    for (int64_t tile = (int64_t)L.by * L.nw + L.wave; tile < tiles; tile += stride) {
+        const int64_t v = (tile << L.rpw_log2) + L.r_in;
+        if (v >= V2) continue;  // whole groups leave together
+        const int64_t beg2 = indptr2[v], end2 = indptr2[v + 1];
+        double outer[CPL];
+#pragma unroll
+        for (int k = 0; k < CPL; k++) outer[k] = 0.0;
+        for (int64_t e0 = beg2; e0 < end2; e0 += lps) {
+            // bounds of the next `lps` entries, one per lane of the group
+            uint32_t my_beg = 0u, my_n = 0u;
+            if (e0 + L.g < end2) {
+                const int64_t u = indices2[e0 + L.g];
+                const int64_t b1 = indptr1[u];
+                my_beg = (uint32_t)b1;
+                my_n = (uint32_t)(indptr1[u + 1] - b1);
+            }
+            const int cnt = (int)min((int64_t)lps, end2 - e0);
+            uint32_t beg = __shfl(my_beg, first_lane), n = __shfl(my_n, first_lane);
+            Words4 cur[kPre];
+#pragma unroll
+            for (int k = 0; k < kPre; k++) cur[k] = L.words(beg + 4 * k);
+            for (int j = 0; j < cnt; j++) {
+                const int jn = min(j + 1, cnt - 1);
+                const uint32_t beg1 = __shfl(my_beg, first_lane + jn), n1 = __shfl(my_n, first_lane + jn);
+                Words4 nxt[kPre];
+#pragma unroll
+                for (int k = 0; k < kPre; k++) nxt[k] = L.words(beg1 + 4 * k);
+                if (L.active && n > 0) {
+                    const double inv1 = 1.0 / (double)n;
+                    float acc[CPL];
+#pragma unroll
+                    for (int k = 0; k < CPL; k++) acc[k] = 0.0f;
+                    if (n <= (uint32_t)kRun) {
+#pragma unroll
+                        for (int k = 0; k < kPre; k++)
+                            if ((uint32_t)(4 * k) < n) L.add4(cur[k], n - 4 * k, acc);
+                        if (n > 4 * kPre) L.run(beg + 4 * kPre, beg + n, acc);
+#pragma unroll
+                        for (int k = 0; k < CPL; k++) outer[k] += (double)acc[k] * inv1;
+                    } else {
+                        double total[CPL];
+#pragma unroll
+                        for (int k = 0; k < CPL; k++) total[k] = 0.0;
+                        for (uint32_t c0 = beg; c0 < beg + n; c0 += kRun) {
+#pragma unroll
+                            for (int k = 0; k < CPL; k++) acc[k] = 0.0f;
+                            L.run(c0, min(beg + n, c0 + (uint32_t)kRun), acc);
+#pragma unroll
+                            for (int k = 0; k < CPL; k++) total[k] += (double)acc[k];
+                        }
+#pragma unroll
+                        for (int k = 0; k < CPL; k++) outer[k] += total[k] * inv1;
+                    }
+                }
+                beg = beg1, n = n1;
+#pragma unroll
+                for (int k = 0; k < kPre; k++) cur[k] = nxt[k];
+            }
+        }
+        if (L.active) {
+            const double inv2 = end2 > beg2 ? 1.0 / (double)(end2 - beg2) : 0.0;
+            float res[CPL];
+#pragma unroll
+            for (int k = 0; k < CPL; k++) res[k] = (float)(outer[k] * inv2);
+            L.store(out, v, D, res);
+        }
+    }
+}
+
 // The slice plus its zero row can exceed the 64 KB a workgroup gets by default.
 template <typename Kern>
 bool allow_lds(Kern kern, size_t bytes) {
@@ -582,6 +675,33 @@ bool launch_gather_mean_vq_sliced(bifeat_params *p, const MeanCall &c) {
         if (with_long) gather_mean_vq_long_kernel<4><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQA);
     }
 #undef BF_VQA
+    return true;
+}
+
+// Two rounds in one call for vector codes with the codebooks in LDS: the pre-pass transposes
+// the codes of the outer block's list entries, then one kernel walks seed lists over runs of
+// the planes.  Any list length.  False (nothing launched) outside the sliced kernels' shapes or
+// when the workspace cannot be had.
+bool launch_gather_mean_2hop_vq_sliced(bifeat_params *p, const HopCall &c) {
+    const VqGeom g = vq_geometry(p);
+    if (!g.ok || (uintptr_t)c.out % 16 || p->payload / 16 > 64) return false;
+    const int64_t MS = plane_entries(c.E1);
+    if (p->payload * MS >= ((int64_t)1 << 32)) return false;  // 32-bit plane offsets
+    const int w = p->scheme.vq_width, len = p->scheme.vq_length;
+    const int cpl = w % 8 == 0 ? 8 : 4;
+    if (cpl == 8 ? !allow_lds(gather_mean_vq_2hop_kernel<8>, g.lds) : !allow_lds(gather_mean_vq_2hop_kernel<4>, g.lds))
+        return false;
+    if (!ensure_scratch(p, (size_t)p->payload * MS, c.s)) return false;
+    if (c.E1 > 0) launch_planes(p, c.codes, c.indices1, false, c.E1, (uint32_t *)p->d_scratch, c.s);
+    const int lps = g.LPS * 4 / cpl, rpw = 64 / lps;
+    const int64_t tiles = (c.V2 + rpw - 1) / rpw;
+    const int grid = sliced_grid(p, tiles * g.NS, 1024, g.NS);
+#define BF_VQH                                                                                   \
+    (const uint32_t *)p->d_scratch, MS, c.indptr1, c.indptr2, c.indices2, c.V2, (int)p->D, p->P, w, \
+        len, g.SP, g.NS, ilog2(lps), p->cbytes, p->d_cb, c.out
+    if (cpl == 8) gather_mean_vq_2hop_kernel<8><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQH);
+    else gather_mean_vq_2hop_kernel<4><<<grid, kVqThreads, g.lds, c.s>>>(BF_VQH);
+#undef BF_VQH
     return true;
 }
 

@@ -251,3 +251,30 @@ def test_random_shapes_bounds_and_row_strides(bf, torch):
         got = q.gather_mean_2hop(cu(table), cu(indptr1), cu(indices1), cu(indptr2), cu(indices2))
         assert q.poll_status(wait=True), f"case {case}"
         assert_close(got.cpu().numpy(), want, s, f"case {case}: {kind} {bits}-bit D={D} m={m} stride {q.row_bytes}")
+
+
+@pytest.mark.parametrize("D,w,length", [(64, 8, 16), (96, 4, 32), (128, 16, 64), (768, 8, 256), (40, 8, 8),
+                                        (192, 4, 16)])   # 48 parts in slices of 32: a slice with idle lanes
+def test_vector_codes_with_the_codebooks_on_chip(bf, torch, D, w, length):
+    # power-of-two widths take the kernel that keeps codebook slices in LDS: short and long lists,
+    # empty ones, repeats; with and without a bound (it needs none)
+    s, codes, q = _table(bf, "vq", 8, D, N=3000, w=w, length=length)
+    rng = np.random.default_rng(D + w)
+    V1, V2 = 500, 131
+    indptr1, indices1, indptr2, indices2 = _blocks(codes.shape[0], V1, V2, 12, 9, rng)
+    d1 = np.diff(indptr1)
+    d1[7] = 150                                             # one long outer list
+    indptr1 = np.concatenate([[0], np.cumsum(d1)]).astype(np.int64)
+    indices1 = rng.integers(0, codes.shape[0], int(indptr1[-1])).astype(np.int64)
+    indices2[indptr2[1] + 3] = 7
+    want = orc.gather_mean_2hop(s, codes, indptr1, indices1, indptr2, indices2)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    args = (cu(codes), cu(indptr1), cu(indices1), cu(indptr2), cu(indices2))
+    got = q.gather_mean_2hop(*args).cpu().numpy()
+    assert_close(got, want, s, f"vq D={D} w={w}")
+    assert not got[0].any()
+    # the one-round call over the outer block shares the slice geometry
+    assert_close(q.gather_mean(args[0], args[1], args[2]).cpu().numpy(),
+                 orc.gather_mean(s, codes, indptr1, indices1), s, f"vq D={D} w={w} one round")
+    q.set_option("vq_sliced", 0)                            # the same from L2 (general kernel)
+    assert_close(q.gather_mean_2hop(*args).cpu().numpy(), want, s, f"vq D={D} w={w} from L2")
