@@ -303,7 +303,7 @@ int bifeat_gather_mean_2hop(bifeat_params *p, const uint8_t *codes, int64_t N,
 int bifeat_poll_status(bifeat_params *p, void *stream, int32_t wait);
 
 /* Sizes the handle's workspace for gather calls of up to max_requests rows
- * (gather_dequant: M; gather_mean / gather_sum: E), so that no later call
+ * (gather_dequant: M; gather_mean / gather_sum: E; gather_mean_2hop: E1), so that no later call
  * allocates.  Only vector codes use a workspace; for the other kinds this is a
  * no-op.  Not during a stream capture (BIFEAT_EHIP). */
 int bifeat_reserve(bifeat_params *p, int64_t max_requests, void *stream);
