@@ -278,3 +278,44 @@ def test_vector_codes_with_the_codebooks_on_chip(bf, torch, D, w, length):
                  orc.gather_mean(s, codes, indptr1, indices1), s, f"vq D={D} w={w} one round")
     q.set_option("vq_sliced", 0)                            # the same from L2 (general kernel)
     assert_close(q.gather_mean_2hop(*args).cpu().numpy(), want, s, f"vq D={D} w={w} from L2")
+
+
+def test_replays_from_a_captured_graph(bf, torch):
+    # scalar codes: the call only enqueues kernels; vector codes: the workspace is sized before
+    # the capture, and a capture that would need a larger one runs the kernel that needs none
+    rng = np.random.default_rng(77)
+    cu = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    for kind, bits, D, w, length, hint in [("uniform", 4, 128, 0, 0, 12), ("uniform", 2, 64, 0, 0, 0),
+                                           ("vq", 8, 64, 8, 16, 0)]:
+        s, codes, q = _table(bf, kind, bits, D, N=3000, w=w, length=length)
+        small = _blocks(codes.shape[0], 300, 90, 12, 9, rng)
+        big = _blocks(codes.shape[0], 2500, 700, 12, 9, rng)
+        dcodes = cu(codes)
+        d_small, d_big = [cu(a) for a in small], [cu(a) for a in big]
+        out_small = torch.empty((90, D), device="cuda")
+        out_big = torch.empty((700, D), device="cuda")
+        q.set_option("mean_max_degree", hint)
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            q.gather_mean_2hop(dcodes, *d_small, out=out_small)       # sizes the workspace (vector codes)
+            stream.synchronize()
+            g_small, g_big = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_small, stream=stream):
+                q.gather_mean_2hop(dcodes, *d_small, out=out_small)
+            with torch.cuda.graph(g_big, stream=stream):
+                q.gather_mean_2hop(dcodes, *d_big, out=out_big)
+        want_small = orc.gather_mean_2hop(s, codes, *small)
+        want_big = orc.gather_mean_2hop(s, codes, *big)
+        for rep in range(3):
+            out_small.fill_(float("nan"))
+            out_big.fill_(float("nan"))
+            g_small.replay()
+            g_big.replay()
+            torch.cuda.synchronize()
+            assert_close(out_small.cpu().numpy(), want_small, s, f"{kind}: captured small, replay {rep}")
+            assert_close(out_big.cpu().numpy(), want_big, s, f"{kind}: captured big, replay {rep}")
+            if rep == 0:   # eager work (and workspace growth) between replays
+                got = q.gather_mean_2hop(dcodes, *d_big)
+                assert_close(got.cpu().numpy(), want_big, s, f"{kind}: eager between replays")
+        q.set_option("mean_max_degree", 0)
+        assert q.poll_status()
